@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of libtng on one MI355X.
+
+Workload (the one the headline metric is quoted on): the encode/decode microbenchmark --
+M = 8 worker gradients of d = 2^27 fp32, g_m = g~ + N(0, 0.1) |g~|, g~ ~ N(0, 1), seed 1.
+One step = tng_normalize_encode + tng_decode_aggregate over all 8 gradients (iteration number =
+step number), inputs resident in HBM.  The headline value is ternary codes with subtraction
+normalisation; the other three variants (4-bit, quotient) are timed the same way and reported
+under "variants".  Per-kernel durations come from HIP events recorded by the library on its
+stream inside the timed region; the oracle is timed on the host on a bounded sample.
+
+Prints one JSON line on stdout (progress goes to stderr).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """hipEvent_t handles created through the HIP runtime (the library records them itself)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.ev = []
+        for _ in range(n):
+            e = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(e))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            self.ev.append(e.value)
+
+    def elapsed_ms(self, a, b):
+        out = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(out), ctypes.c_void_p(self.ev[a]), ctypes.c_void_p(self.ev[b]))
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(out.value)
+
+    def destroy(self):
+        for e in self.ev:
+            self.hip.hipEventDestroy(ctypes.c_void_p(e))
+        self.ev = []
+
+
+def time_codec(torch, B, g, gref, bits, norm, steps, warmup, seed):
+    """Times `steps` encode+decode passes; returns whole-loop ms/step and per-kernel mean ms."""
+    M, d = g.shape
+    ctx = B.Context(d=d, M=M, bits=bits, norm=norm, seed=seed, device=g.device)
+    codes = torch.empty((M, ctx.words), dtype=torch.int32, device=g.device)
+    scales = torch.empty(M, device=g.device)
+    vbar = torch.empty(d, device=g.device)
+    for it in range(warmup):
+        ctx.normalize_encode(it, g, gref, codes, scales)
+        ctx.decode_aggregate(codes, scales, gref, vbar)
+    ev = HipEvents(5 * steps)
+    ctx.set_profile_events(ev.ev, steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for it in range(steps):
+        ctx.normalize_encode(warmup + it, g, gref, codes, scales)
+        ctx.decode_aggregate(codes, scales, gref, vbar)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    k_scale = sum(ev.elapsed_ms(5 * i + 0, 5 * i + 1) for i in range(steps)) / steps
+    k_quant = sum(ev.elapsed_ms(5 * i + 1, 5 * i + 2) for i in range(steps)) / steps
+    k_dec = sum(ev.elapsed_ms(5 * i + 3, 5 * i + 4) for i in range(steps)) / steps
+    ctx.set_profile_events(None, 0)
+    ev.destroy()
+    words = ctx.words
+    ctx.close()
+    del codes, scales, vbar
+    ms = (t1 - t0) * 1e3 / steps
+    # algorithmic bytes per launch: each operand once per kernel
+    b_scale = 4 * M * d + 4 * d
+    b_quant = 4 * M * d + 4 * d + 4 * M * words
+    b_dec = 4 * M * words + 4 * d + 4 * d
+    return {
+        "ms_per_step": ms,
+        "fp32_in_GBps": 4.0 * M * d / (ms * 1e-3) / 1e9,
+        "kernels": {
+            "absmax": {"ms": k_scale, "bytes": b_scale, "GBps": b_scale / (k_scale * 1e-3) / 1e9},
+            "quantize_pack": {"ms": k_quant, "bytes": b_quant, "GBps": b_quant / (k_quant * 1e-3) / 1e9},
+            "decode": {"ms": k_dec, "bytes": b_dec, "GBps": b_dec / (k_dec * 1e-3) / 1e9},
+        },
+        "two_pass_bytes": b_scale + b_quant + b_dec,
+        "two_pass_GBps": (b_scale + b_quant + b_dec) / (ms * 1e-3) / 1e9,
+    }
+
+
+def cpu_baseline(g, gref, seed, sample_d):
+    """The oracle as it stands, on a bounded sample (first sample_d coordinates of every worker)."""
+    import numpy as np
+
+    from oracle import tng_oracle as O
+
+    M = g.shape[0]
+    gh = g[:, :sample_d].cpu().numpy()
+    rh = gref[:sample_d].cpu().numpy()
+    cfg = O.Config(d=sample_d, M=M, bits=2, norm=O.NORM_SUB, seed=seed)
+    t0 = time.perf_counter()
+    codes, scales = O.normalize_encode(cfg, 0, gh, rh)
+    vbar = O.decode_aggregate(cfg, codes, scales, rh, sample_d)
+    t1 = time.perf_counter()
+    assert np.isfinite(vbar).all()
+    return {
+        "value": 4.0 * M * sample_d / (t1 - t0) / 1e9,
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"numpy oracle, one encode+decode pass (ternary, subtraction) over M={M} x the first "
+                  f"2^{sample_d.bit_length() - 1} of 2^{g.shape[1].bit_length() - 1} coordinates, "
+                  f"{t1 - t0:.1f} s, single thread; host has {os.cpu_count()} logical CPUs",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--log2d", type=int, default=27, help="log2 of the gradient dimension (27 = the headline workload)")
+    ap.add_argument("--workers", type=int, default=8)
+    ap.add_argument("--cpu-log2d", type=int, default=25, help="log2 of the oracle's sample size per worker")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-variants", action="store_true", help="time only the headline variant")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (the workers are simulated on it); --gpus above 1 is not supported")
+        sys.exit(2)
+
+    import torch
+
+    from paper_1901_08227_amd import binding as B
+    from paper_1901_08227_amd import synth
+
+    B.lib()  # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    M, d, seed = args.workers, 1 << args.log2d, 1
+    log(f"generating g[{M}][2^{args.log2d}] and the reference on {torch.cuda.get_device_name(0)}")
+    g, gref = synth.codec_inputs(M, d, seed, rel_variance=0.1, device=dev)
+    torch.cuda.synchronize()
+
+    log("timing ternary / subtraction (headline)")
+    head = time_codec(torch, B, g, gref, 2, B.NORM_SUB, args.steps, args.warmup, seed)
+    variants = []
+    if not args.no_variants:
+        for bits, norm, name in [(4, B.NORM_SUB, "4bit/sub"), (2, B.NORM_QUOT, "ternary/quot"), (4, B.NORM_QUOT, "4bit/quot")]:
+            log(f"timing {name}")
+            r = time_codec(torch, B, g, gref, bits, norm, args.steps, args.warmup, seed)
+            variants.append({"variant": name, "ms_per_step": round(r["ms_per_step"], 4),
+                             "fp32_in_GBps": round(r["fp32_in_GBps"], 1),
+                             "two_pass_GBps": round(r["two_pass_GBps"], 1),
+                             "kernel_ms": {k: round(v["ms"], 4) for k, v in r["kernels"].items()}})
+
+    dom_name = max(head["kernels"], key=lambda k: head["kernels"][k]["ms"])
+    dom = head["kernels"][dom_name]
+    out = {
+        "metric": "tng_encode_decode_fp32_in_throughput",
+        "value": round(head["fp32_in_GBps"], 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(head["ms_per_step"], 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"encode+decode microbenchmark: M={M} workers x d=2^{args.log2d} fp32, "
+                               "g = ref + N(0,0.1)|ref|, ref ~ N(0,1), ternary codes, subtraction normalisation, seed 1",
+                   "M": M, "d": d, "bits": 2, "norm": "sub"},
+        "pct_hbm_peak_two_pass": round(100.0 * head["two_pass_GBps"] / HBM_PEAK_GBPS, 2),
+        "two_pass_algorithmic_GBps": round(head["two_pass_GBps"], 1),
+        "kernel_ms": {k: round(v["ms"], 4) for k, v in head["kernels"].items()},
+        "kernel_GBps": {k: round(v["GBps"], 1) for k, v in head["kernels"].items()},
+        "variants": variants,
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(dom["GBps"], 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None},
+    }
+    if not args.no_cpu:
+        log("timing the oracle on the host")
+        out["cpu_baseline"] = cpu_baseline(g, gref, seed, min(1 << args.cpu_log2d, d))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

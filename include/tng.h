@@ -1,0 +1,173 @@
+/*
+ * libtng -- the per-iteration data-parallel step of Trajectory Normalized Gradients (TNG,
+ * arXiv 1901.08227) for M simulated workers on one AMD MI355X (gfx950).
+ *
+ * One iteration is Algorithm 1 of the paper with the normalisation of Eqs. 1-2:
+ *   every worker m: local gradient g^m(w_t); normalise against the shared reference g~
+ *   (v = g - g~, Eq. 1; v = g ./ g~, Eq. 2; v = (g - g~) ./ g~', the combined form given
+ *   after Eq. 2); scale R_m = max_d |v_d|; stochastic low-bit code of v/R_m (section
+ *   "Gradient Compression"); pack;  server: decode, average over m, undo the
+ *   normalisation, w <- w - eta v (Background, Eq. "qsgd"), refresh g~ from the decoded
+ *   average (sections "Reference Vectors", "Convex Problems").
+ *
+ * General conventions
+ *   - C ABI, no exceptions, no exit(); every call returns a tng_status.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library allocates no device memory: scratch space is the
+ *     caller's workspace handed to tng_create.  tng_ctx is a small host object.
+ *   - All device work is enqueued on the hipStream_t given to tng_create and is
+ *     asynchronous; outputs are valid once the caller has synchronised that stream.
+ *     Only tng_set_logreg_dense / tng_set_logreg_csr block (a small host-to-device copy).
+ *   - float = IEEE binary32.  The normalise / threshold / decode arithmetic is evaluated
+ *     with one rounding per operation (no fused multiply-add, subnormals kept) so that
+ *     codes are reproducible bit for bit; for fixed (config, inputs, iter) the outputs of
+ *     encode and decode do not depend on launch geometry or on earlier calls.
+ *   - Layout: g is row-major [M][d] with row pitch d; codes is row-major [M][words] with
+ *     words = tng_words_per_row(d, bits); element e of a row sits in word e / (32/bits) at
+ *     bit offset (e % (32/bits)) * bits; code = level | sign << (bits-1); unused high bits
+ *     of the last word are zero.  g, gref, gref2, w, vbar, noise must be 16-byte aligned,
+ *     codes and scales 4-byte aligned.
+ *   - Inputs are assumed finite; non-finite gradients give unspecified codes.
+ *   - Errors: a NULL pointer, misalignment or an out-of-range field gives
+ *     TNG_ERR_INVALID_ARG and enqueues nothing; a call that needs problem data that was
+ *     not set gives TNG_ERR_BAD_STATE; a workspace smaller than tng_workspace_bytes gives
+ *     TNG_ERR_WORKSPACE; a failed launch gives TNG_ERR_HIP.
+ */
+#ifndef TNG_H
+#define TNG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tng_ctx tng_ctx;
+
+typedef enum {
+  TNG_OK = 0,
+  TNG_ERR_INVALID_ARG = 1,
+  TNG_ERR_BAD_STATE = 2,
+  TNG_ERR_WORKSPACE = 3,
+  TNG_ERR_UNSUPPORTED = 4,
+  TNG_ERR_HIP = 5
+} tng_status;
+
+/* How the gradient is normalised before coding (section "Normalized Gradients"). */
+typedef enum {
+  TNG_NORM_NONE = 0, /* v = g: zero reference, plain compressed SGD (remark after Proposition 2) */
+  TNG_NORM_SUB = 1,  /* Eq. 1: v = g - g~,         decoded as g~ + r                           */
+  TNG_NORM_QUOT = 2, /* Eq. 2: v = g ./ g~,        decoded as g~ (.) r                         */
+  TNG_NORM_COMB = 3  /* combined: v = (g - g~) ./ g~', decoded as g~' (.) r + g~               */
+} tng_norm;
+
+/* How the reference is refreshed (section "Reference Vectors"; "Convex Problems"). */
+typedef enum {
+  TNG_REF_ZERO = 0,    /* never: g~ keeps the caller's initial value (zeros in Algorithm 1)     */
+  TNG_REF_LAST_AVG = 1 /* g~ <- decoded average of this iteration when (iter+1) % period == 0   */
+} tng_ref_policy;
+
+typedef enum {
+  TNG_PROB_EXTERNAL = 0,     /* caller fills g; tng_local_grad is not available                 */
+  TNG_PROB_LOGREG_DENSE = 1, /* logistic regression, dense row-major features                   */
+  TNG_PROB_LOGREG_CSR = 2,   /* logistic regression, CSR features                               */
+  TNG_PROB_ROSENBROCK = 3    /* chain Rosenbrock function + additive noise                      */
+} tng_problem;
+
+typedef struct {
+  uint64_t d;          /* dimension of w, 1 <= d <= 2^34                                        */
+  uint32_t M;          /* number of simulated workers, >= 1                                     */
+  uint32_t bits;       /* 2: ternary {-1,0,1} x R; 4: sign + 3-bit level, 7 levels              */
+  int32_t norm;        /* tng_norm                                                              */
+  float quot_eps;      /* > 0: reference entries with |g~| < eps are replaced by +-eps (Eq. 2)  */
+  int32_t ref_policy;  /* tng_ref_policy                                                        */
+  uint32_t ref_period; /* K >= 1                                                                */
+  uint64_t seed;       /* Philox key                                                            */
+  float lr;            /* eta, finite                                                           */
+  float l2;            /* l2 regularisation of the logistic problems, finite                    */
+  uint32_t batch;      /* minibatch rows per worker (logistic problems), >= 1 there             */
+  int32_t problem;     /* tng_problem                                                           */
+} tng_config;
+
+/* ceil(d * bits / 32); 0 if bits is not 2 or 4. */
+uint64_t tng_words_per_row(uint64_t d, uint32_t bits);
+
+/* Device scratch bytes tng_create needs for this configuration; 0 if the configuration is invalid. */
+size_t tng_workspace_bytes(const tng_config* cfg);
+
+/* Creates a context.  cfg: host.  workspace: device, 256-byte aligned, at least
+ * tng_workspace_bytes(cfg) bytes, owned by the caller and kept alive until tng_destroy.
+ * hip_stream: a hipStream_t (NULL = the default stream).  *out receives the context. */
+tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_bytes,
+                      void* hip_stream, tng_ctx** out);
+tng_status tng_destroy(tng_ctx* ctx);
+const char* tng_status_string(tng_status s); /* static storage */
+
+/* Problem data (Background: worker m holds its own shard Omega_m).  X, y, rowptr, col, val:
+ * host arrays of M device pointers; n_rows: host array of M row counts (1 <= n < 2^32).
+ * Dense shards are row-major [n_rows[m]][d], 16-byte aligned; labels are 0/1 floats.
+ * CSR: rowptr int64[n_rows+1], col int32 in [0, d), val float.  The device data must outlive
+ * the context or the next tng_set_* call.  These two calls copy the pointer tables into the
+ * workspace and block until that copy is done. */
+tng_status tng_set_logreg_dense(tng_ctx* ctx, const float* const* X, const float* const* y,
+                                const uint64_t* n_rows);
+tng_status tng_set_logreg_csr(tng_ctx* ctx, const int64_t* const* rowptr,
+                              const int32_t* const* col, const float* const* val,
+                              const float* const* y, const uint64_t* n_rows);
+/* Rosenbrock: additive noise of the coming iteration, device [M][d], or NULL for none
+ * ("Nonconvex Problems": the stochastic gradient is the exact gradient plus Gaussian noise). */
+tng_status tng_set_noise(tng_ctx* ctx, const float* noise);
+/* Second reference g~' of TNG_NORM_COMB, device [d]; must be set before encode / decode. */
+tng_status tng_set_second_reference(tng_ctx* ctx, const float* gref2);
+
+/* Raw 32-bit draws first .. first+count-1 of the sequence (seed, iter, worker, stream) of the
+ * counter-based generator Philox4x32-10 (Salmon et al., SC'11): draw j is output word j & 3 of
+ * the block with counter (j >> 2, worker, iter, stream) and key (seed low, seed high).
+ * Stream 0 feeds the rounding decisions (element e of worker m uses draw e), stream 1 the
+ * minibatch row ids.  out: device uint32[count]. */
+tng_status tng_rng_draws(tng_ctx* ctx, uint32_t iter, uint32_t worker, uint32_t stream,
+                         uint64_t first, uint64_t count, uint32_t* out);
+
+/* Minibatch row ids of iteration iter, idx[m][j] = (draw_j * n_rows[m]) >> 32, uniform with
+ * replacement (Background: "uniformly sampled").  idx: device uint32[M][batch]. */
+tng_status tng_minibatch_indices(tng_ctx* ctx, uint32_t iter, uint32_t* idx);
+
+/* Algorithm 1, local gradient of every worker at w.  w: device [d]; g: device [M][d] (out).
+ * Logistic problems: g_m = (1/B) sum_{i in batch_m(iter)} (sigma(x_i . w) - y_i) x_i + l2 w.
+ * Rosenbrock: g_m = grad f(w) + noise_m, f(x) = sum_i 100 (x_{i+1} - x_i^2)^2 + (1 - x_i)^2. */
+tng_status tng_local_grad(tng_ctx* ctx, uint32_t iter, const float* w, float* g);
+
+/* Workers' side of Algorithm 1 (normalise, R_m, sample, pack).  g: device [M][d]; gref: device
+ * [d] (ignored, may be NULL, for TNG_NORM_NONE); codes: device [M][words] (out); scales:
+ * device [M] (out), scales[m] = R_m = max_d |v_d| of worker m, taken as 0 below FLT_MIN. */
+tng_status tng_normalize_encode(tng_ctx* ctx, uint32_t iter, const float* g, const float* gref,
+                                uint32_t* codes, float* scales);
+
+/* Server's side: vbar[e] = denorm( (sum_m decode(codes[m][e]) in worker order) * (1/M) ).
+ * codes, scales, gref as above; vbar: device [d] (out). */
+tng_status tng_decode_aggregate(tng_ctx* ctx, const uint32_t* codes, const float* scales,
+                                const float* gref, float* vbar);
+
+/* Reference rule: TNG_REF_LAST_AVG and (iter+1) % ref_period == 0: gref <- vbar; else no-op. */
+tng_status tng_update_reference(tng_ctx* ctx, uint32_t iter, const float* vbar, float* gref);
+
+/* One whole iteration: local_grad (unless TNG_PROB_EXTERNAL, where g is an input),
+ * normalize_encode, decode_aggregate, w <- w - lr * vbar, update_reference.
+ * w, gref: device [d], updated in place; g, codes, scales, vbar: device, as above. */
+tng_status tng_step(tng_ctx* ctx, uint32_t iter, float* w, float* gref, float* g,
+                    uint32_t* codes, float* scales, float* vbar);
+
+/* Timing hook for benchmarks and profilers (no counterpart in the paper).  events: host array of
+ * 5 * slots hipEvent_t created by the caller with timing enabled, or NULL to switch the hook off;
+ * the array is copied.  Encode call number c (tng_normalize_encode or the encode part of tng_step,
+ * counted from this call on) records, on the context's stream, events[5 (c % slots) + 0] before
+ * the scale pass, + 1 between the scale pass and the quantise pass, + 2 after the quantise pass;
+ * decode call number c records + 3 before and + 4 after the decode kernel.  The events stay owned
+ * by the caller and must outlive the calls that record them. */
+tng_status tng_set_profile_events(tng_ctx* ctx, void* const* events, uint32_t slots);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TNG_H */

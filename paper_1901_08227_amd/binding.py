@@ -1,0 +1,242 @@
+"""ctypes binding of libtng (include/tng.h).  Argument marshalling only: every step of the
+iteration runs in the HIP kernels of the library; torch tensors are used as device memory.
+
+The module-level functions carry the names of the C entry points and take a context handle
+plus torch CUDA tensors; `Context` owns the workspace and keeps problem data alive.
+There is no fallback: if the built library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtng.so")
+
+TNG_OK = 0
+TNG_ERR_INVALID_ARG, TNG_ERR_BAD_STATE, TNG_ERR_WORKSPACE, TNG_ERR_UNSUPPORTED, TNG_ERR_HIP = 1, 2, 3, 4, 5
+NORM_NONE, NORM_SUB, NORM_QUOT, NORM_COMB = 0, 1, 2, 3
+REF_ZERO, REF_LAST_AVG = 0, 1
+PROB_EXTERNAL, PROB_LOGREG_DENSE, PROB_LOGREG_CSR, PROB_ROSENBROCK = 0, 1, 2, 3
+
+
+class TngConfig(ctypes.Structure):
+    _fields_ = [
+        ("d", ctypes.c_uint64), ("M", ctypes.c_uint32), ("bits", ctypes.c_uint32),
+        ("norm", ctypes.c_int32), ("quot_eps", ctypes.c_float),
+        ("ref_policy", ctypes.c_int32), ("ref_period", ctypes.c_uint32),
+        ("seed", ctypes.c_uint64), ("lr", ctypes.c_float), ("l2", ctypes.c_float),
+        ("batch", ctypes.c_uint32), ("problem", ctypes.c_int32),
+    ]
+
+
+class TngError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (tng_status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (python -m paper_1901_08227_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"libtng is not built: {LIB_PATH} is missing; run __graft_entry__.build()")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u32, u64, cfgp = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.POINTER(TngConfig)
+        L.tng_words_per_row.restype, L.tng_words_per_row.argtypes = u64, [u64, u32]
+        L.tng_workspace_bytes.restype, L.tng_workspace_bytes.argtypes = ctypes.c_size_t, [cfgp]
+        L.tng_status_string.restype, L.tng_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        sigs = {
+            "tng_create": [cfgp, vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)],
+            "tng_destroy": [vp],
+            "tng_set_logreg_dense": [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(u64)],
+            "tng_set_logreg_csr": [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                   ctypes.POINTER(vp), ctypes.POINTER(u64)],
+            "tng_set_noise": [vp, vp],
+            "tng_set_second_reference": [vp, vp],
+            "tng_set_profile_events": [vp, ctypes.POINTER(vp), u32],
+            "tng_rng_draws": [vp, u32, u32, u32, u64, u64, vp],
+            "tng_minibatch_indices": [vp, u32, vp],
+            "tng_local_grad": [vp, u32, vp, vp],
+            "tng_normalize_encode": [vp, u32, vp, vp, vp, vp],
+            "tng_decode_aggregate": [vp, vp, vp, vp, vp],
+            "tng_update_reference": [vp, u32, vp, vp],
+            "tng_step": [vp, u32, vp, vp, vp, vp, vp, vp],
+        }
+        for name, argtypes in sigs.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = ctypes.c_int, argtypes
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().tng_status_string(int(status)).decode()
+
+
+def tng_words_per_row(d: int, bits: int) -> int:
+    return int(lib().tng_words_per_row(d, bits))
+
+
+def tng_workspace_bytes(cfg: TngConfig) -> int:
+    return int(lib().tng_workspace_bytes(ctypes.byref(cfg)))
+
+
+def _check(status: int, where: str):
+    if status != TNG_OK:
+        raise TngError(status, where)
+
+
+def _ptr(t, dtype, numel, name):
+    """Device address of a contiguous CUDA tensor of the given dtype and at least numel elements."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name}: expected a CUDA tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: expected contiguous {dtype}, got {t.dtype}")
+    if t.numel() < numel:
+        raise ValueError(f"{name}: needs {numel} elements, has {t.numel()}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Context:
+    """A tng_ctx plus the device workspace it was created on (torch owns the memory)."""
+
+    def __init__(self, *, d, M, bits=2, norm=NORM_SUB, quot_eps=1e-8, ref_policy=REF_LAST_AVG, ref_period=1,
+                 seed=0, lr=0.1, l2=0.0, batch=0, problem=PROB_EXTERNAL, device="cuda:0", stream=None):
+        self.cfg = TngConfig(d=d, M=M, bits=bits, norm=norm, quot_eps=quot_eps, ref_policy=ref_policy,
+                             ref_period=ref_period, seed=seed, lr=lr, l2=l2, batch=batch, problem=problem)
+        nbytes = tng_workspace_bytes(self.cfg)
+        if nbytes == 0:
+            raise TngError(TNG_ERR_INVALID_ARG, "tng_workspace_bytes")
+        self.device = torch.device(device)
+        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=self.device)
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device)
+        self.stream = stream
+        self.handle = ctypes.c_void_p()
+        _check(lib().tng_create(ctypes.byref(self.cfg), ctypes.c_void_p(self.workspace.data_ptr()), nbytes,
+                                ctypes.c_void_p(stream.cuda_stream), ctypes.byref(self.handle)), "tng_create")
+        self.d, self.M, self.bits, self.batch = int(d), int(M), int(bits), int(batch)
+        self.words = tng_words_per_row(d, bits)
+        self._keep = {}
+
+    def close(self):
+        if self.handle:
+            lib().tng_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- problem data
+    def _table(self, tensors, dtype, numels, name):
+        arr = (ctypes.c_void_p * self.M)()
+        for m, t in enumerate(tensors):
+            arr[m] = _ptr(t, dtype, numels[m], f"{name}[{m}]").value
+        return arr
+
+    def set_logreg_dense(self, X, y):
+        """X: list of M tensors [n_m][d] float32; y: list of M tensors [n_m] float32 (0/1)."""
+        n = [int(x.shape[0]) for x in X]
+        rows = (ctypes.c_uint64 * self.M)(*n)
+        tx = self._table(X, torch.float32, [k * self.d for k in n], "X")
+        ty = self._table(y, torch.float32, n, "y")
+        self._keep["data"] = (list(X), list(y))
+        self.n_rows = n
+        _check(lib().tng_set_logreg_dense(self.handle, tx, ty, rows), "tng_set_logreg_dense")
+
+    def set_logreg_csr(self, rowptr, col, val, y):
+        n = [int(r.numel()) - 1 for r in rowptr]
+        rows = (ctypes.c_uint64 * self.M)(*n)
+        nnz = [int(c.numel()) for c in col]
+        tr = self._table(rowptr, torch.int64, [k + 1 for k in n], "rowptr")
+        tc = self._table(col, torch.int32, nnz, "col")
+        tv = self._table(val, torch.float32, nnz, "val")
+        ty = self._table(y, torch.float32, n, "y")
+        self._keep["data"] = (list(rowptr), list(col), list(val), list(y))
+        self.n_rows = n
+        _check(lib().tng_set_logreg_csr(self.handle, tr, tc, tv, ty, rows), "tng_set_logreg_csr")
+
+    def set_noise(self, noise):
+        self._keep["noise"] = noise
+        _check(lib().tng_set_noise(self.handle, _ptr(noise, torch.float32, self.M * self.d, "noise")), "tng_set_noise")
+
+    def set_second_reference(self, gref2):
+        self._keep["gref2"] = gref2
+        _check(lib().tng_set_second_reference(self.handle, _ptr(gref2, torch.float32, self.d, "gref2")),
+               "tng_set_second_reference")
+
+    def set_profile_events(self, events, slots):
+        """events: list of 5*slots hipEvent_t handles (ints), or None to switch the hook off."""
+        if not events:
+            _check(lib().tng_set_profile_events(self.handle, None, 0), "tng_set_profile_events")
+            return
+        arr = (ctypes.c_void_p * len(events))(*events)
+        _check(lib().tng_set_profile_events(self.handle, arr, slots), "tng_set_profile_events")
+
+    # ---- the calls
+    def rng_draws(self, it, worker, stream, first, count, out):
+        _check(lib().tng_rng_draws(self.handle, it, worker, stream, first, count,
+                                   _ptr(out, torch.int32, count, "out")), "tng_rng_draws")
+
+    def minibatch_indices(self, it, idx):
+        _check(lib().tng_minibatch_indices(self.handle, it, _ptr(idx, torch.int32, self.M * self.batch, "idx")),
+               "tng_minibatch_indices")
+
+    def local_grad(self, it, w, g):
+        _check(lib().tng_local_grad(self.handle, it, _ptr(w, torch.float32, self.d, "w"),
+                                    _ptr(g, torch.float32, self.M * self.d, "g")), "tng_local_grad")
+
+    def normalize_encode(self, it, g, gref, codes, scales):
+        _check(lib().tng_normalize_encode(
+            self.handle, it, _ptr(g, torch.float32, self.M * self.d, "g"), _ptr(gref, torch.float32, self.d, "gref"),
+            _ptr(codes, torch.int32, self.M * self.words, "codes"), _ptr(scales, torch.float32, self.M, "scales")),
+            "tng_normalize_encode")
+
+    def decode_aggregate(self, codes, scales, gref, vbar):
+        _check(lib().tng_decode_aggregate(
+            self.handle, _ptr(codes, torch.int32, self.M * self.words, "codes"),
+            _ptr(scales, torch.float32, self.M, "scales"), _ptr(gref, torch.float32, self.d, "gref"),
+            _ptr(vbar, torch.float32, self.d, "vbar")), "tng_decode_aggregate")
+
+    def update_reference(self, it, vbar, gref):
+        _check(lib().tng_update_reference(self.handle, it, _ptr(vbar, torch.float32, self.d, "vbar"),
+                                          _ptr(gref, torch.float32, self.d, "gref")), "tng_update_reference")
+
+    def step(self, it, w, gref, g, codes, scales, vbar):
+        _check(lib().tng_step(
+            self.handle, it, _ptr(w, torch.float32, self.d, "w"), _ptr(gref, torch.float32, self.d, "gref"),
+            _ptr(g, torch.float32, self.M * self.d, "g"), _ptr(codes, torch.int32, self.M * self.words, "codes"),
+            _ptr(scales, torch.float32, self.M, "scales"), _ptr(vbar, torch.float32, self.d, "vbar")), "tng_step")
+
+
+# Module-level spellings of the C entry points (same names, same argument order).
+def tng_local_grad(ctx: Context, it, w, g):
+    ctx.local_grad(it, w, g)
+
+
+def tng_normalize_encode(ctx: Context, it, g, gref, codes, scales):
+    ctx.normalize_encode(it, g, gref, codes, scales)
+
+
+def tng_decode_aggregate(ctx: Context, codes, scales, gref, vbar):
+    ctx.decode_aggregate(codes, scales, gref, vbar)
+
+
+def tng_update_reference(ctx: Context, it, vbar, gref):
+    ctx.update_reference(it, vbar, gref)
+
+
+def tng_step(ctx: Context, it, w, gref, g, codes, scales, vbar):
+    ctx.step(it, w, gref, g, codes, scales, vbar)

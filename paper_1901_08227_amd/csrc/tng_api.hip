@@ -1,0 +1,360 @@
+// C-ABI layer of libtng: argument checking, workspace partition, and the call sequence of one
+// TNG iteration (Algorithm 1 of arXiv 1901.08227 with the normalisation of Eqs. 1-2).
+#include "../../include/tng.h"
+
+#include "tng_device.hpp"
+#include "tng_kernels.hpp"
+
+#include <cmath>
+#include <new>
+#include <vector>
+
+struct tng_ctx {
+  tng_config cfg;
+  hipStream_t stream;
+  tng::CodecShape shape;
+  // workspace partition (device)
+  uint32_t* idx;          // [M][batch] minibatch row ids
+  float* resid;           // [M][batch] sigma(z) - y
+  const void** tables;    // 5 pointer tables of M entries: X|rowptr, col, val, y, and n_rows
+  bool have_dense, have_csr;
+  const float* noise;     // Rosenbrock noise, may be null
+  const float* gref2;     // second reference of the combined normalisation
+  std::vector<hipEvent_t> prof;  // optional timing events, 5 per slot
+  uint32_t prof_slots;
+  uint64_t enc_calls, dec_calls;
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t round_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bool config_valid(const tng_config* c) {
+  if (c == nullptr) return false;
+  if (c->d == 0 || c->d > (1ull << 34)) return false;
+  if (c->M == 0 || c->M > 65535u) return false;
+  if (c->bits != 2 && c->bits != 4) return false;
+  if (c->norm < TNG_NORM_NONE || c->norm > TNG_NORM_COMB) return false;
+  if (!(c->quot_eps > 0.0f) || !std::isfinite(c->quot_eps)) return false;
+  if (c->ref_policy != TNG_REF_ZERO && c->ref_policy != TNG_REF_LAST_AVG) return false;
+  if (c->ref_period == 0) return false;
+  if (!std::isfinite(c->lr) || !std::isfinite(c->l2)) return false;
+  if (c->problem < TNG_PROB_EXTERNAL || c->problem > TNG_PROB_ROSENBROCK) return false;
+  const bool logreg = c->problem == TNG_PROB_LOGREG_DENSE || c->problem == TNG_PROB_LOGREG_CSR;
+  if (logreg && c->batch == 0) return false;
+  return true;
+}
+
+struct Partition {
+  size_t idx_off, resid_off, tables_off, total;
+};
+
+Partition partition(const tng_config* c) {
+  Partition p{};
+  const bool logreg = c->problem == TNG_PROB_LOGREG_DENSE || c->problem == TNG_PROB_LOGREG_CSR;
+  const size_t mb = logreg ? (size_t)c->M * c->batch : 0;
+  size_t off = 0;
+  p.idx_off = off;
+  off += round_up(mb * sizeof(uint32_t));
+  p.resid_off = off;
+  off += round_up(mb * sizeof(float));
+  p.tables_off = off;
+  off += round_up(logreg ? (size_t)c->M * 5 * sizeof(void*) : 0);
+  p.total = off < kAlign ? kAlign : off;
+  return p;
+}
+
+inline bool refresh_now(const tng_config& c, uint32_t iter) {
+  return c.ref_policy == TNG_REF_LAST_AVG && ((uint64_t)iter + 1) % c.ref_period == 0;
+}
+
+inline tng_status hip_status(hipError_t e) { return e == hipSuccess ? TNG_OK : TNG_ERR_HIP; }
+
+tng::LogregData logreg_tables(const tng_ctx* ctx) {
+  const uint32_t M = ctx->cfg.M;
+  tng::LogregData p{};
+  const void** t = ctx->tables;
+  p.X = reinterpret_cast<const float* const*>(t);
+  p.rowptr = reinterpret_cast<const int64_t* const*>(t);
+  p.col = reinterpret_cast<const int32_t* const*>(t + M);
+  p.val = reinterpret_cast<const float* const*>(t + 2 * (size_t)M);
+  p.y = reinterpret_cast<const float* const*>(t + 3 * (size_t)M);
+  p.n_rows = reinterpret_cast<const uint64_t*>(t + 4 * (size_t)M);
+  return p;
+}
+
+bool needs_ref(const tng_config& c) { return c.norm != TNG_NORM_NONE; }
+
+inline void mark(tng_ctx* ctx, uint64_t call, int which) {
+  if (ctx->prof_slots != 0) (void)hipEventRecord(ctx->prof[5 * (call % ctx->prof_slots) + which], ctx->stream);
+}
+
+tng_status encode_impl(tng_ctx* ctx, uint32_t iter, const float* g, const float* gref, uint32_t* codes,
+                       float* scales) {
+  const uint64_t call = ctx->enc_calls++;
+  hipError_t e = tng::launch_fill_u32(reinterpret_cast<uint32_t*>(scales), ctx->cfg.M, 0u, ctx->stream);
+  if (e != hipSuccess) return TNG_ERR_HIP;
+  mark(ctx, call, 0);
+  e = tng::launch_absmax(ctx->shape, g, gref, ctx->gref2, scales, ctx->stream);
+  if (e != hipSuccess) return TNG_ERR_HIP;
+  mark(ctx, call, 1);
+  e = tng::launch_quantize_pack(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, ctx->stream);
+  mark(ctx, call, 2);
+  return hip_status(e);
+}
+
+tng_status decode_impl(tng_ctx* ctx, const uint32_t* codes, const float* scales, const float* gref, float* vbar,
+                       float* w, float* ref_out) {
+  const uint64_t call = ctx->dec_calls++;
+  mark(ctx, call, 3);
+  const hipError_t e = tng::launch_decode(ctx->shape, codes, scales, gref, ctx->gref2, vbar, w, ctx->cfg.lr,
+                                          ref_out, ctx->stream);
+  mark(ctx, call, 4);
+  return hip_status(e);
+}
+
+tng_status check_codec_args(const tng_ctx* ctx, const float* g, const float* gref, const void* codes,
+                            const float* scales, const float* vbar, bool need_g, bool need_vbar) {
+  if (ctx == nullptr || codes == nullptr || scales == nullptr) return TNG_ERR_INVALID_ARG;
+  if (need_g && g == nullptr) return TNG_ERR_INVALID_ARG;
+  if (need_vbar && vbar == nullptr) return TNG_ERR_INVALID_ARG;
+  if (needs_ref(ctx->cfg) && gref == nullptr) return TNG_ERR_INVALID_ARG;
+  if (!aligned(g, 16) || !aligned(gref, 16) || !aligned(vbar, 16)) return TNG_ERR_INVALID_ARG;
+  if (!aligned(codes, 4) || !aligned(scales, 4)) return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.norm == TNG_NORM_COMB && ctx->gref2 == nullptr) return TNG_ERR_BAD_STATE;
+  return TNG_OK;
+}
+
+tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g) {
+  const tng_config& c = ctx->cfg;
+  const uint32_t k0 = ctx->shape.k0, k1 = ctx->shape.k1;
+  hipError_t e = hipSuccess;
+  switch (c.problem) {
+    case TNG_PROB_LOGREG_DENSE: {
+      if (!ctx->have_dense) return TNG_ERR_BAD_STATE;
+      const tng::LogregData p = logreg_tables(ctx);
+      e = tng::launch_minibatch_indices(k0, k1, iter, c.M, c.batch, p.n_rows, ctx->idx, ctx->stream);
+      if (e != hipSuccess) return TNG_ERR_HIP;
+      e = tng::launch_logreg_dense_grad(p, c.d, c.M, c.batch, c.l2, ctx->idx, ctx->resid, w, g, ctx->stream);
+      return hip_status(e);
+    }
+    case TNG_PROB_LOGREG_CSR: {
+      if (!ctx->have_csr) return TNG_ERR_BAD_STATE;
+      const tng::LogregData p = logreg_tables(ctx);
+      e = tng::launch_minibatch_indices(k0, k1, iter, c.M, c.batch, p.n_rows, ctx->idx, ctx->stream);
+      if (e != hipSuccess) return TNG_ERR_HIP;
+      e = tng::launch_logreg_csr_grad(p, c.d, c.M, c.batch, c.l2, ctx->idx, ctx->resid, w, g, ctx->stream);
+      return hip_status(e);
+    }
+    case TNG_PROB_ROSENBROCK:
+      e = tng::launch_rosenbrock_grad(c.d, c.M, w, ctx->noise, g, ctx->stream);
+      return hip_status(e);
+    default:
+      return TNG_ERR_BAD_STATE;
+  }
+}
+
+tng_status upload_tables(tng_ctx* ctx, const void* const* t0, const void* const* t1, const void* const* t2,
+                         const void* const* t3, const uint64_t* n_rows) {
+  const uint32_t M = ctx->cfg.M;
+  std::vector<const void*> host(5 * (size_t)M, nullptr);
+  for (uint32_t m = 0; m < M; ++m) {
+    if (n_rows[m] == 0 || n_rows[m] >= (1ull << 32)) return TNG_ERR_INVALID_ARG;
+    if (t0[m] == nullptr || t3[m] == nullptr) return TNG_ERR_INVALID_ARG;
+    if (t1 != nullptr && (t1[m] == nullptr || t2[m] == nullptr)) return TNG_ERR_INVALID_ARG;
+    host[m] = t0[m];
+    host[M + m] = t1 ? t1[m] : nullptr;
+    host[2 * (size_t)M + m] = t2 ? t2[m] : nullptr;
+    host[3 * (size_t)M + m] = t3[m];
+    static_assert(sizeof(void*) == sizeof(uint64_t), "pointer tables and row counts share one array");
+    host[4 * (size_t)M + m] = reinterpret_cast<const void*>(static_cast<uintptr_t>(n_rows[m]));
+  }
+  if (hipMemcpyAsync(ctx->tables, host.data(), host.size() * sizeof(void*), hipMemcpyHostToDevice,
+                     ctx->stream) != hipSuccess)
+    return TNG_ERR_HIP;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TNG_ERR_HIP;
+  return TNG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t tng_words_per_row(uint64_t d, uint32_t bits) {
+  if (bits != 2 && bits != 4) return 0;
+  const uint64_t per = 32 / bits;
+  return (d + per - 1) / per;
+}
+
+size_t tng_workspace_bytes(const tng_config* cfg) {
+  if (!config_valid(cfg)) return 0;
+  return partition(cfg).total;
+}
+
+const char* tng_status_string(tng_status s) {
+  switch (s) {
+    case TNG_OK: return "ok";
+    case TNG_ERR_INVALID_ARG: return "invalid argument";
+    case TNG_ERR_BAD_STATE: return "call not valid in this state (problem data missing or wrong problem kind)";
+    case TNG_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case TNG_ERR_UNSUPPORTED: return "unsupported";
+    case TNG_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_bytes, void* hip_stream,
+                      tng_ctx** out) {
+  if (out == nullptr) return TNG_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (!config_valid(cfg)) return TNG_ERR_INVALID_ARG;
+  const Partition p = partition(cfg);
+  if (workspace == nullptr || !aligned(workspace, kAlign) || workspace_bytes < p.total) return TNG_ERR_WORKSPACE;
+  tng_ctx* ctx = new (std::nothrow) tng_ctx();
+  if (ctx == nullptr) return TNG_ERR_HIP;
+  ctx->cfg = *cfg;
+  ctx->stream = static_cast<hipStream_t>(hip_stream);
+  ctx->shape.d = cfg->d;
+  ctx->shape.words = tng_words_per_row(cfg->d, cfg->bits);
+  ctx->shape.M = cfg->M;
+  ctx->shape.bits = (int)cfg->bits;
+  ctx->shape.norm = cfg->norm;
+  ctx->shape.eps = cfg->quot_eps;
+  ctx->shape.k0 = (uint32_t)(cfg->seed & 0xFFFFFFFFull);
+  ctx->shape.k1 = (uint32_t)(cfg->seed >> 32);
+  char* base = static_cast<char*>(workspace);
+  ctx->idx = reinterpret_cast<uint32_t*>(base + p.idx_off);
+  ctx->resid = reinterpret_cast<float*>(base + p.resid_off);
+  ctx->tables = reinterpret_cast<const void**>(base + p.tables_off);
+  ctx->have_dense = ctx->have_csr = false;
+  ctx->noise = nullptr;
+  ctx->gref2 = nullptr;
+  ctx->prof_slots = 0;
+  ctx->enc_calls = ctx->dec_calls = 0;
+  *out = ctx;
+  return TNG_OK;
+}
+
+tng_status tng_destroy(tng_ctx* ctx) {
+  if (ctx == nullptr) return TNG_ERR_INVALID_ARG;
+  delete ctx;
+  return TNG_OK;
+}
+
+tng_status tng_set_logreg_dense(tng_ctx* ctx, const float* const* X, const float* const* y,
+                                const uint64_t* n_rows) {
+  if (ctx == nullptr || X == nullptr || y == nullptr || n_rows == nullptr) return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.problem != TNG_PROB_LOGREG_DENSE) return TNG_ERR_BAD_STATE;
+  for (uint32_t m = 0; m < ctx->cfg.M; ++m)
+    if (!aligned(X[m], 16)) return TNG_ERR_INVALID_ARG;
+  const tng_status s = upload_tables(ctx, reinterpret_cast<const void* const*>(X), nullptr, nullptr,
+                                     reinterpret_cast<const void* const*>(y), n_rows);
+  if (s == TNG_OK) ctx->have_dense = true;
+  return s;
+}
+
+tng_status tng_set_logreg_csr(tng_ctx* ctx, const int64_t* const* rowptr, const int32_t* const* col,
+                              const float* const* val, const float* const* y, const uint64_t* n_rows) {
+  if (ctx == nullptr || rowptr == nullptr || col == nullptr || val == nullptr || y == nullptr ||
+      n_rows == nullptr)
+    return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.problem != TNG_PROB_LOGREG_CSR) return TNG_ERR_BAD_STATE;
+  const tng_status s = upload_tables(ctx, reinterpret_cast<const void* const*>(rowptr),
+                                     reinterpret_cast<const void* const*>(col),
+                                     reinterpret_cast<const void* const*>(val),
+                                     reinterpret_cast<const void* const*>(y), n_rows);
+  if (s == TNG_OK) ctx->have_csr = true;
+  return s;
+}
+
+tng_status tng_set_noise(tng_ctx* ctx, const float* noise) {
+  if (ctx == nullptr || !aligned(noise, 16)) return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.problem != TNG_PROB_ROSENBROCK) return TNG_ERR_BAD_STATE;
+  ctx->noise = noise;
+  return TNG_OK;
+}
+
+tng_status tng_set_second_reference(tng_ctx* ctx, const float* gref2) {
+  if (ctx == nullptr || gref2 == nullptr || !aligned(gref2, 16)) return TNG_ERR_INVALID_ARG;
+  ctx->gref2 = gref2;
+  return TNG_OK;
+}
+
+tng_status tng_set_profile_events(tng_ctx* ctx, void* const* events, uint32_t slots) {
+  if (ctx == nullptr || (events == nullptr && slots != 0)) return TNG_ERR_INVALID_ARG;
+  ctx->prof.clear();
+  ctx->prof_slots = 0;
+  ctx->enc_calls = ctx->dec_calls = 0;
+  if (events == nullptr || slots == 0) return TNG_OK;
+  for (size_t i = 0; i < 5 * (size_t)slots; ++i) {
+    if (events[i] == nullptr) {
+      ctx->prof.clear();
+      return TNG_ERR_INVALID_ARG;
+    }
+    ctx->prof.push_back(static_cast<hipEvent_t>(events[i]));
+  }
+  ctx->prof_slots = slots;
+  return TNG_OK;
+}
+
+tng_status tng_rng_draws(tng_ctx* ctx, uint32_t iter, uint32_t worker, uint32_t stream, uint64_t first,
+                         uint64_t count, uint32_t* out) {
+  if (ctx == nullptr || (out == nullptr && count != 0) || !aligned(out, 4)) return TNG_ERR_INVALID_ARG;
+  if (first + count < first || ((first + count) >> 2) > (1ull << 32)) return TNG_ERR_INVALID_ARG;
+  return hip_status(tng::launch_rng_draws(ctx->shape.k0, ctx->shape.k1, iter, worker, stream, first, count, out,
+                                          ctx->stream));
+}
+
+tng_status tng_minibatch_indices(tng_ctx* ctx, uint32_t iter, uint32_t* idx) {
+  if (ctx == nullptr || idx == nullptr || !aligned(idx, 4)) return TNG_ERR_INVALID_ARG;
+  if (!ctx->have_dense && !ctx->have_csr) return TNG_ERR_BAD_STATE;
+  const tng::LogregData p = logreg_tables(ctx);
+  return hip_status(tng::launch_minibatch_indices(ctx->shape.k0, ctx->shape.k1, iter, ctx->cfg.M,
+                                                  ctx->cfg.batch, p.n_rows, idx, ctx->stream));
+}
+
+tng_status tng_local_grad(tng_ctx* ctx, uint32_t iter, const float* w, float* g) {
+  if (ctx == nullptr || w == nullptr || g == nullptr || !aligned(w, 16) || !aligned(g, 16))
+    return TNG_ERR_INVALID_ARG;
+  return local_grad_impl(ctx, iter, w, g);
+}
+
+tng_status tng_normalize_encode(tng_ctx* ctx, uint32_t iter, const float* g, const float* gref,
+                                uint32_t* codes, float* scales) {
+  const tng_status s = check_codec_args(ctx, g, gref, codes, scales, nullptr, true, false);
+  if (s != TNG_OK) return s;
+  return encode_impl(ctx, iter, g, gref, codes, scales);
+}
+
+tng_status tng_decode_aggregate(tng_ctx* ctx, const uint32_t* codes, const float* scales, const float* gref,
+                                float* vbar) {
+  const tng_status s = check_codec_args(ctx, nullptr, gref, codes, scales, vbar, false, true);
+  if (s != TNG_OK) return s;
+  return decode_impl(ctx, codes, scales, gref, vbar, nullptr, nullptr);
+}
+
+tng_status tng_update_reference(tng_ctx* ctx, uint32_t iter, const float* vbar, float* gref) {
+  if (ctx == nullptr || vbar == nullptr || gref == nullptr || !aligned(vbar, 16) || !aligned(gref, 16))
+    return TNG_ERR_INVALID_ARG;
+  if (!refresh_now(ctx->cfg, iter)) return TNG_OK;
+  return hip_status(tng::launch_copy_f32(gref, vbar, ctx->cfg.d, ctx->stream));
+}
+
+tng_status tng_step(tng_ctx* ctx, uint32_t iter, float* w, float* gref, float* g, uint32_t* codes,
+                    float* scales, float* vbar) {
+  if (ctx == nullptr || w == nullptr || gref == nullptr || !aligned(w, 16)) return TNG_ERR_INVALID_ARG;
+  tng_status s = check_codec_args(ctx, g, gref, codes, scales, vbar, true, true);
+  if (s != TNG_OK) return s;
+  if (ctx->cfg.problem != TNG_PROB_EXTERNAL) {
+    s = local_grad_impl(ctx, iter, w, g);
+    if (s != TNG_OK) return s;
+  }
+  s = encode_impl(ctx, iter, g, gref, codes, scales);
+  if (s != TNG_OK) return s;
+  float* ref_out = refresh_now(ctx->cfg, iter) ? gref : nullptr;
+  return decode_impl(ctx, codes, scales, gref, vbar, w, ref_out);
+}
+
+}  // extern "C"

@@ -1,0 +1,554 @@
+// Codec kernels of libtng: scale (max of the normalised gradient), stochastic quantise + pack,
+// and decode + average + de-normalise (+ iterate / reference update), for gfx950.
+//
+// All three stream fp32 data once; they are bound by HBM bandwidth (and, for the quantiser, by the
+// integer multiplies of the counter-based RNG), never by matrix math.  Layout choices:
+//  * a workgroup owns a tile of coordinates and loops over the workers inside the kernel, so the
+//    shared reference tile is fetched once and kept in registers;
+//  * every global access is a coalesced 16-byte (fp32) or 4-byte (packed words) per-lane access;
+//    the 2- or 4-bit codes a lane produces are transposed into whole words through LDS;
+//  * Philox block j covers elements 4j..4j+3, i.e. exactly one float4.
+#include "tng_device.hpp"
+#include "tng_kernels.hpp"
+
+#include <float.h>
+#include <type_traits>
+
+namespace tng {
+
+namespace {
+
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kLoadsPerLane = 4;  // float4 loads per lane and worker in the quantiser tile
+constexpr uint32_t kMaxGridX = 1u << 20;
+
+__global__ __launch_bounds__(kBlock) void fill_u32_kernel(uint32_t* p, uint64_t n, uint32_t v) {
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+
+__global__ __launch_bounds__(kBlock) void copy_f32_kernel(float* __restrict__ dst,
+                                                          const float* __restrict__ src, uint64_t n) {
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(kBlock) void copy_f32x4_kernel(float4* __restrict__ dst,
+                                                            const float4* __restrict__ src, uint64_t n) {
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(kBlock) void rng_draws_kernel(uint32_t k0, uint32_t k1, uint32_t iter,
+                                                           uint32_t worker, uint32_t stream,
+                                                           uint64_t first, uint64_t count, uint32_t* out) {
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < count; i += stride) {
+    const uint64_t j = first + i;
+    const U32x4 r = philox4x32_10((uint32_t)(j >> 2), worker, iter, stream, k0, k1);
+    const uint32_t lane = (uint32_t)(j & 3);
+    out[i] = lane == 0 ? r.x : lane == 1 ? r.y : lane == 2 ? r.z : r.w;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Reference operands of one float4 of coordinates.
+// ------------------------------------------------------------------------------------------
+template <int NORM>
+struct RefTile {
+  float4 r1, r2;
+  __device__ __forceinline__ void load(const float4* ref, const float4* ref2, uint64_t i, float eps) {
+    r1 = make_float4(0.f, 0.f, 0.f, 0.f);
+    r2 = make_float4(1.f, 1.f, 1.f, 1.f);
+    if (NORM == kNormSub || NORM == kNormComb) r1 = ref[i];
+    if (NORM == kNormQuot) {
+      const float4 r = ref[i];
+      r1 = make_float4(clamp_ref(r.x, eps), clamp_ref(r.y, eps), clamp_ref(r.z, eps), clamp_ref(r.w, eps));
+    }
+    if (NORM == kNormComb) {
+      const float4 r = ref2[i];
+      r2 = make_float4(clamp_ref(r.x, eps), clamp_ref(r.y, eps), clamp_ref(r.z, eps), clamp_ref(r.w, eps));
+    }
+  }
+};
+
+template <int NORM>
+__device__ __forceinline__ void load_ref_scalar(const float* ref, const float* ref2, uint64_t e, float eps,
+                                                float& r1, float& r2) {
+  r1 = 0.f;
+  r2 = 1.f;
+  if (NORM == kNormSub || NORM == kNormComb) r1 = ref[e];
+  if (NORM == kNormQuot) r1 = clamp_ref(ref[e], eps);
+  if (NORM == kNormComb) r2 = clamp_ref(ref2[e], eps);
+}
+
+// Block maximum of MC per-thread values, then one atomic max per worker on the bit pattern
+// (non-negative floats order like unsigned integers, so the result is order independent).
+// A maximum below the smallest normal number is left as 0.
+template <int MC>
+__device__ __forceinline__ void block_max_to_global(float (&mx)[MC], uint32_t m0, uint32_t M,
+                                                    uint32_t* scale_bits) {
+  __shared__ float red[MC][kWavesPerBlock];
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) {
+    const float v = wave_max(mx[mm]);
+    if (lane == 0) red[mm][wave] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < MC && m0 + threadIdx.x < M) {
+    float v = red[threadIdx.x][0];
+#pragma unroll
+    for (int k = 1; k < kWavesPerBlock; ++k) v = fmaxf(v, red[threadIdx.x][k]);
+    if (v >= FLT_MIN) atomicMax(scale_bits + m0 + threadIdx.x, __float_as_uint(v));
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Pass 1: R_m = max_e |v_{m,e}|   (section "Gradient Compression": R = max_d |v_d|)
+// ------------------------------------------------------------------------------------------
+template <int NORM, int MC>
+__global__ __launch_bounds__(kBlock) void absmax_vec_kernel(const float4* __restrict__ g4,
+                                                            const float4* __restrict__ ref4,
+                                                            const float4* __restrict__ ref24,
+                                                            uint32_t* scale_bits, uint64_t nvec,
+                                                            uint32_t M, float eps) {
+  const uint32_t m0 = blockIdx.y * MC;
+  float mx[MC];
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) mx[mm] = 0.f;
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) {
+    RefTile<NORM> rt;
+    rt.load(ref4, ref24, i, eps);
+#pragma unroll
+    for (int mm = 0; mm < MC; ++mm) {
+      const uint32_t m = min(m0 + mm, M - 1);  // MC divides M in practice; the clamp only repeats a row
+      const float4 x = g4[(uint64_t)m * nvec + i];
+      const float a0 = fabsf(normalize<NORM>(x.x, rt.r1.x, rt.r2.x));
+      const float a1 = fabsf(normalize<NORM>(x.y, rt.r1.y, rt.r2.y));
+      const float a2 = fabsf(normalize<NORM>(x.z, rt.r1.z, rt.r2.z));
+      const float a3 = fabsf(normalize<NORM>(x.w, rt.r1.w, rt.r2.w));
+      mx[mm] = fmaxf(mx[mm], fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)));
+    }
+  }
+  block_max_to_global<MC>(mx, m0, M, scale_bits);
+}
+
+template <int NORM>
+__global__ __launch_bounds__(kBlock) void absmax_scalar_kernel(const float* __restrict__ g,
+                                                               const float* __restrict__ ref,
+                                                               const float* __restrict__ ref2,
+                                                               uint32_t* scale_bits, uint64_t d, uint32_t M,
+                                                               float eps) {
+  const uint32_t m = blockIdx.y;
+  float mx[1] = {0.f};
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x; e < d; e += stride) {
+    float r1, r2;
+    load_ref_scalar<NORM>(ref, ref2, e, eps, r1, r2);
+    mx[0] = fmaxf(mx[0], fabsf(normalize<NORM>(g[(uint64_t)m * d + e], r1, r2)));
+  }
+  block_max_to_global<1>(mx, m, M, scale_bits);
+}
+
+// ------------------------------------------------------------------------------------------
+// Pass 2: normalise, draw, round, sign, pack   (Algorithm 1: sample z, transmit sign (.) z and R)
+//
+// A wavefront owns 64 * 4 float4 = 1024 consecutive coordinates.  Load j of lane l covers
+// coordinates 256 j + 4 l .. + 3, so every load instruction is one contiguous 1 KiB.  The four
+// codes of a load form an 8-bit (ternary) or 16-bit (4-bit codes) fragment; fragment (j, l) is
+// fragment number 64 j + l of the wavefront's packed output, so writing fragments to LDS at that
+// index and reading LDS back as 32-bit words gives each lane whole words to store, contiguously.
+// ------------------------------------------------------------------------------------------
+template <int NORM, int BITS, int MC>
+__global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
+    const float4* __restrict__ g4, const float4* __restrict__ ref4, const float4* __restrict__ ref24,
+    const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words,
+    uint32_t M, float eps, uint32_t k0, uint32_t k1, uint32_t iter) {
+  constexpr int L = kLoadsPerLane;
+  constexpr int WPW = kWave * L * 4 * BITS / 32;  // packed words per wavefront tile
+  __shared__ uint32_t lds[kWavesPerBlock][WPW];
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const uint64_t wave_tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+  const uint64_t vec_base = wave_tile * (kWave * L);
+  const uint64_t word_base = wave_tile * WPW;
+
+  RefTile<NORM> rt[L];
+  uint64_t iv[L];
+  bool ok[L];
+#pragma unroll
+  for (int j = 0; j < L; ++j) {
+    iv[j] = vec_base + (uint64_t)j * kWave + lane;
+    ok[j] = iv[j] < nvec;
+    if (ok[j]) rt[j].load(ref4, ref24, iv[j], eps);
+  }
+
+  const uint32_t m0 = blockIdx.y * MC;
+#pragma unroll 1
+  for (int mm = 0; mm < MC; ++mm) {
+    const uint32_t m = m0 + mm;
+    if (m >= M) break;
+    const float R = scales[m];
+    uint32_t frag[L];
+#pragma unroll
+    for (int j = 0; j < L; ++j) frag[j] = 0u;
+    if (R != 0.f) {
+      const float inv_r = 1.0f / R;
+      const float4* row = g4 + (uint64_t)m * nvec;
+#pragma unroll
+      for (int j = 0; j < L; ++j) {
+        if (ok[j]) {
+          const float4 x = row[iv[j]];
+          const U32x4 rnd = philox4x32_10((uint32_t)iv[j], m, iter, 0u, k0, k1);
+          const uint32_t c0 = quantize_code<BITS>(normalize<NORM>(x.x, rt[j].r1.x, rt[j].r2.x), inv_r, rnd.x);
+          const uint32_t c1 = quantize_code<BITS>(normalize<NORM>(x.y, rt[j].r1.y, rt[j].r2.y), inv_r, rnd.y);
+          const uint32_t c2 = quantize_code<BITS>(normalize<NORM>(x.z, rt[j].r1.z, rt[j].r2.z), inv_r, rnd.z);
+          const uint32_t c3 = quantize_code<BITS>(normalize<NORM>(x.w, rt[j].r1.w, rt[j].r2.w), inv_r, rnd.w);
+          frag[j] = c0 | (c1 << BITS) | (c2 << (2 * BITS)) | (c3 << (3 * BITS));
+        }
+      }
+    }
+    if (BITS == 2) {
+      volatile uint8_t* b = reinterpret_cast<volatile uint8_t*>(&lds[wave][0]);
+#pragma unroll
+      for (int j = 0; j < L; ++j) b[j * kWave + lane] = (uint8_t)frag[j];
+    } else {
+      volatile uint16_t* h = reinterpret_cast<volatile uint16_t*>(&lds[wave][0]);
+#pragma unroll
+      for (int j = 0; j < L; ++j) h[j * kWave + lane] = (uint16_t)frag[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    uint32_t* out = codes + (uint64_t)m * words;
+    const volatile uint32_t* wsrc = &lds[wave][0];
+#pragma unroll
+    for (int k = 0; k < WPW / kWave; ++k) {
+      const uint64_t wi = word_base + (uint64_t)k * kWave + lane;
+      const uint32_t word = wsrc[k * kWave + lane];
+      if (wi < words) out[wi] = word;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+// Any d (rows need not be 16-byte aligned): one thread per packed word.
+template <int NORM, int BITS>
+__global__ __launch_bounds__(kBlock) void quantize_pack_scalar_kernel(
+    const float* __restrict__ g, const float* __restrict__ ref, const float* __restrict__ ref2,
+    const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t d, uint64_t words, uint32_t M,
+    float eps, uint32_t k0, uint32_t k1, uint32_t iter) {
+  constexpr int PER = 32 / BITS;
+  const uint32_t m = blockIdx.y;
+  const float R = scales[m];
+  const float inv_r = R != 0.f ? 1.0f / R : 0.f;
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t wi = (uint64_t)blockIdx.x * kBlock + threadIdx.x; wi < words; wi += stride) {
+    uint32_t word = 0u;
+    if (R != 0.f) {
+#pragma unroll 1
+      for (int q = 0; q < PER / 4; ++q) {
+        const uint64_t e0 = wi * PER + (uint64_t)q * 4;
+        if (e0 >= d) break;
+        const U32x4 rnd = philox4x32_10((uint32_t)(e0 >> 2), m, iter, 0u, k0, k1);
+        const uint32_t rw[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const uint64_t e = e0 + k;
+          if (e < d) {
+            float r1, r2;
+            load_ref_scalar<NORM>(ref, ref2, e, eps, r1, r2);
+            const float v = normalize<NORM>(g[(uint64_t)m * d + e], r1, r2);
+            word |= quantize_code<BITS>(v, inv_r, rw[k]) << ((q * 4 + k) * BITS);
+          }
+        }
+      }
+    }
+    codes[(uint64_t)m * words + wi] = word;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Server: decode, average over workers in worker order, de-normalise (Eq. 1 / Eq. 2), and
+// optionally w <- w - lr * v and reference <- v in the same pass.
+// ------------------------------------------------------------------------------------------
+constexpr int kScaleChunk = 256;
+
+template <int BITS>
+__device__ __forceinline__ void stage_scales(const float* __restrict__ scales, uint32_t m_base, uint32_t M,
+                                             float* sR, float* sStep) {
+  constexpr float S = (float)((1 << (BITS - 1)) - 1);
+  __syncthreads();
+  if (threadIdx.x < kScaleChunk && m_base + threadIdx.x < M) {
+    const float R = scales[m_base + threadIdx.x];
+    sR[threadIdx.x] = R;
+    sStep[threadIdx.x] = R / S;
+  }
+  __syncthreads();
+}
+
+template <int NORM, int BITS>
+__global__ __launch_bounds__(kBlock) void decode_vec_kernel(
+    const uint32_t* __restrict__ codes, const float* __restrict__ scales, const float4* ref4,
+    const float4* __restrict__ ref24, float4* __restrict__ vbar4, float4* __restrict__ w4, float4* refout4,
+    uint64_t nvec, uint64_t words, uint32_t M, float eps, float inv_m, float lr) {
+  __shared__ float sR[kScaleChunk], sStep[kScaleChunk];
+  using frag_t = typename std::conditional<BITS == 2, uint8_t, uint16_t>::type;
+  constexpr uint32_t MASK = (1u << BITS) - 1u;
+  const frag_t* __restrict__ frags = reinterpret_cast<const frag_t*>(codes);
+  const uint64_t row_frags = words * (32 / (4 * BITS));
+  const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool active = i < nvec;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (uint32_t m_base = 0; m_base < M; m_base += kScaleChunk) {
+    stage_scales<BITS>(scales, m_base, M, sR, sStep);
+    if (active) {
+      const uint32_t cnt = min((uint32_t)kScaleChunk, M - m_base);
+      const frag_t* p = frags + (uint64_t)m_base * row_frags + i;
+#pragma unroll 8
+      for (uint32_t mm = 0; mm < cnt; ++mm) {
+        const uint32_t f = p[(uint64_t)mm * row_frags];
+        const float R = sR[mm], step = sStep[mm];
+        acc.x = acc.x + decode_code<BITS>(f & MASK, R, step);
+        acc.y = acc.y + decode_code<BITS>((f >> BITS) & MASK, R, step);
+        acc.z = acc.z + decode_code<BITS>((f >> (2 * BITS)) & MASK, R, step);
+        acc.w = acc.w + decode_code<BITS>((f >> (3 * BITS)) & MASK, R, step);
+      }
+    }
+  }
+  if (!active) return;
+  RefTile<NORM> rt;
+  rt.load(ref4, ref24, i, eps);
+  float4 v;
+  v.x = denormalize<NORM>(acc.x * inv_m, rt.r1.x, rt.r2.x);
+  v.y = denormalize<NORM>(acc.y * inv_m, rt.r1.y, rt.r2.y);
+  v.z = denormalize<NORM>(acc.z * inv_m, rt.r1.z, rt.r2.z);
+  v.w = denormalize<NORM>(acc.w * inv_m, rt.r1.w, rt.r2.w);
+  vbar4[i] = v;
+  if (w4 != nullptr) {
+    float4 w = w4[i];
+    const float px = lr * v.x, py = lr * v.y, pz = lr * v.z, pw = lr * v.w;
+    w.x = w.x - px;
+    w.y = w.y - py;
+    w.z = w.z - pz;
+    w.w = w.w - pw;
+    w4[i] = w;
+  }
+  if (refout4 != nullptr) refout4[i] = v;
+}
+
+template <int NORM, int BITS>
+__global__ __launch_bounds__(kBlock) void decode_scalar_kernel(
+    const uint32_t* __restrict__ codes, const float* __restrict__ scales, const float* ref,
+    const float* __restrict__ ref2, float* __restrict__ vbar, float* __restrict__ w, float* refout, uint64_t d,
+    uint64_t words, uint32_t M, float eps, float inv_m, float lr) {
+  __shared__ float sR[kScaleChunk], sStep[kScaleChunk];
+  constexpr int PER = 32 / BITS;
+  constexpr uint32_t MASK = (1u << BITS) - 1u;
+  const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool active = e < d;
+  const uint64_t wi = e / PER;
+  const uint32_t sh = (uint32_t)(e % PER) * BITS;
+  float acc = 0.f;
+  for (uint32_t m_base = 0; m_base < M; m_base += kScaleChunk) {
+    stage_scales<BITS>(scales, m_base, M, sR, sStep);
+    if (active) {
+      const uint32_t cnt = min((uint32_t)kScaleChunk, M - m_base);
+      for (uint32_t mm = 0; mm < cnt; ++mm) {
+        const uint32_t word = codes[(uint64_t)(m_base + mm) * words + wi];
+        acc = acc + decode_code<BITS>((word >> sh) & MASK, sR[mm], sStep[mm]);
+      }
+    }
+  }
+  if (!active) return;
+  float r1, r2;
+  load_ref_scalar<NORM>(ref, ref2, e, eps, r1, r2);
+  const float v = denormalize<NORM>(acc * inv_m, r1, r2);
+  vbar[e] = v;
+  if (w != nullptr) {
+    const float p = lr * v;
+    w[e] = w[e] - p;
+  }
+  if (refout != nullptr) refout[e] = v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Launch geometry
+// ------------------------------------------------------------------------------------------
+inline uint32_t div_up_u32(uint64_t a, uint64_t b) {
+  const uint64_t q = (a + b - 1) / b;
+  return (uint32_t)(q > kMaxGridX ? kMaxGridX : q);
+}
+
+// Workers handled inside one workgroup: the largest of 8, 4, 2, 1 that divides M and still
+// leaves enough workgroups to fill 256 compute units.
+inline int pick_workers_per_block(uint32_t M, uint64_t tiles) {
+  int mc = 8;
+  while (mc > 1 && (M % mc != 0 || tiles * (M / mc) < 2048)) mc >>= 1;
+  return mc;
+}
+
+inline bool vec_ok(uint64_t d, const void* a, const void* b, const void* c) {
+  auto al = [](const void* p) { return p == nullptr || (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+  return d % 4 == 0 && al(a) && al(b) && al(c);
+}
+
+template <int NORM, int MC>
+hipError_t absmax_vec_launch(const CodecShape& c, const float* g, const float* gref, const float* gref2,
+                             uint32_t* bits, hipStream_t s) {
+  const uint64_t nvec = c.d / 4;
+  const uint32_t per_y = div_up_u32(nvec, kBlock);
+  const uint32_t gx = per_y < 4096u ? per_y : 4096u;
+  dim3 grid(gx, (c.M + MC - 1) / MC);
+  hipLaunchKernelGGL((absmax_vec_kernel<NORM, MC>), grid, dim3(kBlock), 0, s,
+                     reinterpret_cast<const float4*>(g), reinterpret_cast<const float4*>(gref),
+                     reinterpret_cast<const float4*>(gref2), bits, nvec, c.M, c.eps);
+  return hipGetLastError();
+}
+
+template <int NORM>
+hipError_t absmax_dispatch(const CodecShape& c, const float* g, const float* gref, const float* gref2,
+                           uint32_t* bits, hipStream_t s) {
+  if (vec_ok(c.d, g, gref, gref2)) {
+    const int mc = pick_workers_per_block(c.M, (c.d / 4 + kBlock - 1) / kBlock);
+    switch (mc) {
+      case 8: return absmax_vec_launch<NORM, 8>(c, g, gref, gref2, bits, s);
+      case 4: return absmax_vec_launch<NORM, 4>(c, g, gref, gref2, bits, s);
+      case 2: return absmax_vec_launch<NORM, 2>(c, g, gref, gref2, bits, s);
+      default: return absmax_vec_launch<NORM, 1>(c, g, gref, gref2, bits, s);
+    }
+  }
+  const uint32_t per_y = div_up_u32(c.d, kBlock);
+  dim3 grid(per_y < 4096u ? per_y : 4096u, c.M);
+  hipLaunchKernelGGL((absmax_scalar_kernel<NORM>), grid, dim3(kBlock), 0, s, g, gref, gref2, bits, c.d,
+                     c.M, c.eps);
+  return hipGetLastError();
+}
+
+template <int NORM, int BITS, int MC>
+hipError_t quantize_vec_launch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                               const float* gref2, const float* scales, uint32_t* codes, hipStream_t s) {
+  const uint64_t nvec = c.d / 4;
+  const uint64_t tiles = (nvec + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
+  dim3 grid((uint32_t)tiles, (c.M + MC - 1) / MC);
+  hipLaunchKernelGGL((quantize_pack_vec_kernel<NORM, BITS, MC>), grid, dim3(kBlock), 0, s,
+                     reinterpret_cast<const float4*>(g), reinterpret_cast<const float4*>(gref),
+                     reinterpret_cast<const float4*>(gref2), scales, codes, nvec, c.words, c.M, c.eps, c.k0,
+                     c.k1, iter);
+  return hipGetLastError();
+}
+
+template <int NORM, int BITS>
+hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                             const float* gref2, const float* scales, uint32_t* codes, hipStream_t s) {
+  if (vec_ok(c.d, g, gref, gref2)) {
+    const uint64_t tiles = (c.d / 4 + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
+    const int mc = pick_workers_per_block(c.M, tiles);
+    switch (mc) {
+      case 8: return quantize_vec_launch<NORM, BITS, 8>(c, iter, g, gref, gref2, scales, codes, s);
+      case 4: return quantize_vec_launch<NORM, BITS, 4>(c, iter, g, gref, gref2, scales, codes, s);
+      case 2: return quantize_vec_launch<NORM, BITS, 2>(c, iter, g, gref, gref2, scales, codes, s);
+      default: return quantize_vec_launch<NORM, BITS, 1>(c, iter, g, gref, gref2, scales, codes, s);
+    }
+  }
+  const uint32_t per_y = div_up_u32(c.words, kBlock);
+  dim3 grid(per_y < 65536u ? per_y : 65536u, c.M);
+  hipLaunchKernelGGL((quantize_pack_scalar_kernel<NORM, BITS>), grid, dim3(kBlock), 0, s, g, gref, gref2,
+                     scales, codes, c.d, c.words, c.M, c.eps, c.k0, c.k1, iter);
+  return hipGetLastError();
+}
+
+template <int NORM, int BITS>
+hipError_t decode_dispatch(const CodecShape& c, const uint32_t* codes, const float* scales, const float* gref,
+                           const float* gref2, float* vbar, float* w, float lr, float* ref_out,
+                           hipStream_t s) {
+  const float inv_m = 1.0f / (float)c.M;
+  if (vec_ok(c.d, gref, gref2, vbar) && vec_ok(c.d, w, ref_out, nullptr)) {
+    const uint64_t nvec = c.d / 4;
+    const uint64_t blocks = (nvec + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL((decode_vec_kernel<NORM, BITS>), dim3((uint32_t)blocks), dim3(kBlock), 0, s, codes,
+                       scales, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2),
+                       reinterpret_cast<float4*>(vbar), reinterpret_cast<float4*>(w),
+                       reinterpret_cast<float4*>(ref_out), nvec, c.words, c.M, c.eps, inv_m, lr);
+    return hipGetLastError();
+  }
+  const uint64_t blocks = (c.d + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL((decode_scalar_kernel<NORM, BITS>), dim3((uint32_t)blocks), dim3(kBlock), 0, s, codes,
+                     scales, gref, gref2, vbar, w, ref_out, c.d, c.words, c.M, c.eps, inv_m, lr);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const uint32_t gx = div_up_u32(n, kBlock);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(gx < 8192u ? gx : 8192u), dim3(kBlock), 0, s, p, n, value);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_f32(float* dst, const float* src, uint64_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  if (vec_ok(n, dst, src, nullptr)) {
+    const uint32_t gx = div_up_u32(n / 4, kBlock);
+    hipLaunchKernelGGL(copy_f32x4_kernel, dim3(gx < 16384u ? gx : 16384u), dim3(kBlock), 0, s,
+                       reinterpret_cast<float4*>(dst), reinterpret_cast<const float4*>(src), n / 4);
+  } else {
+    const uint32_t gx = div_up_u32(n, kBlock);
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(gx < 16384u ? gx : 16384u), dim3(kBlock), 0, s, dst, src, n);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_rng_draws(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t worker, uint32_t stream,
+                            uint64_t first, uint64_t count, uint32_t* out, hipStream_t s) {
+  if (count == 0) return hipSuccess;
+  const uint32_t gx = div_up_u32(count, kBlock);
+  hipLaunchKernelGGL(rng_draws_kernel, dim3(gx < 8192u ? gx : 8192u), dim3(kBlock), 0, s, k0, k1, iter,
+                     worker, stream, first, count, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_absmax(const CodecShape& c, const float* g, const float* gref, const float* gref2,
+                         float* scales, hipStream_t s) {
+  uint32_t* bits = reinterpret_cast<uint32_t*>(scales);
+  switch (c.norm) {
+    case kNormNone: return absmax_dispatch<kNormNone>(c, g, nullptr, nullptr, bits, s);
+    case kNormSub: return absmax_dispatch<kNormSub>(c, g, gref, nullptr, bits, s);
+    case kNormQuot: return absmax_dispatch<kNormQuot>(c, g, gref, nullptr, bits, s);
+    default: return absmax_dispatch<kNormComb>(c, g, gref, gref2, bits, s);
+  }
+}
+
+hipError_t launch_quantize_pack(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                                const float* gref2, const float* scales, uint32_t* codes, hipStream_t s) {
+#define TNG_Q(NORM, R1, R2)                                                                    \
+  return c.bits == 2 ? quantize_dispatch<NORM, 2>(c, iter, g, R1, R2, scales, codes, s)        \
+                     : quantize_dispatch<NORM, 4>(c, iter, g, R1, R2, scales, codes, s)
+  switch (c.norm) {
+    case kNormNone: TNG_Q(kNormNone, nullptr, nullptr);
+    case kNormSub: TNG_Q(kNormSub, gref, nullptr);
+    case kNormQuot: TNG_Q(kNormQuot, gref, nullptr);
+    default: TNG_Q(kNormComb, gref, gref2);
+  }
+#undef TNG_Q
+}
+
+hipError_t launch_decode(const CodecShape& c, const uint32_t* codes, const float* scales, const float* gref,
+                         const float* gref2, float* vbar, float* w, float lr, float* ref_out, hipStream_t s) {
+#define TNG_D(NORM, R1, R2)                                                                          \
+  return c.bits == 2 ? decode_dispatch<NORM, 2>(c, codes, scales, R1, R2, vbar, w, lr, ref_out, s)   \
+                     : decode_dispatch<NORM, 4>(c, codes, scales, R1, R2, vbar, w, lr, ref_out, s)
+  switch (c.norm) {
+    case kNormNone: TNG_D(kNormNone, nullptr, nullptr);
+    case kNormSub: TNG_D(kNormSub, gref, nullptr);
+    case kNormQuot: TNG_D(kNormQuot, gref, nullptr);
+    default: TNG_D(kNormComb, gref, gref2);
+  }
+#undef TNG_D
+}
+
+}  // namespace tng

@@ -1,0 +1,117 @@
+// Device-side helpers shared by the libtng kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tng {
+
+constexpr int kNormNone = 0;
+constexpr int kNormSub = 1;
+constexpr int kNormQuot = 2;
+constexpr int kNormComb = 3;
+
+constexpr int kBlock = 256;  // threads per workgroup: 4 wavefronts of 64
+constexpr int kWave = 64;
+
+struct U32x4 {
+  uint32_t x, y, z, w;
+};
+
+// Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).  One round sends the counter
+// (c0,c1,c2,c3) to (hi(B*c2)^c1^k0, lo(B*c2), hi(A*c0)^c3^k1, lo(A*c0)); the key moves by two
+// Weyl increments between rounds.  The key is wave-uniform, so the round keys live in SGPRs.
+__device__ __forceinline__ U32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1) {
+  constexpr uint32_t A = 0xD2511F53u, B = 0xCD9E8D57u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t pa = (uint64_t)A * c0;
+    const uint64_t pb = (uint64_t)B * c2;
+    const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)pb;
+    c3 = (uint32_t)pa;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return U32x4{c0, c1, c2, c3};
+}
+
+// Uniform on the 24-bit grid {0, 2^-24, ..., 1 - 2^-24}; both steps are exact in binary32.
+__device__ __forceinline__ float uniform24(uint32_t word) {
+  return (float)(word >> 8) * 0x1p-24f;
+}
+
+// Reference made safe to divide by (Eq. 2): |r| < eps -> copysign(eps, r).
+__device__ __forceinline__ float clamp_ref(float r, float eps) {
+  return fabsf(r) < eps ? copysignf(eps, r) : r;
+}
+
+// The vector handed to the coder.  r1 is g~ (SUB, COMB) or the clamped g~ (QUOT);
+// r2 is the clamped g~' (COMB only).
+template <int NORM>
+__device__ __forceinline__ float normalize(float g, float r1, float r2) {
+  if (NORM == kNormSub) return g - r1;
+  if (NORM == kNormQuot) return g / r1;
+  if (NORM == kNormComb) return (g - r1) / r2;
+  return g;
+}
+
+template <int NORM>
+__device__ __forceinline__ float denormalize(float mean, float r1, float r2) {
+  if (NORM == kNormSub) return r1 + mean;
+  if (NORM == kNormQuot) return r1 * mean;
+  if (NORM == kNormComb) {
+    const float p = r2 * mean;
+    return p + r1;
+  }
+  return mean;
+}
+
+// Stochastic rounding of |v|/R onto {0, 1/S, ..., 1} (section "Gradient Compression"; S = 1 is the
+// ternary coder with P(z = 1) = |v|/R).  Returns level | sign << (BITS-1), sign cleared at level 0.
+template <int BITS>
+__device__ __forceinline__ uint32_t quantize_code(float v, float inv_r, uint32_t word) {
+  constexpr int S = (1 << (BITS - 1)) - 1;
+  const float a = fabsf(v);
+  const float t = fminf(a * inv_r, 1.0f);
+  const float x = t * (float)S;
+  const int lo = (int)x;
+  const float f = x - (float)lo;
+  const uint32_t level = (uint32_t)lo + (uniform24(word) < f ? 1u : 0u);
+  const uint32_t neg = (v < 0.0f && level != 0u) ? 1u : 0u;
+  return level | (neg << (BITS - 1));
+}
+
+// Value of one code: +-(R/S) * level, level S giving R itself; the unused pattern
+// "sign with level 0" decodes to +0.
+template <int BITS>
+__device__ __forceinline__ float decode_code(uint32_t code, float r, float step) {
+  constexpr uint32_t S = (1u << (BITS - 1)) - 1u;
+  const uint32_t level = code & S;
+  const bool neg = ((code >> (BITS - 1)) & 1u) != 0u;
+  float mag;
+  if (BITS == 2) {
+    mag = level ? r : 0.0f;
+  } else {
+    mag = (level == S) ? r : step * (float)level;
+  }
+  return (neg && level != 0u) ? -mag : mag;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+  return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+}  // namespace tng

@@ -1,0 +1,55 @@
+// Host-side launch interface between the C-ABI layer and the HIP kernels of libtng.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tng {
+
+struct CodecShape {
+  uint64_t d;      // elements per worker
+  uint64_t words;  // packed 32-bit words per worker row
+  uint32_t M;      // workers
+  int bits;        // 2 or 4
+  int norm;        // kNorm*
+  float eps;       // clamp of the divisor reference
+  uint32_t k0, k1; // Philox key (seed low, seed high)
+};
+
+hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t s);
+hipError_t launch_copy_f32(float* dst, const float* src, uint64_t n, hipStream_t s);
+hipError_t launch_rng_draws(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t worker, uint32_t stream,
+                            uint64_t first, uint64_t count, uint32_t* out, hipStream_t s);
+
+// scales[m] = max_e |normalize(g[m][e])|, 0 when below FLT_MIN.  scales must hold zeros on entry.
+hipError_t launch_absmax(const CodecShape& c, const float* g, const float* gref, const float* gref2,
+                         float* scales, hipStream_t s);
+hipError_t launch_quantize_pack(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                                const float* gref2, const float* scales, uint32_t* codes, hipStream_t s);
+// vbar = denorm(mean_m decode).  If w != nullptr also w -= lr * vbar; if ref_out != nullptr also
+// ref_out = vbar (ref_out may alias gref).
+hipError_t launch_decode(const CodecShape& c, const uint32_t* codes, const float* scales,
+                         const float* gref, const float* gref2, float* vbar, float* w, float lr,
+                         float* ref_out, hipStream_t s);
+
+struct LogregData {
+  const float* const* X;        // device table [M] of dense shards (dense problem)
+  const int64_t* const* rowptr; // device tables [M] (CSR problem)
+  const int32_t* const* col;
+  const float* const* val;
+  const float* const* y;        // device table [M]
+  const uint64_t* n_rows;       // device [M]
+};
+
+hipError_t launch_minibatch_indices(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t M, uint32_t batch,
+                                    const uint64_t* n_rows, uint32_t* idx, hipStream_t s);
+hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
+                                    const uint32_t* idx, float* resid, const float* w, float* g,
+                                    hipStream_t s);
+hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
+                                  const uint32_t* idx, float* resid, const float* w, float* g,
+                                  hipStream_t s);
+hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, float* g,
+                                  hipStream_t s);
+
+}  // namespace tng

@@ -1,0 +1,148 @@
+"""GPU parity of tng_normalize_encode / tng_decode_aggregate / tng_update_reference against
+the oracle: packed codes and scales bit-exact, decoded averages bit-exact (contract: 1e-5)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tng_oracle as O
+from gpu_util import DEV, buffers, make_ctx, oracle_cfg, say, u32
+from paper_1901_08227_amd import binding as B
+from paper_1901_08227_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+NORMS = [B.NORM_NONE, B.NORM_SUB, B.NORM_QUOT, B.NORM_COMB]
+
+
+def _inputs(M, d, seed, scale=1.0):
+    g, gref = synth.codec_inputs(M, d, seed, device=DEV)
+    gref2 = torch.randn(d, generator=torch.Generator(device=DEV).manual_seed(seed + 1), device=DEV) + 2.0
+    return g * scale, gref * scale, gref2
+
+
+def _check_encode_decode(ctx, it, g, gref, gref2, tag):
+    say(f"codec case {tag}: d={ctx.d} M={ctx.M} bits={ctx.bits} norm={ctx.cfg.norm} it={it}")
+    buf = buffers(ctx)
+    if ctx.cfg.norm == B.NORM_COMB:
+        ctx.set_second_reference(gref2)
+    ctx.normalize_encode(it, g, gref, buf["codes"], buf["scales"])
+    ctx.decode_aggregate(buf["codes"], buf["scales"], gref, buf["vbar"])
+    torch.cuda.synchronize()
+    cfg = oracle_cfg(ctx)
+    gh, rh, r2h = g.cpu().numpy(), gref.cpu().numpy(), gref2.cpu().numpy()
+    codes, scales = O.normalize_encode(cfg, it, gh, rh, r2h)
+    assert np.array_equal(buf["scales"].cpu().numpy(), scales), f"{tag}: scales"
+    got = u32(buf["codes"])
+    if not np.array_equal(got, codes):
+        bad = np.argwhere(got != codes)
+        raise AssertionError(f"{tag}: {len(bad)} packed words differ, first at {bad[0]}: "
+                             f"{got[tuple(bad[0])]:#x} vs {codes[tuple(bad[0])]:#x}")
+    vbar = O.decode_aggregate(cfg, codes, scales, rh, ctx.d, r2h)
+    assert np.array_equal(buf["vbar"].cpu().numpy(), vbar), f"{tag}: decoded average"
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("norm", NORMS)
+def test_tail_sizes(bits, norm):
+    for d in [1, 3, 4, 5, 15, 16, 17, 63, 64, 65, 1000, 1024, 4099]:
+        for M in ([1, 3] if d > 100 else [2]):
+            g, gref, gref2 = _inputs(M, d, seed=d + M)
+            ctx = make_ctx(d, M, bits, norm, seed=d * 7 + M)
+            _check_encode_decode(ctx, 5, g, gref, gref2, "tail")
+            ctx.close()
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("norm", NORMS)
+def test_several_tiles_and_ragged_last_tile(bits, norm):
+    # vector path: tiles of 4096 coordinates per workgroup; 20 tiles + a ragged tail, M not a power of two
+    for d, M in [(4096 * 20 + 4 * 37, 3), (4096 * 3, 8), (4096 * 5 + 8, 16), (4096 * 2 + 12, 6)]:
+        g, gref, gref2 = _inputs(M, d, seed=d % 1000 + M)
+        ctx = make_ctx(d, M, bits, norm, seed=99)
+        _check_encode_decode(ctx, 1, g, gref, gref2, "tiles")
+        ctx.close()
+
+
+def test_many_workers_and_chunked_scales():
+    d, M = 2048, 300          # decode stages scales in chunks of 256 workers
+    g, gref, gref2 = _inputs(M, d, seed=4)
+    for bits in (2, 4):
+        ctx = make_ctx(d, M, bits, B.NORM_SUB, seed=5)
+        _check_encode_decode(ctx, 2, g, gref, gref2, "many workers")
+        ctx.close()
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_degenerate_inputs(bits):
+    d, M = 4096 + 16, 3
+    g, gref, gref2 = _inputs(M, d, seed=8)
+    # a worker whose gradient equals the reference: R = 0 (Eq. 1) / R = 1, top level (Eq. 2)
+    g[1] = gref
+    for norm in (B.NORM_SUB, B.NORM_QUOT):
+        ctx = make_ctx(d, M, bits, norm, seed=3)
+        _check_encode_decode(ctx, 0, g, gref, gref2, "g == gref")
+        ctx.close()
+    # all-zero gradients and zero reference
+    z = torch.zeros_like(g)
+    ctx = make_ctx(d, M, bits, B.NORM_SUB, seed=3)
+    _check_encode_decode(ctx, 0, z, torch.zeros_like(gref), gref2, "zeros")
+    # subnormal maximum (scale taken as 0) and barely normal maximum
+    tiny = torch.zeros_like(g)
+    tiny[0, 7] = 1e-39
+    tiny[2, 9] = -1.2e-38
+    _check_encode_decode(ctx, 0, tiny, torch.zeros_like(gref), gref2, "tiny")
+    ctx.close()
+    # reference entries that are zero, negative zero and below the clamp (Eq. 2)
+    gref_z = gref.clone()
+    gref_z[0], gref_z[1], gref_z[2], gref_z[3] = 0.0, -0.0, 3e-9, -3e-9
+    for norm in (B.NORM_QUOT, B.NORM_COMB):
+        ctx = make_ctx(d, M, bits, norm, seed=3)
+        _check_encode_decode(ctx, 0, g * 1e-9, gref_z, gref_z.clone(), "clamped reference")
+        ctx.close()
+    # huge and tiny magnitudes
+    ctx = make_ctx(d, M, bits, B.NORM_SUB, seed=3)
+    _check_encode_decode(ctx, 0, g * 1e30, gref * 1e30, gref2, "huge")
+    _check_encode_decode(ctx, 0, g * 1e-30, gref * 1e-30, gref2, "small")
+    ctx.close()
+
+
+def test_codes_do_not_depend_on_call_history_and_change_with_iteration_and_seed():
+    d, M = 4096 * 4, 4
+    g, gref, gref2 = _inputs(M, d, seed=1)
+    ctx = make_ctx(d, M, 2, B.NORM_SUB, seed=11)
+    a, b, c = buffers(ctx), buffers(ctx), buffers(ctx)
+    ctx.normalize_encode(3, g, gref, a["codes"], a["scales"])
+    ctx.normalize_encode(4, g, gref, c["codes"], c["scales"])
+    ctx.normalize_encode(3, g, gref, b["codes"], b["scales"])
+    torch.cuda.synchronize()
+    assert torch.equal(a["codes"], b["codes"]) and torch.equal(a["scales"], b["scales"])
+    assert not torch.equal(a["codes"], c["codes"]) and torch.equal(a["scales"], c["scales"])
+    other = make_ctx(d, M, 2, B.NORM_SUB, seed=12)
+    other.normalize_encode(3, g, gref, c["codes"], c["scales"])
+    torch.cuda.synchronize()
+    assert not torch.equal(a["codes"], c["codes"])
+    # worker rows with identical gradients still get different codes (worker index is in the counter)
+    g2 = g.clone()
+    g2[1] = g2[0]
+    ctx.normalize_encode(3, g2, gref, a["codes"], a["scales"])
+    torch.cuda.synchronize()
+    assert not torch.equal(a["codes"][0], a["codes"][1])
+    ctx.close()
+    other.close()
+
+
+def test_update_reference_rule():
+    d = 1000
+    vbar = torch.randn(d, device=DEV)
+    for policy, period, it, expect_copy in [(B.REF_LAST_AVG, 1, 0, True), (B.REF_LAST_AVG, 16, 14, False),
+                                            (B.REF_LAST_AVG, 16, 15, True), (B.REF_LAST_AVG, 16, 31, True),
+                                            (B.REF_ZERO, 1, 0, False)]:
+        ctx = make_ctx(d, 2, 2, B.NORM_SUB, ref_policy=policy, ref_period=period)
+        gref = torch.zeros(d, device=DEV)
+        ctx.update_reference(it, vbar, gref)
+        torch.cuda.synchronize()
+        cfg = oracle_cfg(ctx)
+        ref = O.update_reference(cfg, it, vbar.cpu().numpy(), np.zeros(d, dtype=np.float32))
+        assert np.array_equal(gref.cpu().numpy(), ref)
+        assert torch.equal(gref, vbar) == expect_copy
+        ctx.close()
