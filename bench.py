@@ -139,6 +139,9 @@ def main():
     ap.add_argument("--cpu-log2d", type=int, default=25, help="log2 of the oracle's sample size per worker")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-variants", action="store_true", help="time only the headline variant")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain copy kernel of known size (d floats read, d floats written) three "
+                         "times, as the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (the workers are simulated on it); --gpus above 1 is not supported")
@@ -167,6 +170,15 @@ def main():
                              "fp32_in_GBps": round(r["fp32_in_GBps"], 1),
                              "two_pass_GBps": round(r["two_pass_GBps"], 1),
                              "kernel_ms": {k: round(v["ms"], 4) for k, v in r["kernels"].items()}})
+
+    if args.copy_calibration:
+        ctx = B.Context(d=d, M=M, bits=2, norm=B.NORM_SUB, ref_policy=B.REF_LAST_AVG, ref_period=1, device=dev)
+        dst = torch.empty(d, device=dev)
+        for _ in range(3):
+            ctx.update_reference(0, gref, dst)   # copy_f32x4_kernel: reads 4 d bytes, writes 4 d bytes
+        torch.cuda.synchronize()
+        ctx.close()
+        log(f"copy calibration: 3 launches of the plain copy kernel, {4 * d} bytes read and written each")
 
     dom_name = max(head["kernels"], key=lambda k: head["kernels"][k]["ms"])
     dom = head["kernels"][dom_name]
