@@ -129,6 +129,27 @@ def cpu_baseline(g, gref, seed, sample_d):
     }
 
 
+def measured_traffic(kernel, M, d, bits, norm_name):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when
+    the summary is for another workload or the kernel sources have changed since it was taken."""
+    import glob
+    import hashlib
+
+    path = os.path.join(ROOT, "profiles", "codec_M8_d2p27_ternary_sub_hbm_traffic.json")
+    try:
+        rec = json.load(open(path))
+    except OSError:
+        return None
+    if rec.get("workload") != f"M={M} d=2^{d.bit_length() - 1} bits={bits} norm={norm_name}":
+        return None
+    h = hashlib.sha256()
+    for fn in sorted(glob.glob(os.path.join(ROOT, "paper_1901_08227_amd", "csrc", "*"))):
+        h.update(open(fn, "rb").read())
+    if h.hexdigest() != rec.get("kernel_source_sha256"):
+        return None
+    return rec["traffic_bytes_per_launch"].get(kernel)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -204,7 +225,9 @@ def main():
         "kernel_GBps": {k: round(v["GBps"], 1) for k, v in head["kernels"].items()},
         "variants": variants,
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(dom["GBps"], 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None},
+                     "unit": "GB/s", "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4),
+                     "algorithmic_bytes_per_launch": dom["bytes"],
+                     "traffic": measured_traffic(dom_name, M, d, 2, "sub")},
     }
     if not args.no_cpu:
         log("timing the oracle on the host")
