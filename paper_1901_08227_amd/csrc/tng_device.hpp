@@ -18,6 +18,28 @@ struct U32x4 {
   uint32_t x, y, z, w;
 };
 
+// Streaming (non-temporal) 16-byte accesses: data that is touched once per kernel.
+typedef float v4f_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4 load_stream(const float4* p) {
+  const v4f_t v = __builtin_nontemporal_load(reinterpret_cast<const v4f_t*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ void store_stream(float4* p, const float4& x) {
+  v4f_t v;
+  v.x = x.x;
+  v.y = x.y;
+  v.z = x.z;
+  v.w = x.w;
+  __builtin_nontemporal_store(v, reinterpret_cast<v4f_t*>(p));
+}
+
+// a ^ b ^ c in one instruction (three-input bitwise op of gfx950, truth table 0x96).
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 // Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).  One round sends the counter
 // (c0,c1,c2,c3) to (hi(B*c2)^c1^k0, lo(B*c2), hi(A*c0)^c3^k1, lo(A*c0)); the key moves by two
 // Weyl increments between rounds.  The key is wave-uniform, so the round keys live in SGPRs.
@@ -28,8 +50,8 @@ __device__ __forceinline__ U32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
   for (int r = 0; r < 10; ++r) {
     const uint64_t pa = (uint64_t)A * c0;
     const uint64_t pb = (uint64_t)B * c2;
-    const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1, k0);
+    const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3, k1);
     c1 = (uint32_t)pb;
     c3 = (uint32_t)pa;
     c0 = n0;
@@ -76,6 +98,13 @@ __device__ __forceinline__ float denormalize(float mean, float r1, float r2) {
 template <int BITS>
 __device__ __forceinline__ uint32_t quantize_code(float v, float inv_r, uint32_t word) {
   constexpr int S = (1 << (BITS - 1)) - 1;
+  if (BITS == 2) {
+    // S = 1: x = min(|v|/R, 1) has floor 1 and fraction 0 when it reaches 1, else floor 0 and
+    // fraction x, so level = [u < |v| * inv_r] without the clamp (u < 1 always): the same bits
+    // as the general formula below, in fewer operations.
+    const uint32_t level = uniform24(word) < fabsf(v) * inv_r ? 1u : 0u;
+    return level | (((__float_as_uint(v) >> 31) & level) << 1);  // -0 has level 0, so its sign is dropped
+  }
   const float a = fabsf(v);
   const float t = fminf(a * inv_r, 1.0f);
   const float x = t * (float)S;
