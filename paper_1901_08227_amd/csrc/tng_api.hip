@@ -17,6 +17,7 @@ struct tng_ctx {
   uint32_t* idx;          // [M][batch] minibatch row ids
   float* resid;           // [M][batch] sigma(z) - y
   const void** tables;    // 5 pointer tables of M entries: X|rowptr, col, val, y, and n_rows
+  float* partials;        // [kAbsmaxMaxBlocks][M] partial maxima of the scale pass
   bool have_dense, have_csr;
   const float* noise;     // Rosenbrock noise, may be null
   const float* gref2;     // second reference of the combined normalisation
@@ -48,7 +49,7 @@ bool config_valid(const tng_config* c) {
 }
 
 struct Partition {
-  size_t idx_off, resid_off, tables_off, total;
+  size_t idx_off, resid_off, tables_off, partials_off, total;
 };
 
 Partition partition(const tng_config* c) {
@@ -62,7 +63,9 @@ Partition partition(const tng_config* c) {
   off += round_up(mb * sizeof(float));
   p.tables_off = off;
   off += round_up(logreg ? (size_t)c->M * 5 * sizeof(void*) : 0);
-  p.total = off < kAlign ? kAlign : off;
+  p.partials_off = off;
+  off += round_up((size_t)tng::kAbsmaxMaxBlocks * c->M * sizeof(float));
+  p.total = off;
   return p;
 }
 
@@ -94,10 +97,8 @@ inline void mark(tng_ctx* ctx, uint64_t call, int which) {
 tng_status encode_impl(tng_ctx* ctx, uint32_t iter, const float* g, const float* gref, uint32_t* codes,
                        float* scales) {
   const uint64_t call = ctx->enc_calls++;
-  hipError_t e = tng::launch_fill_u32(reinterpret_cast<uint32_t*>(scales), ctx->cfg.M, 0u, ctx->stream);
-  if (e != hipSuccess) return TNG_ERR_HIP;
   mark(ctx, call, 0);
-  e = tng::launch_absmax(ctx->shape, g, gref, ctx->gref2, scales, ctx->stream);
+  hipError_t e = tng::launch_absmax(ctx->shape, g, gref, ctx->gref2, ctx->partials, scales, ctx->stream);
   if (e != hipSuccess) return TNG_ERR_HIP;
   mark(ctx, call, 1);
   e = tng::launch_quantize_pack(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, ctx->stream);
@@ -228,6 +229,7 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->idx = reinterpret_cast<uint32_t*>(base + p.idx_off);
   ctx->resid = reinterpret_cast<float*>(base + p.resid_off);
   ctx->tables = reinterpret_cast<const void**>(base + p.tables_off);
+  ctx->partials = reinterpret_cast<float*>(base + p.partials_off);
   ctx->have_dense = ctx->have_csr = false;
   ctx->noise = nullptr;
   ctx->gref2 = nullptr;

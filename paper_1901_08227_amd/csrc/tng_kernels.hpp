@@ -21,9 +21,13 @@ hipError_t launch_copy_f32(float* dst, const float* src, uint64_t n, hipStream_t
 hipError_t launch_rng_draws(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t worker, uint32_t stream,
                             uint64_t first, uint64_t count, uint32_t* out, hipStream_t s);
 
-// scales[m] = max_e |normalize(g[m][e])|, 0 when below FLT_MIN.  scales must hold zeros on entry.
+// Workgroups (per worker group) of the scale pass; each leaves one partial maximum per worker.
+constexpr uint32_t kAbsmaxMaxBlocks = 4096;
+
+// scales[m] = max_e |normalize(g[m][e])|, 0 when below FLT_MIN.  partials: device scratch of
+// kAbsmaxMaxBlocks * M floats.  Two launches: partial maxima per workgroup, then one reduction.
 hipError_t launch_absmax(const CodecShape& c, const float* g, const float* gref, const float* gref2,
-                         float* scales, hipStream_t s);
+                         float* partials, float* scales, hipStream_t s);
 hipError_t launch_quantize_pack(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
                                 const float* gref2, const float* scales, uint32_t* codes, hipStream_t s);
 // vbar = denorm(mean_m decode).  If w != nullptr also w -= lr * vbar; if ref_out != nullptr also
