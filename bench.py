@@ -129,6 +129,91 @@ def cpu_baseline(g, gref, seed, sample_d):
     }
 
 
+def time_steps(torch, ctx, state, steps, warmup, per_step=None):
+    """Times `steps` calls of tng_step (whole iteration); returns ms per step."""
+    w, gref, g, codes, scales, vbar = state
+    for it in range(warmup):
+        if per_step:
+            per_step(it)
+        ctx.step(it, w, gref, g, codes, scales, vbar)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for it in range(warmup, warmup + steps):
+        if per_step:
+            per_step(it)
+        ctx.step(it, w, gref, g, codes, scales, vbar)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def step_state(torch, ctx, w0):
+    dev = w0.device
+    return (w0.clone(), torch.zeros(ctx.d, device=dev), torch.empty((ctx.M, ctx.d), device=dev),
+            torch.empty((ctx.M, ctx.words), dtype=torch.int32, device=dev), torch.empty(ctx.M, device=dev),
+            torch.empty(ctx.d, device=dev))
+
+
+def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup):
+    """tng_step (local gradient + encode + decode + update + reference refresh) on the four training
+    workloads.  The two large logistic workloads keep their per-step shape (d, M, minibatch, density) but
+    hold fewer rows per worker than described: a step touches only the minibatch rows, so its traffic
+    does not depend on the shard size."""
+    out = []
+
+    def record(name, ms, algo_bytes, note):
+        out.append({"workload": name, "ms_per_step": round(ms, 4), "steps_per_s": round(1e3 / ms, 1),
+                    "algorithmic_GBps": round(algo_bytes / (ms * 1e-3) / 1e9, 1),
+                    "pct_hbm_peak": round(100 * algo_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2), "note": note})
+
+    # small dense logistic regression: latency bound
+    M, n, d, batch = 4, 2000, 1000, 64
+    X, y, _ = synth.logreg_dense(M, n, d, seed=0, device=dev)
+    ctx = B.Context(d=d, M=M, bits=2, norm=B.NORM_SUB, seed=0, lr=0.1, batch=batch, problem=B.PROB_LOGREG_DENSE, device=dev)
+    ctx.set_logreg_dense([X[m] for m in range(M)], [y[m] for m in range(M)])
+    ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), steps * 4, warmup)
+    record("dense logistic d=1000 M=4 B=64 ternary sub", ms, 2 * 4 * M * batch * d + 2 * (4 * M * d) + M * ctx.words * 8 + 24 * d,
+           "launch-latency bound")
+    ctx.close()
+    del X, y
+
+    # Rosenbrock chain
+    M, d = 8, 1 << 20
+    ctx = B.Context(d=d, M=M, bits=2, norm=B.NORM_SUB, seed=1, lr=1e-5, problem=B.PROB_ROSENBROCK, device=dev)
+    noises = [synth.gradient_noise(M, d, 1, it, variance=0.01, device=dev) for it in range(8)]
+    ms = time_steps(torch, ctx, step_state(torch, ctx, synth.rosenbrock_start(d, 1, device=dev)), steps, warmup,
+                    per_step=lambda it: ctx.set_noise(noises[it % 8]))
+    record("Rosenbrock chain d=2^20 M=8 ternary sub", ms, 4 * M * d * 2 + 4 * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
+           "noise read + g write + two encode passes + decode/update")
+    ctx.close()
+    del noises
+
+    # wide dense logistic regression, quotient normalisation
+    M, n, d, batch = 16, 8192, 1 << 16, 256
+    X = [torch.randn((n, d), device=dev, generator=torch.Generator(device=dev).manual_seed(m)) for m in range(M)]
+    y = [(torch.rand(n, device=dev) < 0.5).float() for _ in range(M)]
+    ctx = B.Context(d=d, M=M, bits=2, norm=B.NORM_QUOT, seed=2, lr=0.1, batch=batch, problem=B.PROB_LOGREG_DENSE, device=dev)
+    ctx.set_logreg_dense(X, y)
+    ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), steps, warmup)
+    record("dense logistic d=2^16 M=16 B=256 2-bit quot", ms, 2 * 4 * M * batch * d + 3 * (4 * M * d) + M * ctx.words * 8 + 24 * d,
+           f"{n} rows per worker held (per-step traffic is that of the minibatch rows, read twice)")
+    ctx.close()
+    del X, y
+
+    # sparse logistic regression at d = 2^24
+    M, n, d, batch = 64, 2048, 1 << 24, 512
+    nnz_row = round(1e-3 * d)
+    shards, _ = synth.logreg_csr(M, n, d, nnz_row, seed=3, device=dev)
+    ctx = B.Context(d=d, M=M, bits=4, norm=B.NORM_SUB, seed=3, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR, device=dev)
+    ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), max(steps // 2, 5), max(warmup // 2, 2))
+    nnz = M * batch * nnz_row
+    record("sparse logistic d=2^24 M=64 B=512 nnz/row=16777 4-bit sub", ms,
+           2 * 8 * nnz + 4 * M * d + 2 * 4 * nnz + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
+           f"{n} rows per worker held; bytes: CSR rows read twice, g zero-fill, atomic read-modify-write, two encode passes, decode/update")
+    ctx.close()
+    return out
+
+
 def measured_traffic(kernel, M, d, bits, norm_name):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when
     the summary is for another workload or the kernel sources have changed since it was taken."""
@@ -160,6 +245,8 @@ def main():
     ap.add_argument("--cpu-log2d", type=int, default=25, help="log2 of the oracle's sample size per worker")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-variants", action="store_true", help="time only the headline variant")
+    ap.add_argument("--no-codec", action="store_true", help="skip the encode/decode microbenchmark (development aid)")
+    ap.add_argument("--no-steps", action="store_true", help="skip the whole-iteration (tng_step) workloads")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain copy kernel of known size (d floats read, d floats written) three "
                          "times, as the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -175,6 +262,10 @@ def main():
 
     B.lib()  # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
+    if args.no_codec:
+        for r in whole_iteration_benchmarks(torch, B, synth, dev, 20, 5):
+            print(json.dumps(r), flush=True)
+        return
     M, d, seed = args.workers, 1 << args.log2d, 1
     log(f"generating g[{M}][2^{args.log2d}] and the reference on {torch.cuda.get_device_name(0)}")
     g, gref = synth.codec_inputs(M, d, seed, rel_variance=0.1, device=dev)
@@ -201,6 +292,18 @@ def main():
         ctx.close()
         log(f"copy calibration: 3 launches of the plain copy kernel, {4 * d} bytes read and written each")
 
+    cpu = None
+    if not args.no_cpu:
+        log("timing the oracle on the host")
+        cpu = cpu_baseline(g, gref, seed, min(1 << args.cpu_log2d, d))
+    iteration_results = []
+    if not args.no_steps:
+        del g, gref
+        torch.cuda.empty_cache()
+        log("timing whole iterations (tng_step) on the training workloads")
+        iteration_results = whole_iteration_benchmarks(torch, B, synth, dev, 20, 5)
+        g = gref = None
+
     dom_name = max(head["kernels"], key=lambda k: head["kernels"][k]["ms"])
     dom = head["kernels"][dom_name]
     out = {
@@ -224,14 +327,14 @@ def main():
         "kernel_ms": {k: round(v["ms"], 4) for k, v in head["kernels"].items()},
         "kernel_GBps": {k: round(v["GBps"], 1) for k, v in head["kernels"].items()},
         "variants": variants,
+        "iterations": iteration_results,
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(dom["GBps"], 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": dom["bytes"],
                      "traffic": measured_traffic(dom_name, M, d, 2, "sub")},
     }
-    if not args.no_cpu:
-        log("timing the oracle on the host")
-        out["cpu_baseline"] = cpu_baseline(g, gref, seed, min(1 << args.cpu_log2d, d))
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out), flush=True)
 
 

@@ -107,7 +107,8 @@ const char* tng_status_string(tng_status s); /* static storage */
 /* Problem data (Background: worker m holds its own shard Omega_m).  X, y, rowptr, col, val:
  * host arrays of M device pointers; n_rows: host array of M row counts (1 <= n < 2^32).
  * Dense shards are row-major [n_rows[m]][d], 16-byte aligned; labels are 0/1 floats.
- * CSR: rowptr int64[n_rows+1], col int32 in [0, d), val float.  The device data must outlive
+ * CSR: rowptr int64[n_rows+1], col int32 in [0, d) ascending within each row, fewer than 2^32
+ * entries per row, val float.  The device data must outlive
  * the context or the next tng_set_* call.  These two calls copy the pointer tables into the
  * workspace and block until that copy is done. */
 tng_status tng_set_logreg_dense(tng_ctx* ctx, const float* const* X, const float* const* y,
