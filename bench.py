@@ -208,8 +208,9 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup):
     ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), max(steps // 2, 5), max(warmup // 2, 2))
     nnz = M * batch * nnz_row
     record("sparse logistic d=2^24 M=64 B=512 nnz/row=16777 4-bit sub", ms,
-           2 * 8 * nnz + 4 * M * d + 2 * 4 * nnz + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
-           f"{n} rows per worker held; bytes: CSR rows read twice, g zero-fill, atomic read-modify-write, two encode passes, decode/update")
+           4 * nnz + 2 * 8 * nnz + 4 * M * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
+           f"{n} rows per worker held; bytes: column ids once (segment bounds), (col, val) twice (z pass, g pass), "
+           "g written once, two encode passes, decode/update")
     ctx.close()
     return out
 

@@ -18,7 +18,9 @@ struct tng_ctx {
   float* resid;           // [M][batch] sigma(z) - y
   const void** tables;    // 5 pointer tables of M entries: X|rowptr, col, val, y, and n_rows
   float* partials;        // [kAbsmaxMaxBlocks][M] partial maxima of the scale pass
-  uint32_t* bounds;       // [M][batch][tiles+1] segment bounds of the CSR gradient
+  int64_t* rowbase;       // [M][batch] start of each minibatch row in the worker's CSR arrays
+  uint32_t* bounds;       // [M][tiles+1][batch] segment bounds of the CSR gradient
+  float* zpart;           // [M][tiles][batch] per-tile partial dot products of the CSR gradient
   bool have_dense, have_csr;
   const float* noise;     // Rosenbrock noise, may be null
   const float* gref2;     // second reference of the combined normalisation
@@ -50,7 +52,7 @@ bool config_valid(const tng_config* c) {
 }
 
 struct Partition {
-  size_t idx_off, resid_off, tables_off, partials_off, bounds_off, total;
+  size_t idx_off, resid_off, tables_off, partials_off, rowbase_off, bounds_off, zpart_off, total;
 };
 
 Partition partition(const tng_config* c) {
@@ -66,9 +68,14 @@ Partition partition(const tng_config* c) {
   off += round_up(logreg ? (size_t)c->M * 5 * sizeof(void*) : 0);
   p.partials_off = off;
   off += round_up((size_t)tng::kAbsmaxMaxBlocks * c->M * sizeof(float));
+  p.rowbase_off = off;
+  if (c->problem == TNG_PROB_LOGREG_CSR) off += round_up((size_t)c->M * c->batch * sizeof(int64_t));
   p.bounds_off = off;
   if (c->problem == TNG_PROB_LOGREG_CSR)
     off += round_up((size_t)c->M * c->batch * (tng::csr_tiles(c->d) + 1) * sizeof(uint32_t));
+  p.zpart_off = off;
+  if (c->problem == TNG_PROB_LOGREG_CSR)
+    off += round_up((size_t)c->M * c->batch * tng::csr_tiles(c->d) * sizeof(float));
   p.total = off;
   return p;
 }
@@ -150,8 +157,8 @@ tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g
       const tng::LogregData p = logreg_tables(ctx);
       e = tng::launch_minibatch_indices(k0, k1, iter, c.M, c.batch, p.n_rows, ctx->idx, ctx->stream);
       if (e != hipSuccess) return TNG_ERR_HIP;
-      e = tng::launch_logreg_csr_grad(p, c.d, c.M, c.batch, c.l2, ctx->idx, ctx->bounds, ctx->resid, w, g,
-                                      ctx->stream);
+      e = tng::launch_logreg_csr_grad(p, c.d, c.M, c.batch, c.l2, ctx->idx, ctx->rowbase, ctx->bounds, ctx->zpart,
+                                      ctx->resid, w, g, ctx->stream);
       return hip_status(e);
     }
     case TNG_PROB_ROSENBROCK:
@@ -235,7 +242,9 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->resid = reinterpret_cast<float*>(base + p.resid_off);
   ctx->tables = reinterpret_cast<const void**>(base + p.tables_off);
   ctx->partials = reinterpret_cast<float*>(base + p.partials_off);
+  ctx->rowbase = reinterpret_cast<int64_t*>(base + p.rowbase_off);
   ctx->bounds = reinterpret_cast<uint32_t*>(base + p.bounds_off);
+  ctx->zpart = reinterpret_cast<float*>(base + p.zpart_off);
   ctx->have_dense = ctx->have_csr = false;
   ctx->noise = nullptr;
   ctx->gref2 = nullptr;

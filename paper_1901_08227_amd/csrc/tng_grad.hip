@@ -146,23 +146,33 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
 // Gathering w[col] and scattering into g[col] one stored entry at a time costs a 64-byte memory
 // transaction per 4 useful bytes (measured: 9.5 ms + 26 ms per step at d = 2^24, M = 64, B = 512).
 // Instead the columns are cut into tiles of 2^kCsrTileShift coordinates and a workgroup owns one
-// (tile, worker): the tile of w, then the tile of g, lives in LDS, and every minibatch row
+// (worker, tile): the tile of w, then the tile of g, lives in LDS, and every minibatch row
 // contributes the contiguous segment of its (ascending) columns that falls into the tile.
 //   1. csr_bounds_kernel   one coalesced pass over the minibatch rows' column ids: for every row
-//                          and tile, the position of the first entry at or beyond the tile start;
-//   2. csr_z_kernel        z_i += sum over the segment of val * w_tile[col]   (fp32 atomics on z);
+//                          and tile, the offset of the first entry at or beyond the tile start;
+//   2. csr_z_kernel        per (row, tile) partial dot product sum val * w_tile[col];
+//      csr_z_reduce_kernel z_i = sum of the partials over the tiles;
 //   3. csr_grad_kernel     r_i = sigma(z_i) - y_i; g_tile[col] += (r_i / B) val in LDS, then the whole
 //                          tile is written once (+ l2 w): no zero fill, no global atomics.
+// The g tile is accumulated in fp64: on this hardware an fp32 LDS atomic add serialises over the
+// lanes (~170 clocks per wavefront instruction) while the fp64 one runs at ~12; as a side effect g
+// is the correctly rounded sum almost always, whatever the order of the additions.
 // Entries are read twice in segment-sized pieces, g is written once.
 // ------------------------------------------------------------------------------------------
-constexpr int kCsrThreads = 1024;            // 16 wavefronts: one workgroup per compute unit
-constexpr int kCsrRowsPerTrip = 1024;        // minibatch rows whose segment bounds are staged in LDS at once
-constexpr int kCsrLanes = 64;                // lanes that share one row segment (a wavefront)
-constexpr int kCsrUnroll = 8;                // row segments in flight per wavefront
+constexpr int kCsrThreads = 1024;  // 16 wavefronts
+constexpr int kCsrRows = 512;      // minibatch rows staged in LDS per trip
+constexpr int kCsrLanes = 32;      // lanes that share one row segment (mean segment: 16 entries at 0.1 % density)
+constexpr int kCsrUnroll = 16;     // row segments in flight per lane group
+constexpr uint32_t kCsrGroups = kCsrThreads / kCsrLanes;
+static_assert(kCsrGroups * kCsrUnroll == kCsrRows, "one sweep of the lane groups covers one trip");
 
+// rowbase[m][i] = position of minibatch row i in worker m's col / val arrays; bounds[m][t][i]
+// (tile-major, so that a workgroup reads the bounds of all its rows contiguously) = offset within
+// the row of the first entry whose column is at or beyond the start of tile t; t = 0 .. ntiles.
 __global__ __launch_bounds__(kBlock) void csr_bounds_kernel(const int64_t* const* __restrict__ rowptrs,
                                                             const int32_t* const* __restrict__ cols,
                                                             const uint32_t* __restrict__ idx,
+                                                            int64_t* __restrict__ rowbase,
                                                             uint32_t* __restrict__ bounds, uint32_t batch,
                                                             uint32_t ntiles, uint32_t tile_shift) {
   const uint32_t m = blockIdx.y, i = blockIdx.x;
@@ -170,148 +180,190 @@ __global__ __launch_bounds__(kBlock) void csr_bounds_kernel(const int64_t* const
   const int64_t a = rowptrs[m][row];
   const uint32_t nnz = (uint32_t)(rowptrs[m][row + 1] - a);
   const int32_t* __restrict__ c = cols[m] + a;
-  uint32_t* __restrict__ out = bounds + ((uint64_t)m * batch + i) * (ntiles + 1);
+  if (threadIdx.x == 0) rowbase[(uint64_t)m * batch + i] = a;
+  uint32_t* __restrict__ out = bounds + (uint64_t)m * (ntiles + 1) * batch + i;
   // entry k opens every tile after the tile of entry k-1 up to its own tile
   for (uint32_t k = threadIdx.x; k <= nnz; k += kBlock) {
     const uint32_t prev = k == 0 ? 0u : ((uint32_t)c[k - 1] >> tile_shift) + 1u;
     const uint32_t cur = k == nnz ? ntiles : ((uint32_t)c[k] >> tile_shift);
-    for (uint32_t t = prev; t <= cur; ++t) out[t] = k;
+    for (uint32_t t = prev; t <= cur; ++t) out[(uint64_t)t * batch] = k;
   }
 }
 
 // Stages, for minibatch rows first .. first+count-1 of worker m, the entry range of the row that
-// falls into tile t (absolute positions in the worker's col / val arrays).
-__device__ __forceinline__ void csr_stage_segments(const int64_t* __restrict__ rowptr, const uint32_t* __restrict__ idx,
+// falls into tile t (absolute positions).
+__device__ __forceinline__ void csr_stage_segments(const int64_t* __restrict__ rowbase,
                                                    const uint32_t* __restrict__ bounds, uint32_t m, uint32_t batch,
                                                    uint32_t ntiles, uint32_t t, uint32_t first, uint32_t count,
                                                    int64_t* sLo, uint32_t* sLen) {
+  const uint32_t* __restrict__ b = bounds + ((uint64_t)m * (ntiles + 1) + t) * batch + first;
+  const int64_t* __restrict__ base = rowbase + (uint64_t)m * batch + first;
   for (uint32_t j = threadIdx.x; j < count; j += kCsrThreads) {
-    const uint64_t r = (uint64_t)m * batch + first + j;
-    const uint32_t* b = bounds + r * (ntiles + 1) + t;
-    const uint32_t lo = b[0], hi = b[1];
-    sLo[j] = rowptr[idx[r]] + lo;
+    const uint32_t lo = b[j], hi = b[batch + j];
+    sLo[j] = base[j] + lo;
     sLen[j] = hi - lo;
   }
 }
 
-__global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int64_t* const* __restrict__ rowptrs,
-                                                            const int32_t* const* __restrict__ cols,
-                                                            const float* const* __restrict__ vals,
-                                                            const uint32_t* __restrict__ idx,
-                                                            const uint32_t* __restrict__ bounds,
-                                                            const float* __restrict__ w, float* __restrict__ z,
-                                                            uint64_t d, uint32_t batch, uint32_t ntiles,
-                                                            uint32_t tile_shift) {
-  extern __shared__ float tile[];  // w over the tile's columns
-  __shared__ int64_t sLo[kCsrRowsPerTrip];
-  __shared__ uint32_t sLen[kCsrRowsPerTrip];
-  const uint32_t t = blockIdx.x, m = blockIdx.y;
-  const uint32_t T = 1u << tile_shift;
-  const uint64_t c0 = (uint64_t)t << tile_shift;
-  for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) tile[j] = c0 + j < d ? w[c0 + j] : 0.f;
-  const int32_t* __restrict__ c = cols[m];
-  const float* __restrict__ v = vals[m];
-  const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
-  constexpr uint32_t kGroups = kCsrThreads / kCsrLanes;
-  for (uint32_t first = 0; first < batch; first += kCsrRowsPerTrip) {
-    const uint32_t count = min((uint32_t)kCsrRowsPerTrip, batch - first);
-    __syncthreads();
-    csr_stage_segments(rowptrs[m], idx, bounds, m, batch, ntiles, t, first, count, sLo, sLen);
-    __syncthreads();
-    for (uint32_t j0 = group * kCsrUnroll; j0 < count; j0 += kGroups * kCsrUnroll) {
-      // first lane-width of every segment: all loads issued before any is used
-      int64_t lo[kCsrUnroll];
-      uint32_t len[kCsrUnroll];
-      int32_t cu[kCsrUnroll];
-      float vu[kCsrUnroll], acc[kCsrUnroll];
+// The first lane-width of entries of kCsrUnroll row segments, all loads issued before any is used.
+struct CsrBatch {
+  uint32_t len[kCsrUnroll];
+  int32_t col[kCsrUnroll];
+  float val[kCsrUnroll];
+};
+
+__device__ __forceinline__ void csr_load_batch(const int32_t* __restrict__ c, const float* __restrict__ v,
+                                               const int64_t* sLo, const uint32_t* sLen, uint32_t j0, uint32_t count,
+                                               uint32_t gl, CsrBatch& b) {
 #pragma unroll
-      for (int u = 0; u < kCsrUnroll; ++u) {
-        const uint32_t j = j0 + u;
-        lo[u] = j < count ? sLo[j] : 0;
-        len[u] = j < count ? sLen[j] : 0u;
-        cu[u] = 0;
-        vu[u] = 0.f;
-        if (gl < len[u]) {
-          cu[u] = c[lo[u] + gl];
-          vu[u] = v[lo[u] + gl];
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < kCsrUnroll; ++u) {
-        acc[u] = gl < len[u] ? vu[u] * tile[(uint32_t)cu[u] - (uint32_t)c0] : 0.f;
-        for (uint32_t k = gl + kCsrLanes; k < len[u]; k += kCsrLanes)  // rare: segments longer than a wavefront
-          acc[u] = __builtin_fmaf(v[lo[u] + k], tile[(uint32_t)c[lo[u] + k] - (uint32_t)c0], acc[u]);
-      }
-#pragma unroll
-      for (int u = 0; u < kCsrUnroll; ++u) {
-        const float sum = wave_sum(acc[u]);
-        if (gl == 0 && len[u] != 0) unsafeAtomicAdd(z + (uint64_t)m * batch + first + j0 + u, sum);
-      }
+  for (int u = 0; u < kCsrUnroll; ++u) {
+    const uint32_t j = j0 + u;
+    b.len[u] = j < count ? sLen[j] : 0u;
+    b.col[u] = 0;
+    b.val[u] = 0.f;
+    if (gl < b.len[u]) {
+      const int64_t lo = sLo[j];
+      b.col[u] = c[lo + gl];
+      b.val[u] = v[lo + gl];
     }
   }
 }
 
-__global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int64_t* const* __restrict__ rowptrs,
-                                                               const int32_t* const* __restrict__ cols,
+__global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int32_t* const* __restrict__ cols,
+                                                            const float* const* __restrict__ vals,
+                                                            const int64_t* __restrict__ rowbase,
+                                                            const uint32_t* __restrict__ bounds,
+                                                            const float* __restrict__ w, float* __restrict__ zparts,
+                                                            uint64_t d, uint32_t batch, uint32_t ntiles,
+                                                            uint32_t tile_shift) {
+  extern __shared__ float wtile[];  // w over the tile's columns
+  __shared__ int64_t sLo[kCsrRows];
+  __shared__ uint32_t sLen[kCsrRows];
+  // workers vary fastest across the grid: the workgroups that run side by side share one tile of w
+  const uint32_t m = blockIdx.x, t = blockIdx.y;
+  const uint32_t T = 1u << tile_shift;
+  const uint64_t c0 = (uint64_t)t << tile_shift;
+  float* __restrict__ zpart = zparts + ((uint64_t)m * ntiles + t) * batch;
+  if (tile_shift == kCsrTileShift && c0 + T <= d && (reinterpret_cast<uintptr_t>(w) & 15u) == 0) {
+    // full-size tile: all its loads in flight at once, then the LDS stores
+    constexpr int kVec = (1 << kCsrTileShift) / (4 * kCsrThreads);
+    const float4* __restrict__ w4 = reinterpret_cast<const float4*>(w + c0);
+    float4* tile4 = reinterpret_cast<float4*>(wtile);
+    float4 tmp[kVec];
+#pragma unroll
+    for (int q = 0; q < kVec; ++q) tmp[q] = w4[q * kCsrThreads + threadIdx.x];
+#pragma unroll
+    for (int q = 0; q < kVec; ++q) tile4[q * kCsrThreads + threadIdx.x] = tmp[q];
+  } else {
+    for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) wtile[j] = c0 + j < d ? w[c0 + j] : 0.f;
+  }
+  const int32_t* __restrict__ c = cols[m];
+  const float* __restrict__ v = vals[m];
+  const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
+  for (uint32_t first = 0; first < batch; first += kCsrRows) {
+    const uint32_t count = min((uint32_t)kCsrRows, batch - first);
+    __syncthreads();
+    csr_stage_segments(rowbase, bounds, m, batch, ntiles, t, first, count, sLo, sLen);
+    __syncthreads();
+    const uint32_t j0 = group * kCsrUnroll;
+    CsrBatch b;
+    csr_load_batch(c, v, sLo, sLen, j0, count, gl, b);
+    float acc[kCsrUnroll];
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u) {
+      acc[u] = gl < b.len[u] ? b.val[u] * wtile[(uint32_t)b.col[u] - (uint32_t)c0] : 0.f;
+      for (uint32_t k = gl + kCsrLanes; k < b.len[u]; k += kCsrLanes)  // rare: segments longer than the lane group
+        acc[u] = __builtin_fmaf(v[sLo[j0 + u] + k], wtile[(uint32_t)c[sLo[j0 + u] + k] - (uint32_t)c0], acc[u]);
+    }
+    // 16 sums over 32 lanes by halving: after the four exchange steps lane l holds the partial sum
+    // of segment (bit4 bit3 bit2 bit1 of l) over the lanes that share those bits.
+    static_assert(kCsrUnroll == 16 && kCsrLanes == 32, "the exchange pattern below is for 16 sums over 32 lanes");
+    float r8[8], r4[4], r2[2];
+    const bool b4 = (gl & 16) != 0, b3 = (gl & 8) != 0, b2 = (gl & 4) != 0, b1 = (gl & 2) != 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) r8[k] = (b4 ? acc[k + 8] : acc[k]) + __shfl_xor(b4 ? acc[k] : acc[k + 8], 16, kWave);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r4[k] = (b3 ? r8[k + 4] : r8[k]) + __shfl_xor(b3 ? r8[k] : r8[k + 4], 8, kWave);
+#pragma unroll
+    for (int k = 0; k < 2; ++k) r2[k] = (b2 ? r4[k + 2] : r4[k]) + __shfl_xor(b2 ? r4[k] : r4[k + 2], 4, kWave);
+    float r1 = (b1 ? r2[1] : r2[0]) + __shfl_xor(b1 ? r2[0] : r2[1], 2, kWave);
+    r1 += __shfl_xor(r1, 1, kWave);
+    const uint32_t u = (b4 ? 8u : 0u) + (b3 ? 4u : 0u) + (b2 ? 2u : 0u) + (b1 ? 1u : 0u);
+    if ((gl & 1u) == 0u && j0 + u < count) zpart[first + j0 + u] = r1;
+  }
+}
+
+// z[m][i] = sum over the tiles of the partial dot products zpart[m][t][i].
+__global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __restrict__ zpart, float* __restrict__ z,
+                                                              uint32_t batch, uint32_t ntiles) {
+  const uint32_t m = blockIdx.y;
+  const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+  if (i >= batch) return;
+  const float* __restrict__ p = zpart + (uint64_t)m * ntiles * batch + i;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  uint32_t t = 0;
+  for (; t + 4 <= ntiles; t += 4) {
+    a0 += p[(uint64_t)t * batch];
+    a1 += p[(uint64_t)(t + 1) * batch];
+    a2 += p[(uint64_t)(t + 2) * batch];
+    a3 += p[(uint64_t)(t + 3) * batch];
+  }
+  for (; t < ntiles; ++t) a0 += p[(uint64_t)t * batch];
+  z[(uint64_t)m * batch + i] = (a0 + a1) + (a2 + a3);
+}
+
+__global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* const* __restrict__ cols,
                                                                const float* const* __restrict__ vals,
                                                                const float* const* __restrict__ ys,
                                                                const uint32_t* __restrict__ idx,
+                                                               const int64_t* __restrict__ rowbase,
                                                                const uint32_t* __restrict__ bounds,
                                                                const float* __restrict__ z, const float* __restrict__ w,
                                                                float* __restrict__ g, uint64_t d, uint32_t batch,
                                                                uint32_t ntiles, uint32_t tile_shift, float inv_b,
                                                                float l2) {
-  extern __shared__ float tile[];  // g over the tile's columns
-  __shared__ int64_t sLo[kCsrRowsPerTrip];
-  __shared__ uint32_t sLen[kCsrRowsPerTrip];
-  __shared__ float sR[kCsrRowsPerTrip];
-  const uint32_t t = blockIdx.x, m = blockIdx.y;
+  extern __shared__ double gtile[];  // g over the tile's columns, accumulated in fp64
+  __shared__ int64_t sLo[kCsrRows];
+  __shared__ uint32_t sLen[kCsrRows];
+  __shared__ float sR[kCsrRows];
+  const uint32_t m = blockIdx.x, t = blockIdx.y;
   const uint32_t T = 1u << tile_shift;
   const uint64_t c0 = (uint64_t)t << tile_shift;
-  for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) tile[j] = 0.f;
+  for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) gtile[j] = 0.0;
   const int32_t* __restrict__ c = cols[m];
   const float* __restrict__ v = vals[m];
   const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
-  constexpr uint32_t kGroups = kCsrThreads / kCsrLanes;
-  for (uint32_t first = 0; first < batch; first += kCsrRowsPerTrip) {
-    const uint32_t count = min((uint32_t)kCsrRowsPerTrip, batch - first);
+  for (uint32_t first = 0; first < batch; first += kCsrRows) {
+    const uint32_t count = min((uint32_t)kCsrRows, batch - first);
     __syncthreads();
-    csr_stage_segments(rowptrs[m], idx, bounds, m, batch, ntiles, t, first, count, sLo, sLen);
+    csr_stage_segments(rowbase, bounds, m, batch, ntiles, t, first, count, sLo, sLen);
     for (uint32_t j = threadIdx.x; j < count; j += kCsrThreads) {
       const uint64_t r = (uint64_t)m * batch + first + j;
       sR[j] = logistic_residual(z[r], ys[m][idx[r]]) * inv_b;
     }
     __syncthreads();
-    for (uint32_t j0 = group * kCsrUnroll; j0 < count; j0 += kGroups * kCsrUnroll) {
-      int64_t lo[kCsrUnroll];
-      uint32_t len[kCsrUnroll];
-      int32_t cu[kCsrUnroll];
-      float vu[kCsrUnroll];
+    const uint32_t j0 = group * kCsrUnroll;
+    CsrBatch b;
+    csr_load_batch(c, v, sLo, sLen, j0, count, gl, b);
 #pragma unroll
-      for (int u = 0; u < kCsrUnroll; ++u) {
-        const uint32_t j = j0 + u;
-        lo[u] = j < count ? sLo[j] : 0;
-        len[u] = j < count ? sLen[j] : 0u;
-        cu[u] = 0;
-        vu[u] = 0.f;
-        if (gl < len[u]) {
-          cu[u] = c[lo[u] + gl];
-          vu[u] = v[lo[u] + gl];
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < kCsrUnroll; ++u) {
-        const float r = len[u] != 0 ? sR[j0 + u] : 0.f;
-        if (gl < len[u]) atomicAdd(&tile[(uint32_t)cu[u] - (uint32_t)c0], r * vu[u]);  // LDS atomic
-        for (uint32_t k = gl + kCsrLanes; k < len[u]; k += kCsrLanes)
-          atomicAdd(&tile[(uint32_t)c[lo[u] + k] - (uint32_t)c0], r * v[lo[u] + k]);
-      }
+    for (int u = 0; u < kCsrUnroll; ++u) {
+      const float r = b.len[u] != 0 ? sR[j0 + u] : 0.f;
+      if (gl < b.len[u]) atomicAdd(&gtile[(uint32_t)b.col[u] - (uint32_t)c0], (double)(r * b.val[u]));
+      for (uint32_t k = gl + kCsrLanes; k < b.len[u]; k += kCsrLanes)
+        atomicAdd(&gtile[(uint32_t)c[sLo[j0 + u] + k] - (uint32_t)c0], (double)(r * v[sLo[j0 + u] + k]));
     }
   }
   __syncthreads();
   float* __restrict__ out = g + (uint64_t)m * d;
-  for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) {
-    if (c0 + j < d) out[c0 + j] = l2 != 0.f ? __builtin_fmaf(l2, w[c0 + j], tile[j]) : tile[j];
+  if (c0 + T <= d && T % 4 == 0 && l2 == 0.f && ((reinterpret_cast<uintptr_t>(out) | (d * 4)) & 15u) == 0) {
+    float4* __restrict__ out4 = reinterpret_cast<float4*>(out + c0);
+    for (uint32_t q = threadIdx.x; q < T / 4; q += kCsrThreads)
+      store_stream(out4 + q, make_float4((float)gtile[4 * q], (float)gtile[4 * q + 1], (float)gtile[4 * q + 2],
+                                         (float)gtile[4 * q + 3]));
+  } else {
+    for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) {
+      if (c0 + j < d) out[c0 + j] = l2 != 0.f ? __builtin_fmaf(l2, w[c0 + j], (float)gtile[j]) : (float)gtile[j];
+    }
   }
 }
 
@@ -394,29 +446,27 @@ uint32_t csr_tiles(uint64_t d) {
 }
 
 hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
-                                  const uint32_t* idx, uint32_t* bounds, float* z, const float* w, float* g,
-                                  hipStream_t s) {
+                                  const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,
+                                  const float* w, float* g, hipStream_t s) {
   const float inv_b = 1.0f / (float)batch;
   const uint32_t shift = csr_tile_shift(d);
   const uint32_t ntiles = csr_tiles(d);
-  const size_t lds = sizeof(float) << shift;
-  static bool attr_set = false;  // the tile may exceed the 64 KiB default limit of dynamic LDS
+  const size_t lds_w = sizeof(float) << shift, lds_g = sizeof(double) << shift;
+  static bool attr_set = false;  // the g tile exceeds the 64 KiB default limit of dynamic LDS
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_z_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) << kCsrTileShift));
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_grad_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) << kCsrTileShift));
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_grad_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)(sizeof(double) << kCsrTileShift));
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(csr_bounds_kernel, dim3(batch, M), dim3(kBlock), 0, s, p.rowptr, p.col, idx, bounds, batch,
-                     ntiles, shift);
-  hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(z), (uint64_t)M * batch, 0u, s);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(csr_z_kernel, dim3(ntiles, M), dim3(kCsrThreads), lds, s, p.rowptr, p.col, p.val, idx, bounds,
-                     w, z, d, batch, ntiles, shift);
-  hipLaunchKernelGGL(csr_grad_kernel, dim3(ntiles, M), dim3(kCsrThreads), lds, s, p.rowptr, p.col, p.val, p.y, idx,
+  hipLaunchKernelGGL(csr_bounds_kernel, dim3(batch, M), dim3(kBlock), 0, s, p.rowptr, p.col, idx, rowbase, bounds,
+                     batch, ntiles, shift);
+  hipLaunchKernelGGL(csr_z_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_w, s, p.col, p.val, rowbase, bounds, w,
+                     zpart, d, batch, ntiles, shift);
+  hipLaunchKernelGGL(csr_z_reduce_kernel, dim3((batch + kBlock - 1) / kBlock, M), dim3(kBlock), 0, s, zpart, z, batch,
+                     ntiles);
+  hipLaunchKernelGGL(csr_grad_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, p.y, idx, rowbase,
                      bounds, z, w, g, d, batch, ntiles, shift, inv_b, l2);
   return hipGetLastError();
 }

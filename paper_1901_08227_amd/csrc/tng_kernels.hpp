@@ -50,14 +50,15 @@ hipError_t launch_minibatch_indices(uint32_t k0, uint32_t k1, uint32_t iter, uin
 hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                     const uint32_t* idx, float* resid, const float* w, float* g,
                                     hipStream_t s);
-// Column tiles of the CSR gradient: 2^kCsrTileShift coordinates (128 KiB of fp32 in LDS).
-constexpr uint32_t kCsrTileShift = 15;
+// Column tiles of the CSR gradient: 2^kCsrTileShift coordinates (128 KiB of fp64 in LDS).
+constexpr uint32_t kCsrTileShift = 14;
 uint32_t csr_tiles(uint64_t d);
-// bounds: device scratch uint32[M][batch][csr_tiles(d) + 1]; z: device scratch float[M][batch].
+// Device scratch: rowbase int64[M][batch]; bounds uint32[M][csr_tiles(d) + 1][batch];
+// zpart float[M][csr_tiles(d)][batch]; z float[M][batch].
 // Columns must be ascending within each row.
 hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
-                                  const uint32_t* idx, uint32_t* bounds, float* z, const float* w, float* g,
-                                  hipStream_t s);
+                                  const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,
+                                  const float* w, float* g, hipStream_t s);
 hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, float* g,
                                   hipStream_t s);
 
