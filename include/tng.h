@@ -65,7 +65,9 @@ typedef enum {
 /* How the reference is refreshed (section "Reference Vectors"; "Convex Problems"). */
 typedef enum {
   TNG_REF_ZERO = 0,    /* never: g~ keeps the caller's initial value (zeros in Algorithm 1)     */
-  TNG_REF_LAST_AVG = 1 /* g~ <- decoded average of this iteration when (iter+1) % period == 0   */
+  TNG_REF_LAST_AVG = 1, /* g~ <- decoded average of this iteration when (iter+1) % period == 0  */
+  TNG_REF_WINDOW_AVG = 2 /* g~ <- mean of the last ref_window decoded averages (second entry of the
+                            list of reference choices), refreshed on the same schedule            */
 } tng_ref_policy;
 
 typedef enum {
@@ -88,6 +90,7 @@ typedef struct {
   float l2;            /* l2 regularisation of the logistic problems, finite                    */
   uint32_t batch;      /* minibatch rows per worker (logistic problems), >= 1 there             */
   int32_t problem;     /* tng_problem                                                           */
+  uint32_t ref_window; /* tau_max >= 1 of TNG_REF_WINDOW_AVG (ignored by the other policies)            */
 } tng_config;
 
 /* ceil(d * bits / 32); 0 if bits is not 2 or 4. */
@@ -119,6 +122,10 @@ tng_status tng_set_logreg_csr(tng_ctx* ctx, const int64_t* const* rowptr,
 /* Rosenbrock: additive noise of the coming iteration, device [M][d], or NULL for none
  * ("Nonconvex Problems": the stochastic gradient is the exact gradient plus Gaussian noise). */
 tng_status tng_set_noise(tng_ctx* ctx, const float* noise);
+/* History of TNG_REF_WINDOW_AVG: device [ref_window][d], zero-filled by the caller before the first
+ * iteration (missing history counts as zeros) and then owned by the library: the decoded average of
+ * iteration iter is kept in slot iter % ref_window.  Must be set before tng_update_reference / tng_step. */
+tng_status tng_set_reference_history(tng_ctx* ctx, float* history);
 /* Second reference g~' of TNG_NORM_COMB, device [d]; must be set before encode / decode. */
 tng_status tng_set_second_reference(tng_ctx* ctx, const float* gref2);
 
@@ -150,7 +157,9 @@ tng_status tng_normalize_encode(tng_ctx* ctx, uint32_t iter, const float* g, con
 tng_status tng_decode_aggregate(tng_ctx* ctx, const uint32_t* codes, const float* scales,
                                 const float* gref, float* vbar);
 
-/* Reference rule: TNG_REF_LAST_AVG and (iter+1) % ref_period == 0: gref <- vbar; else no-op. */
+/* Reference rule.  TNG_REF_LAST_AVG: if (iter+1) % ref_period == 0, gref <- vbar, else no-op.
+ * TNG_REF_WINDOW_AVG: history[iter % ref_window] <- vbar at every iteration, and on a refresh
+ * iteration gref <- (sum of the ref_window slots, oldest first) * (1 / ref_window).  TNG_REF_ZERO: no-op. */
 tng_status tng_update_reference(tng_ctx* ctx, uint32_t iter, const float* vbar, float* gref);
 
 /* One whole iteration: local_grad (unless TNG_PROB_EXTERNAL, where g is an input),

@@ -384,13 +384,15 @@ def update_reference(cfg: Config, it: int, vbar, gref, history=None):
     raise ValueError("ref_policy")
 
 
-def step(cfg: Config, it: int, w, gref, g, gref2=None):
+def step(cfg: Config, it: int, w, gref, g, gref2=None, history=None):
     """One whole iteration from given local gradients g[M][d].
 
-    Returns (w_next, gref_next, codes, scales, vbar).
+    history: the decoded averages of the earlier iterations, oldest first (only read by the
+    window-average reference).  Returns (w_next, gref_next, codes, scales, vbar).
     """
     codes, scales = normalize_encode(cfg, it, g, gref, gref2)
     vbar = decode_aggregate(cfg, codes, scales, gref, g.shape[1], gref2)
     w_next = update_iterate(w, vbar, cfg.lr)
-    gref_next = update_reference(cfg, it, vbar, gref)
+    past = None if history is None else list(history) + [vbar]
+    gref_next = update_reference(cfg, it, vbar, gref, past)
     return w_next, gref_next, codes, scales, vbar

@@ -24,6 +24,7 @@ struct tng_ctx {
   bool have_dense, have_csr;
   const float* noise;     // Rosenbrock noise, may be null
   const float* gref2;     // second reference of the combined normalisation
+  float* history;         // [ref_window][d] ring of decoded averages (window-average reference)
   std::vector<hipEvent_t> prof;  // optional timing events, 5 per slot
   uint32_t prof_slots;
   uint64_t enc_calls, dec_calls;
@@ -42,7 +43,8 @@ bool config_valid(const tng_config* c) {
   if (c->bits != 2 && c->bits != 4) return false;
   if (c->norm < TNG_NORM_NONE || c->norm > TNG_NORM_COMB) return false;
   if (!(c->quot_eps > 0.0f) || !std::isfinite(c->quot_eps)) return false;
-  if (c->ref_policy != TNG_REF_ZERO && c->ref_policy != TNG_REF_LAST_AVG) return false;
+  if (c->ref_policy < TNG_REF_ZERO || c->ref_policy > TNG_REF_WINDOW_AVG) return false;
+  if (c->ref_policy == TNG_REF_WINDOW_AVG && (c->ref_window == 0 || c->ref_window > 65536u)) return false;
   if (c->ref_period == 0) return false;
   if (!std::isfinite(c->lr) || !std::isfinite(c->l2)) return false;
   if (c->problem < TNG_PROB_EXTERNAL || c->problem > TNG_PROB_ROSENBROCK) return false;
@@ -81,7 +83,29 @@ Partition partition(const tng_config* c) {
 }
 
 inline bool refresh_now(const tng_config& c, uint32_t iter) {
-  return c.ref_policy == TNG_REF_LAST_AVG && ((uint64_t)iter + 1) % c.ref_period == 0;
+  return c.ref_policy != TNG_REF_ZERO && ((uint64_t)iter + 1) % c.ref_period == 0;
+}
+
+// Reference update from a finished decoded average (everything except what tng_step fuses into
+// its decode kernel for the last-average policy).
+tng_status update_reference_impl(tng_ctx* ctx, uint32_t iter, const float* vbar, float* gref) {
+  const tng_config& c = ctx->cfg;
+  if (c.ref_policy == TNG_REF_LAST_AVG) {
+    if (!refresh_now(c, iter)) return TNG_OK;
+    return tng::launch_copy_f32(gref, vbar, c.d, ctx->stream) == hipSuccess ? TNG_OK : TNG_ERR_HIP;
+  }
+  if (c.ref_policy == TNG_REF_WINDOW_AVG) {
+    if (ctx->history == nullptr) return TNG_ERR_BAD_STATE;
+    const uint32_t slot = iter % c.ref_window;
+    if (tng::launch_copy_f32(ctx->history + (uint64_t)slot * c.d, vbar, c.d, ctx->stream) != hipSuccess)
+      return TNG_ERR_HIP;
+    if (!refresh_now(c, iter)) return TNG_OK;
+    return tng::launch_window_mean(ctx->history, c.ref_window, (slot + 1) % c.ref_window, c.d, gref, ctx->stream) ==
+                   hipSuccess
+               ? TNG_OK
+               : TNG_ERR_HIP;
+  }
+  return TNG_OK;
 }
 
 inline tng_status hip_status(hipError_t e) { return e == hipSuccess ? TNG_OK : TNG_ERR_HIP; }
@@ -248,6 +272,7 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->have_dense = ctx->have_csr = false;
   ctx->noise = nullptr;
   ctx->gref2 = nullptr;
+  ctx->history = nullptr;
   ctx->prof_slots = 0;
   ctx->enc_calls = ctx->dec_calls = 0;
   *out = ctx;
@@ -290,6 +315,13 @@ tng_status tng_set_noise(tng_ctx* ctx, const float* noise) {
   if (ctx == nullptr || !aligned(noise, 16)) return TNG_ERR_INVALID_ARG;
   if (ctx->cfg.problem != TNG_PROB_ROSENBROCK) return TNG_ERR_BAD_STATE;
   ctx->noise = noise;
+  return TNG_OK;
+}
+
+tng_status tng_set_reference_history(tng_ctx* ctx, float* history) {
+  if (ctx == nullptr || history == nullptr || !aligned(history, 16)) return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.ref_policy != TNG_REF_WINDOW_AVG) return TNG_ERR_BAD_STATE;
+  ctx->history = history;
   return TNG_OK;
 }
 
@@ -355,8 +387,7 @@ tng_status tng_decode_aggregate(tng_ctx* ctx, const uint32_t* codes, const float
 tng_status tng_update_reference(tng_ctx* ctx, uint32_t iter, const float* vbar, float* gref) {
   if (ctx == nullptr || vbar == nullptr || gref == nullptr || !aligned(vbar, 16) || !aligned(gref, 16))
     return TNG_ERR_INVALID_ARG;
-  if (!refresh_now(ctx->cfg, iter)) return TNG_OK;
-  return hip_status(tng::launch_copy_f32(gref, vbar, ctx->cfg.d, ctx->stream));
+  return update_reference_impl(ctx, iter, vbar, gref);
 }
 
 tng_status tng_step(tng_ctx* ctx, uint32_t iter, float* w, float* gref, float* g, uint32_t* codes,
@@ -364,13 +395,21 @@ tng_status tng_step(tng_ctx* ctx, uint32_t iter, float* w, float* gref, float* g
   if (ctx == nullptr || w == nullptr || gref == nullptr || !aligned(w, 16)) return TNG_ERR_INVALID_ARG;
   tng_status s = check_codec_args(ctx, g, gref, codes, scales, vbar, true, true);
   if (s != TNG_OK) return s;
+  if (ctx->cfg.ref_policy == TNG_REF_WINDOW_AVG && ctx->history == nullptr) return TNG_ERR_BAD_STATE;
+  if (ctx->cfg.problem == TNG_PROB_LOGREG_DENSE && !ctx->have_dense) return TNG_ERR_BAD_STATE;
+  if (ctx->cfg.problem == TNG_PROB_LOGREG_CSR && !ctx->have_csr) return TNG_ERR_BAD_STATE;
   if (ctx->cfg.problem != TNG_PROB_EXTERNAL) {
     s = local_grad_impl(ctx, iter, w, g);
     if (s != TNG_OK) return s;
   }
   s = encode_impl(ctx, iter, g, gref, codes, scales);
   if (s != TNG_OK) return s;
-  float* ref_out = refresh_now(ctx->cfg, iter) ? gref : nullptr;
+  if (ctx->cfg.ref_policy == TNG_REF_WINDOW_AVG) {
+    s = decode_impl(ctx, codes, scales, gref, vbar, w, nullptr);
+    if (s != TNG_OK) return s;
+    return update_reference_impl(ctx, iter, vbar, gref);
+  }
+  float* ref_out = refresh_now(ctx->cfg, iter) ? gref : nullptr;  // last-average policy: fused into the decode pass
   return decode_impl(ctx, codes, scales, gref, vbar, w, ref_out);
 }
 

@@ -39,6 +39,23 @@ __global__ __launch_bounds__(kBlock) void copy_f32x4_kernel(float4* __restrict__
   for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
+// Window-average reference (section "Reference Vectors"): mean of the last `window` decoded
+// averages, added oldest first, one rounding per addition.
+__global__ __launch_bounds__(kBlock) void window_mean_kernel(const float* __restrict__ history, uint32_t window,
+                                                             uint32_t first, uint64_t d, float inv_window,
+                                                             float* __restrict__ out) {
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x; e < d; e += stride) {
+    float acc = 0.f;
+    uint32_t slot = first;
+    for (uint32_t k = 0; k < window; ++k) {
+      acc = acc + history[(uint64_t)slot * d + e];
+      slot = slot + 1 == window ? 0u : slot + 1;
+    }
+    out[e] = acc * inv_window;
+  }
+}
+
 __global__ __launch_bounds__(kBlock) void rng_draws_kernel(uint32_t k0, uint32_t k1, uint32_t iter,
                                                            uint32_t worker, uint32_t stream,
                                                            uint64_t first, uint64_t count, uint32_t* out) {
@@ -703,6 +720,14 @@ hipError_t launch_copy_f32(float* dst, const float* src, uint64_t n, hipStream_t
     const uint32_t gx = div_up_u32(n, kBlock);
     hipLaunchKernelGGL(copy_f32_kernel, dim3(gx < 16384u ? gx : 16384u), dim3(kBlock), 0, s, dst, src, n);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_window_mean(const float* history, uint32_t window, uint32_t first, uint64_t d, float* out,
+                              hipStream_t s) {
+  const uint32_t gx = div_up_u32(d, kBlock);
+  hipLaunchKernelGGL(window_mean_kernel, dim3(gx < 16384u ? gx : 16384u), dim3(kBlock), 0, s, history, window, first,
+                     d, 1.0f / (float)window, out);
   return hipGetLastError();
 }
 

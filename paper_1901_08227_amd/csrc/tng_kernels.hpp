@@ -18,6 +18,9 @@ struct CodecShape {
 
 hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t s);
 hipError_t launch_copy_f32(float* dst, const float* src, uint64_t n, hipStream_t s);
+// out = (history[first] + history[first+1] + ... cyclically over `window` slots of d floats) * (1/window)
+hipError_t launch_window_mean(const float* history, uint32_t window, uint32_t first, uint64_t d, float* out,
+                              hipStream_t s);
 hipError_t launch_rng_draws(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t worker, uint32_t stream,
                             uint64_t first, uint64_t count, uint32_t* out, hipStream_t s);
 

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _cfg(**kw):
     base = dict(d=1000, M=4, bits=2, norm=B.NORM_SUB, quot_eps=1e-8, ref_policy=B.REF_LAST_AVG, ref_period=1,
-                seed=0, lr=0.1, l2=0.0, batch=64, problem=B.PROB_LOGREG_DENSE)
+                seed=0, lr=0.1, l2=0.0, batch=64, problem=B.PROB_LOGREG_DENSE, ref_window=1)
     base.update(kw)
     return B.TngConfig(**base)
 
@@ -31,8 +31,8 @@ def test_library_exports_every_declared_entry_point():
 
 
 def test_config_struct_matches_the_header_layout():
-    # d(8) M(4) bits(4) norm(4) eps(4) policy(4) period(4) seed(8) lr(4) l2(4) batch(4) problem(4)
-    assert ctypes.sizeof(B.TngConfig) == 56
+    # d(8) M(4) bits(4) norm(4) eps(4) policy(4) period(4) seed(8) lr(4) l2(4) batch(4) problem(4) window(4) pad(4)
+    assert ctypes.sizeof(B.TngConfig) == 64 and B.TngConfig.ref_window.offset == 56
     assert B.TngConfig.seed.offset == 32 and B.TngConfig.problem.offset == 52
 
 
@@ -48,7 +48,8 @@ def test_workspace_size_and_config_validation():
     assert B.tng_workspace_bytes(_cfg(problem=B.PROB_EXTERNAL, batch=0)) > 0
     bad = [dict(d=0), dict(M=0), dict(bits=3), dict(bits=8), dict(norm=7), dict(quot_eps=0.0),
            dict(quot_eps=float("nan")), dict(ref_policy=5), dict(ref_period=0), dict(lr=float("inf")),
-           dict(l2=float("nan")), dict(batch=0), dict(problem=9), dict(d=(1 << 34) + 1), dict(M=70000)]
+           dict(l2=float("nan")), dict(batch=0), dict(problem=9), dict(d=(1 << 34) + 1), dict(M=70000),
+           dict(ref_policy=B.REF_WINDOW_AVG, ref_window=0)]
     for kw in bad:
         assert B.tng_workspace_bytes(_cfg(**kw)) == 0, kw
         h = ctypes.c_void_p()
@@ -112,6 +113,13 @@ def test_calls_reject_null_and_misaligned_pointers_before_launching():
     assert L.tng_destroy(h) == B.TNG_OK
     h = _fake_ctx(ref_policy=B.REF_ZERO, problem=B.PROB_EXTERNAL, batch=0)
     assert L.tng_update_reference(h, 0, p, p) == B.TNG_OK
+    assert L.tng_set_reference_history(h, p) == B.TNG_ERR_BAD_STATE                    # not a window-average context
+    assert L.tng_destroy(h) == B.TNG_OK
+    # the window-average reference needs its history buffer first
+    h = _fake_ctx(ref_policy=B.REF_WINDOW_AVG, ref_window=4, problem=B.PROB_EXTERNAL, batch=0)
+    assert L.tng_update_reference(h, 0, p, p) == B.TNG_ERR_BAD_STATE
+    assert L.tng_step(h, 0, p, p, p, p, p, p) == B.TNG_ERR_BAD_STATE
+    assert L.tng_set_reference_history(h, None) == B.TNG_ERR_INVALID_ARG
     assert L.tng_destroy(h) == B.TNG_OK
 
 

@@ -159,6 +159,64 @@ def test_csr_logistic_scaled():
     ctx.close()
 
 
+def _ragged_csr(M, n, d, lengths_fn, seed):
+    """CSR shards with a different number of stored entries per row (sorted distinct columns)."""
+    gen = torch.Generator(device="cpu").manual_seed(seed)
+    shards = []
+    for m in range(M):
+        lens = [int(lengths_fn(m, i)) for i in range(n)]
+        rowptr = torch.zeros(n + 1, dtype=torch.int64)
+        rowptr[1:] = torch.cumsum(torch.tensor(lens, dtype=torch.int64), 0)
+        cols = [torch.sort(torch.randperm(d, generator=gen)[:k])[0] for k in lens]
+        col = torch.cat(cols).to(torch.int32) if sum(lens) else torch.zeros(0, dtype=torch.int32)
+        val = torch.randn(int(rowptr[-1]), generator=gen)
+        y = (torch.rand(n, generator=gen) < 0.5).float()
+        shards.append((rowptr.to(DEV), torch.cat([col, torch.zeros(1, dtype=torch.int32)]).to(DEV)[:max(len(col), 1)],
+                       torch.cat([val, torch.zeros(1)]).to(DEV)[:max(len(val), 1)], y.to(DEV)))
+    return shards
+
+
+@pytest.mark.parametrize("case", ["ragged", "tiny_d", "odd_d_many_rows", "dense_rows"])
+def test_csr_logistic_edge_cases(case):
+    if case == "ragged":        # empty rows, one-entry rows, rows longer than a lane group inside one tile
+        M, n, d, batch = 3, 40, (1 << 15) + 24, 33
+        lens = lambda m, i: [0, 1, 2, 700, 33, 5000][(i + m) % 6]
+    elif case == "tiny_d":      # d smaller than a tile, a single partial tile
+        M, n, d, batch = 2, 30, 100, 7
+        lens = lambda m, i: (i * 7 + m) % 60
+    elif case == "odd_d_many_rows":   # more minibatch rows than one staging trip, d not a multiple of 4 (scalar codec)
+        M, n, d, batch = 2, 900, 3 * (1 << 14) + 1, 1100
+        lens = lambda m, i: 20 + (i % 50)
+    else:                       # nearly dense rows: many entries per (row, tile) segment
+        M, n, d, batch = 2, 12, 1 << 14, 12
+        lens = lambda m, i: (1 << 14) - 1 - i
+    say(f"csr edge case {case}: d={d} M={M} n={n} B={batch}")
+    seed = 11
+    shards = _ragged_csr(M, n, d, lens, seed)
+    ctx = make_ctx(d, M, 4, B.NORM_SUB, seed=seed, lr=0.1, l2=0.001, batch=batch, problem=B.PROB_LOGREG_CSR)
+    ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    cfg = oracle_cfg(ctx)
+    host = [tuple(t.cpu().numpy() for t in s) for s in shards]
+    w = 0.1 * torch.randn(d, device=DEV)
+    gref = torch.zeros(d, device=DEV)
+    buf = buffers(ctx)
+    for it in range(2):
+        def grad_ref(w0, it=it):
+            ids = [O.minibatch_indices(seed, it, m, batch, n) for m in range(M)]
+            ref = np.stack([O.grad_logreg_csr(host[m][0], host[m][1], host[m][2], host[m][3], w0, ids[m], d, 0.001)
+                            for m in range(M)])
+            cond = np.zeros((M, d))
+            for m in range(M):
+                Xb = np.zeros((batch, d), dtype=np.float32)
+                for j, i in enumerate(ids[m]):
+                    a, b = host[m][0][i], host[m][0][i + 1]
+                    Xb[j, host[m][1][a:b]] = host[m][2][a:b]
+                cond[m] = logistic_condition(Xb, host[m][3][ids[m]], w0, 0.001)
+            return ref, cond
+        _teacher_forced_step(ctx, cfg, it, w, gref, buf, grad_ref)
+    ctx.close()
+
+
 def test_external_gradients_and_separate_calls_equal_the_fused_step():
     d, M = 4096 * 3 + 4, 4
     g, gref0 = synth.codec_inputs(M, d, 9, device=DEV)
@@ -178,6 +236,43 @@ def test_external_gradients_and_separate_calls_equal_the_fused_step():
         assert torch.equal(ref_a, ref_b) and torch.equal(ref_a, a["vbar"])
         cfg = oracle_cfg(ctx)
         assert np.array_equal(w_a.cpu().numpy(), O.update_iterate(w.cpu().numpy(), a["vbar"].cpu().numpy(), cfg.lr))
+        ctx.close()
+
+
+def test_window_average_reference():
+    # reference = mean of the last 3 decoded averages, refreshed every 2 iterations
+    for d, M, W, K in [(5000, 3, 3, 2), (4099, 2, 4, 1), (1 << 16, 4, 2, 3)]:
+        say(f"window-average reference d={d} M={M} window={W} period={K}")
+        ctx = make_ctx(d, M, 2, B.NORM_SUB, seed=5, lr=1e-5, ref_policy=B.REF_WINDOW_AVG, ref_period=K, ref_window=W,
+                       problem=B.PROB_ROSENBROCK)
+        cfg = oracle_cfg(ctx)
+        history_dev = torch.zeros((W, d), device=DEV)
+        ctx.set_reference_history(history_dev)
+        x = synth.rosenbrock_start(d, 5, device=DEV)
+        gref = torch.zeros(d, device=DEV)
+        buf = buffers(ctx)
+        past = []
+        for it in range(9):
+            noise = synth.gradient_noise(M, d, 5, it, device=DEV)
+            ctx.set_noise(noise)
+            w0, r0 = x.cpu().numpy(), gref.cpu().numpy()
+            ctx.step(it, x, gref, buf["g"], buf["codes"], buf["scales"], buf["vbar"])
+            torch.cuda.synchronize()
+            gh = buf["g"].cpu().numpy()
+            w1, r1, c1, s1, v1 = O.step(cfg, it, w0, r0, gh, history=past)
+            assert np.array_equal(u32(buf["codes"]), c1) and np.array_equal(buf["vbar"].cpu().numpy(), v1)
+            assert np.array_equal(x.cpu().numpy(), w1), f"it={it}: iterate"
+            assert np.array_equal(gref.cpu().numpy(), r1), f"it={it}: window-average reference"
+            past.append(v1)
+            assert np.array_equal(history_dev[it % W].cpu().numpy(), v1)
+        # the separate call does the same as the fused step
+        gref2 = torch.zeros(d, device=DEV)
+        hist2 = torch.zeros((W, d), device=DEV)
+        ctx.set_reference_history(hist2)
+        for it in range(9):
+            ctx.update_reference(it, torch.from_numpy(past[it]).to(DEV), gref2)
+        torch.cuda.synchronize()
+        assert torch.equal(gref2, gref) and torch.equal(hist2, history_dev)
         ctx.close()
 
 
