@@ -465,25 +465,26 @@ __device__ __forceinline__ void stage_scales(const float* __restrict__ scales, u
 constexpr int kDecodeLoads = 4;
 constexpr int kDecodeWorkers = 8;
 
-template <int NORM, int BITS>
+template <int NORM, int BITS, int V>
 __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
     const uint32_t* __restrict__ codes, const float* __restrict__ scales, const float4* ref4,
     const float4* __restrict__ ref24, float4* __restrict__ vbar4, float4* w4, float4* refout4,
     uint64_t nvec, uint64_t words, uint32_t M, float eps, float inv_m, float lr) {
-  constexpr int V = kDecodeLoads;
   constexpr int MCH = kDecodeWorkers;
-  constexpr int WPT = BITS / 2;            // packed words per thread and worker
+  constexpr int FPW = 32 / (4 * BITS);     // 4-code fragments per packed word: 4 (ternary) or 2
+  constexpr int WPT = (V + FPW - 1) / FPW; // packed words per thread and worker (some threads idle when V < FPW)
+  constexpr int WORDS = kBlock * V / FPW;  // packed words per tile and worker
   constexpr int TAB = 1 << BITS;           // table entries per worker
   constexpr uint32_t MASK = (1u << BITS) - 1u;
   constexpr float S = (float)((1 << (BITS - 1)) - 1);
   __shared__ union {
-    lds_u32 b32[MCH][kBlock * WPT];
-    lds_u8 b8[MCH][kBlock * WPT * 4];
-    lds_u16 b16[MCH][kBlock * WPT * 2];
+    lds_u32 b32[MCH][WORDS];
+    lds_u8 b8[MCH][WORDS * 4];
+    lds_u16 b16[MCH][WORDS * 2];
   } buf;
   __shared__ float table[MCH * TAB];
   const uint64_t vec_base = (uint64_t)blockIdx.x * (kBlock * V);
-  const uint64_t word_base = (uint64_t)blockIdx.x * (kBlock * WPT);
+  const uint64_t word_base = (uint64_t)blockIdx.x * WORDS;
   float4 acc[V];
 #pragma unroll
   for (int v = 0; v < V; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -495,9 +496,10 @@ __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
     for (int mm = 0; mm < MCH; ++mm) {
 #pragma unroll
       for (int k = 0; k < WPT; ++k) {
-        const uint64_t wi = word_base + (uint64_t)k * kBlock + threadIdx.x;
+        const uint32_t wl = k * kBlock + threadIdx.x;   // word within the tile
+        const uint64_t wi = word_base + wl;
         wreg[mm][k] = 0u;
-        if ((uint32_t)mm < cnt && wi < words)
+        if ((uint32_t)mm < cnt && wl < (uint32_t)WORDS && wi < words)
           wreg[mm][k] = __builtin_nontemporal_load(codes + (uint64_t)(m_base + mm) * words + wi);
       }
     }
@@ -505,7 +507,8 @@ __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
 #pragma unroll
     for (int mm = 0; mm < MCH; ++mm) {
 #pragma unroll
-      for (int k = 0; k < WPT; ++k) buf.b32[mm][k * kBlock + threadIdx.x] = wreg[mm][k];
+      for (int k = 0; k < WPT; ++k)
+        if (k * kBlock + threadIdx.x < (uint32_t)WORDS) buf.b32[mm][k * kBlock + threadIdx.x] = wreg[mm][k];
     }
     if (threadIdx.x < cnt * TAB) {
       const uint32_t mm = threadIdx.x / TAB, code = threadIdx.x % TAB;
@@ -688,11 +691,19 @@ hipError_t decode_dispatch(const CodecShape& c, const uint32_t* codes, const flo
   const float inv_m = 1.0f / (float)c.M;
   if (vec_ok(c.d, gref, gref2, vbar) && vec_ok(c.d, w, ref_out, nullptr)) {
     const uint64_t nvec = c.d / 4;
-    const uint64_t blocks = (nvec + kBlock * kDecodeLoads - 1) / (kBlock * kDecodeLoads);
-    hipLaunchKernelGGL((decode_vec_kernel<NORM, BITS>), dim3((uint32_t)blocks), dim3(kBlock), 0, s, codes,
-                       scales, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2),
-                       reinterpret_cast<float4*>(vbar), reinterpret_cast<float4*>(w),
-                       reinterpret_cast<float4*>(ref_out), nvec, c.words, c.M, c.eps, inv_m, lr);
+    const uint64_t big_tiles = (nvec + kBlock * kDecodeLoads - 1) / (kBlock * kDecodeLoads);
+    if (big_tiles >= 2048) {
+      hipLaunchKernelGGL((decode_vec_kernel<NORM, BITS, kDecodeLoads>), dim3((uint32_t)big_tiles), dim3(kBlock), 0, s,
+                         codes, scales, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2),
+                         reinterpret_cast<float4*>(vbar), reinterpret_cast<float4*>(w),
+                         reinterpret_cast<float4*>(ref_out), nvec, c.words, c.M, c.eps, inv_m, lr);
+    } else {  // few coordinates: small tiles so that every compute unit still gets work
+      hipLaunchKernelGGL((decode_vec_kernel<NORM, BITS, 1>), dim3((uint32_t)((nvec + kBlock - 1) / kBlock)),
+                         dim3(kBlock), 0, s, codes, scales, reinterpret_cast<const float4*>(gref),
+                         reinterpret_cast<const float4*>(gref2), reinterpret_cast<float4*>(vbar),
+                         reinterpret_cast<float4*>(w), reinterpret_cast<float4*>(ref_out), nvec, c.words, c.M, c.eps,
+                         inv_m, lr);
+    }
     return hipGetLastError();
   }
   const uint64_t blocks = (c.d + kBlock - 1) / kBlock;
