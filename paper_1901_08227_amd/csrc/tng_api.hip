@@ -129,11 +129,15 @@ inline void mark(tng_ctx* ctx, uint64_t call, int which) {
   if (ctx->prof_slots != 0) (void)hipEventRecord(ctx->prof[5 * (call % ctx->prof_slots) + which], ctx->stream);
 }
 
+// fused_rows > 0: a gradient kernel has already left that many rows of partial maxima in the
+// workspace, only their reduction remains of the scale pass.
 tng_status encode_impl(tng_ctx* ctx, uint32_t iter, const float* g, const float* gref, uint32_t* codes,
-                       float* scales) {
+                       float* scales, uint32_t fused_rows = 0) {
   const uint64_t call = ctx->enc_calls++;
   mark(ctx, call, 0);
-  hipError_t e = tng::launch_absmax(ctx->shape, g, gref, ctx->gref2, ctx->partials, scales, ctx->stream);
+  hipError_t e = fused_rows > 0
+                     ? tng::launch_absmax_finish(ctx->partials, fused_rows, ctx->cfg.M, scales, ctx->stream)
+                     : tng::launch_absmax(ctx->shape, g, gref, ctx->gref2, ctx->partials, scales, ctx->stream);
   if (e != hipSuccess) return TNG_ERR_HIP;
   mark(ctx, call, 1);
   e = tng::launch_quantize_pack(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, ctx->stream);
@@ -163,7 +167,9 @@ tng_status check_codec_args(const tng_ctx* ctx, const float* g, const float* gre
   return TNG_OK;
 }
 
-tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g) {
+tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g, const tng::ScaleFusion* fuse,
+                           uint32_t* fused_rows) {
+  if (fused_rows != nullptr) *fused_rows = 0;
   const tng_config& c = ctx->cfg;
   const uint32_t k0 = ctx->shape.k0, k1 = ctx->shape.k1;
   hipError_t e = hipSuccess;
@@ -173,7 +179,8 @@ tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g
       const tng::LogregData p = logreg_tables(ctx);
       e = tng::launch_minibatch_indices(k0, k1, iter, c.M, c.batch, p.n_rows, ctx->idx, ctx->stream);
       if (e != hipSuccess) return TNG_ERR_HIP;
-      e = tng::launch_logreg_dense_grad(p, c.d, c.M, c.batch, c.l2, ctx->idx, ctx->resid, w, g, ctx->stream);
+      e = tng::launch_logreg_dense_grad(p, c.d, c.M, c.batch, c.l2, ctx->idx, ctx->resid, w, g, fuse, fused_rows,
+                                        ctx->stream);
       return hip_status(e);
     }
     case TNG_PROB_LOGREG_CSR: {
@@ -182,11 +189,11 @@ tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g
       e = tng::launch_minibatch_indices(k0, k1, iter, c.M, c.batch, p.n_rows, ctx->idx, ctx->stream);
       if (e != hipSuccess) return TNG_ERR_HIP;
       e = tng::launch_logreg_csr_grad(p, c.d, c.M, c.batch, c.l2, ctx->idx, ctx->rowbase, ctx->bounds, ctx->zpart,
-                                      ctx->resid, w, g, ctx->stream);
+                                      ctx->resid, w, g, fuse, fused_rows, ctx->stream);
       return hip_status(e);
     }
     case TNG_PROB_ROSENBROCK:
-      e = tng::launch_rosenbrock_grad(c.d, c.M, w, ctx->noise, g, ctx->stream);
+      e = tng::launch_rosenbrock_grad(c.d, c.M, w, ctx->noise, g, fuse, fused_rows, ctx->stream);
       return hip_status(e);
     default:
       return TNG_ERR_BAD_STATE;
@@ -367,7 +374,7 @@ tng_status tng_minibatch_indices(tng_ctx* ctx, uint32_t iter, uint32_t* idx) {
 tng_status tng_local_grad(tng_ctx* ctx, uint32_t iter, const float* w, float* g) {
   if (ctx == nullptr || w == nullptr || g == nullptr || !aligned(w, 16) || !aligned(g, 16))
     return TNG_ERR_INVALID_ARG;
-  return local_grad_impl(ctx, iter, w, g);
+  return local_grad_impl(ctx, iter, w, g, nullptr, nullptr);
 }
 
 tng_status tng_normalize_encode(tng_ctx* ctx, uint32_t iter, const float* g, const float* gref,
@@ -398,11 +405,13 @@ tng_status tng_step(tng_ctx* ctx, uint32_t iter, float* w, float* gref, float* g
   if (ctx->cfg.ref_policy == TNG_REF_WINDOW_AVG && ctx->history == nullptr) return TNG_ERR_BAD_STATE;
   if (ctx->cfg.problem == TNG_PROB_LOGREG_DENSE && !ctx->have_dense) return TNG_ERR_BAD_STATE;
   if (ctx->cfg.problem == TNG_PROB_LOGREG_CSR && !ctx->have_csr) return TNG_ERR_BAD_STATE;
+  uint32_t fused_rows = 0;
   if (ctx->cfg.problem != TNG_PROB_EXTERNAL) {
-    s = local_grad_impl(ctx, iter, w, g);
+    const tng::ScaleFusion fuse{ctx->cfg.norm, ctx->cfg.quot_eps, gref, ctx->gref2, ctx->partials};
+    s = local_grad_impl(ctx, iter, w, g, &fuse, &fused_rows);
     if (s != TNG_OK) return s;
   }
-  s = encode_impl(ctx, iter, g, gref, codes, scales);
+  s = encode_impl(ctx, iter, g, gref, codes, scales, fused_rows);
   if (s != TNG_OK) return s;
   if (ctx->cfg.ref_policy == TNG_REF_WINDOW_AVG) {
     s = decode_impl(ctx, codes, scales, gref, vbar, w, nullptr);

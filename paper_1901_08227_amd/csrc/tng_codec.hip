@@ -751,6 +751,11 @@ hipError_t launch_rng_draws(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t wo
   return hipGetLastError();
 }
 
+hipError_t launch_absmax_finish(const float* partials, uint32_t nblocks, uint32_t M, float* scales, hipStream_t s) {
+  hipLaunchKernelGGL(absmax_finish_kernel, dim3(M), dim3(kBlock), 0, s, partials, nblocks, M, scales);
+  return hipGetLastError();
+}
+
 hipError_t launch_absmax(const CodecShape& c, const float* g, const float* gref, const float* gref2,
                          float* partials, float* scales, hipStream_t s) {
   switch (c.norm) {

@@ -82,6 +82,16 @@ __device__ __forceinline__ float normalize(float g, float r1, float r2) {
   return g;
 }
 
+// The same with the kind of normalisation and the raw (unclamped) references as run-time arguments.
+__device__ __forceinline__ float normalize_dyn(int norm, float g, float ref, float ref2, float eps) {
+  switch (norm) {
+    case kNormSub: return g - ref;
+    case kNormQuot: return g / clamp_ref(ref, eps);
+    case kNormComb: return (g - ref) / clamp_ref(ref2, eps);
+    default: return g;
+  }
+}
+
 template <int NORM>
 __device__ __forceinline__ float denormalize(float mean, float r1, float r2) {
   if (NORM == kNormSub) return r1 + mean;

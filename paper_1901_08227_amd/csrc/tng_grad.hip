@@ -40,6 +40,32 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return s;
 }
 
+// Maximum over the workgroup (any size up to 1024 threads); valid in thread 0.  red: 16 floats of LDS.
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  __syncthreads();  // red may still be read from an earlier call
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  const int nw = (blockDim.x + kWave - 1) / kWave;
+  float r = red[0];
+  for (int k = 1; k < nw; ++k) r = fmaxf(r, red[k]);
+  return r;
+}
+
+// Largest |normalize(g)| over the four components of a float4 of gradient values (fused scale pass).
+__device__ __forceinline__ float absmax4(const ScaleFusion& f, const float4& g, const float4& r1, const float4& r2) {
+  return fmaxf(fmaxf(fabsf(normalize_dyn(f.norm, g.x, r1.x, r2.x, f.eps)), fabsf(normalize_dyn(f.norm, g.y, r1.y, r2.y, f.eps))),
+               fmaxf(fabsf(normalize_dyn(f.norm, g.z, r1.z, r2.z, f.eps)), fabsf(normalize_dyn(f.norm, g.w, r1.w, r2.w, f.eps))));
+}
+
+__device__ __forceinline__ void load_refs4(const ScaleFusion& f, uint64_t q, float4& r1, float4& r2) {
+  r1 = make_float4(0.f, 0.f, 0.f, 0.f);
+  r2 = make_float4(1.f, 1.f, 1.f, 1.f);
+  if (f.norm != kNormNone) r1 = reinterpret_cast<const float4*>(f.gref)[q];
+  if (f.norm == kNormComb) r2 = reinterpret_cast<const float4*>(f.gref2)[q];
+}
+
 // sigma(z) - y without cancellation for the labels 0 and 1.
 __device__ __forceinline__ float logistic_residual(float z, float y) {
   const float e = expf(-fabsf(z));           // in (0, 1]
@@ -86,15 +112,17 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_resid_kernel(const float*
 }
 
 // g_m[k] = (1/B) sum_i r_i X[idx_i][k] + l2 w[k]; a thread owns 4 (VEC) or 1 columns.
-template <bool VEC>
+template <bool VEC, bool FUSE>
 __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* const* __restrict__ Xs,
                                                                    const uint32_t* __restrict__ idx,
                                                                    const float* __restrict__ resid,
                                                                    const float* __restrict__ w,
                                                                    float* __restrict__ g, uint64_t d,
-                                                                   uint32_t batch, float inv_b, float l2) {
+                                                                   uint32_t batch, float inv_b, float l2,
+                                                                   ScaleFusion fuse) {
   __shared__ float sR[kBlock];
   __shared__ uint32_t sRow[kBlock];
+  __shared__ float red[16];
   const uint32_t m = blockIdx.y;
   const float* X = Xs[m];
   const uint64_t col = (uint64_t)blockIdx.x * kBlock + threadIdx.x;  // float4 (VEC) or float index
@@ -126,17 +154,28 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
       }
     }
   }
-  if (!active) return;
-  if (VEC) {
-    const float4 wv = reinterpret_cast<const float4*>(w)[col];
-    float4 o;
-    o.x = __builtin_fmaf(l2, wv.x, acc.x * inv_b);
-    o.y = __builtin_fmaf(l2, wv.y, acc.y * inv_b);
-    o.z = __builtin_fmaf(l2, wv.z, acc.z * inv_b);
-    o.w = __builtin_fmaf(l2, wv.w, acc.w * inv_b);
-    reinterpret_cast<float4*>(g + (uint64_t)m * d)[col] = o;
-  } else {
-    g[(uint64_t)m * d + col] = __builtin_fmaf(l2, w[col], acc.x * inv_b);
+  float amax = 0.f;
+  if (active) {
+    if (VEC) {
+      const float4 wv = reinterpret_cast<const float4*>(w)[col];
+      float4 o;
+      o.x = __builtin_fmaf(l2, wv.x, acc.x * inv_b);
+      o.y = __builtin_fmaf(l2, wv.y, acc.y * inv_b);
+      o.z = __builtin_fmaf(l2, wv.z, acc.z * inv_b);
+      o.w = __builtin_fmaf(l2, wv.w, acc.w * inv_b);
+      reinterpret_cast<float4*>(g + (uint64_t)m * d)[col] = o;
+      if (FUSE) {
+        float4 r1, r2;
+        load_refs4(fuse, col, r1, r2);
+        amax = absmax4(fuse, o, r1, r2);
+      }
+    } else {
+      g[(uint64_t)m * d + col] = __builtin_fmaf(l2, w[col], acc.x * inv_b);
+    }
+  }
+  if (FUSE) {
+    amax = block_max(amax, red);
+    if (threadIdx.x == 0) fuse.partials[(uint64_t)blockIdx.x * gridDim.y + m] = amax;
   }
 }
 
@@ -403,31 +442,44 @@ __global__ __launch_bounds__(kBlock) void rosenbrock_kernel(const float* __restr
 
 // d a multiple of 4, 16-byte aligned operands: a thread owns 4 consecutive coordinates; the gradient
 // is computed once and reused for all workers, the noise is streamed with 16-byte loads.
+template <bool FUSE>
 __global__ __launch_bounds__(kBlock) void rosenbrock_vec_kernel(const float* __restrict__ x,
                                                                 const float4* __restrict__ noise4,
-                                                                float4* __restrict__ g4, uint64_t nvec, uint32_t M) {
+                                                                float4* __restrict__ g4, uint64_t nvec, uint32_t M,
+                                                                ScaleFusion fuse) {
+  __shared__ float red[16];
   const uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (q >= nvec) return;
-  const float4 xv = reinterpret_cast<const float4*>(x)[q];
-  const bool first = q == 0, last = q + 1 == nvec;
-  const float xl = first ? 0.f : x[4 * q - 1];
-  const float xr = last ? 0.f : x[4 * q + 4];
-  float4 base;
-  base.x = rosenbrock_component(xl, xv.x, xv.y, !first, true);
-  base.y = rosenbrock_component(xv.x, xv.y, xv.z, true, true);
-  base.z = rosenbrock_component(xv.y, xv.z, xv.w, true, true);
-  base.w = rosenbrock_component(xv.z, xv.w, xr, true, !last);
-#pragma unroll 4
+  const bool active = q < nvec;
+  float4 base = make_float4(0.f, 0.f, 0.f, 0.f), r1 = base, r2 = base;
+  if (active) {
+    const float4 xv = reinterpret_cast<const float4*>(x)[q];
+    const bool first = q == 0, last = q + 1 == nvec;
+    const float xl = first ? 0.f : x[4 * q - 1];
+    const float xr = last ? 0.f : x[4 * q + 4];
+    base.x = rosenbrock_component(xl, xv.x, xv.y, !first, true);
+    base.y = rosenbrock_component(xv.x, xv.y, xv.z, true, true);
+    base.z = rosenbrock_component(xv.y, xv.z, xv.w, true, true);
+    base.w = rosenbrock_component(xv.z, xv.w, xr, true, !last);
+    if (FUSE) load_refs4(fuse, q, r1, r2);
+  }
   for (uint32_t m = 0; m < M; ++m) {
-    float4 o = base;
-    if (noise4 != nullptr) {
-      const float4 n = load_stream(noise4 + (uint64_t)m * nvec + q);
-      o.x = base.x + n.x;
-      o.y = base.y + n.y;
-      o.z = base.z + n.z;
-      o.w = base.w + n.w;
+    float amax = 0.f;
+    if (active) {
+      float4 o = base;
+      if (noise4 != nullptr) {
+        const float4 n = load_stream(noise4 + (uint64_t)m * nvec + q);
+        o.x = base.x + n.x;
+        o.y = base.y + n.y;
+        o.z = base.z + n.z;
+        o.w = base.w + n.w;
+      }
+      g4[(uint64_t)m * nvec + q] = o;
+      if (FUSE) amax = absmax4(fuse, o, r1, r2);
     }
-    g4[(uint64_t)m * nvec + q] = o;
+    if (FUSE) {
+      amax = block_max(amax, red);
+      if (threadIdx.x == 0) fuse.partials[(uint64_t)blockIdx.x * M + m] = amax;
+    }
   }
 }
 
@@ -444,7 +496,8 @@ hipError_t launch_minibatch_indices(uint32_t k0, uint32_t k1, uint32_t iter, uin
 
 hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                     const uint32_t* idx, float* resid, const float* w, float* g,
-                                    hipStream_t s) {
+                                    const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s) {
+  if (fused_rows != nullptr) *fused_rows = 0;
   // Shards are required to be 16-byte aligned; rows stay aligned only when d is a multiple of 4.
   const bool vec = d % 4 == 0 && aligned16(w) && aligned16(g);
   const float inv_b = 1.0f / (float)batch;
@@ -453,14 +506,21 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
     hipLaunchKernelGGL((logreg_dense_resid_kernel<true>), grid_r, dim3(kBlock), 0, s, p.X, p.y, idx, w, resid, d,
                        batch);
     dim3 grid_g((uint32_t)((d / 4 + kBlock - 1) / kBlock), M);
-    hipLaunchKernelGGL((logreg_dense_grad_kernel<true>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
-                       batch, inv_b, l2);
+    if (fuse != nullptr && fused_rows != nullptr && grid_g.x <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
+        aligned16(fuse->gref2)) {
+      hipLaunchKernelGGL((logreg_dense_grad_kernel<true, true>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
+                         batch, inv_b, l2, *fuse);
+      *fused_rows = grid_g.x;
+    } else {
+      hipLaunchKernelGGL((logreg_dense_grad_kernel<true, false>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
+                         batch, inv_b, l2, ScaleFusion{});
+    }
   } else {
     hipLaunchKernelGGL((logreg_dense_resid_kernel<false>), grid_r, dim3(kBlock), 0, s, p.X, p.y, idx, w, resid,
                        d, batch);
     dim3 grid_g((uint32_t)((d + kBlock - 1) / kBlock), M);
-    hipLaunchKernelGGL((logreg_dense_grad_kernel<false>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
-                       batch, inv_b, l2);
+    hipLaunchKernelGGL((logreg_dense_grad_kernel<false, false>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
+                       batch, inv_b, l2, ScaleFusion{});
   }
   return hipGetLastError();
 }
@@ -478,7 +538,9 @@ uint32_t csr_tiles(uint64_t d) {
 
 hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                   const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,
-                                  const float* w, float* g, hipStream_t s) {
+                                  const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
+                                  hipStream_t s) {
+  if (fused_rows != nullptr) *fused_rows = 0;
   const float inv_b = 1.0f / (float)batch;
   const uint32_t shift = csr_tile_shift(d);
   const uint32_t ntiles = csr_tiles(d);
@@ -497,17 +559,30 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
                      zpart, d, batch, ntiles, shift);
   hipLaunchKernelGGL(csr_z_reduce_kernel, dim3((batch + kBlock - 1) / kBlock, M), dim3(kBlock), 0, s, zpart, z, batch,
                      ntiles);
+  // The scale pass is not fused here: this kernel runs one workgroup per compute unit with its phases
+  // back to back, and the extra reference loads and reduction in its epilogue cost more (+0.8 ms at
+  // d = 2^24, M = 64) than the separate scale pass they would replace (0.7 ms).
+  (void)fuse;
   hipLaunchKernelGGL(csr_grad_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, p.y, idx, rowbase,
                      bounds, z, w, g, d, batch, ntiles, shift, inv_b, l2);
   return hipGetLastError();
 }
 
 hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, float* g,
-                                  hipStream_t s) {
+                                  const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s) {
+  if (fused_rows != nullptr) *fused_rows = 0;
   if (d % 4 == 0 && aligned16(x) && aligned16(noise) && aligned16(g)) {
     const uint64_t nvec = d / 4;
-    hipLaunchKernelGGL(rosenbrock_vec_kernel, dim3((uint32_t)((nvec + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, x,
-                       reinterpret_cast<const float4*>(noise), reinterpret_cast<float4*>(g), nvec, M);
+    const uint32_t blocks = (uint32_t)((nvec + kBlock - 1) / kBlock);
+    if (fuse != nullptr && fused_rows != nullptr && blocks <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
+        aligned16(fuse->gref2)) {
+      hipLaunchKernelGGL(rosenbrock_vec_kernel<true>, dim3(blocks), dim3(kBlock), 0, s, x,
+                         reinterpret_cast<const float4*>(noise), reinterpret_cast<float4*>(g), nvec, M, *fuse);
+      *fused_rows = blocks;
+    } else {
+      hipLaunchKernelGGL(rosenbrock_vec_kernel<false>, dim3(blocks), dim3(kBlock), 0, s, x,
+                         reinterpret_cast<const float4*>(noise), reinterpret_cast<float4*>(g), nvec, M, ScaleFusion{});
+    }
     return hipGetLastError();
   }
   const uint64_t bx = (d + kBlock - 1) / kBlock;

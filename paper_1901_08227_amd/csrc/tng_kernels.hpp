@@ -31,6 +31,21 @@ constexpr uint32_t kAbsmaxMaxBlocks = 4096;
 // kAbsmaxMaxBlocks * M floats.  Two launches: partial maxima per workgroup, then one reduction.
 hipError_t launch_absmax(const CodecShape& c, const float* g, const float* gref, const float* gref2,
                          float* partials, float* scales, hipStream_t s);
+// Reduction of nblocks rows of per-workgroup partial maxima (partials[block][m]) to scales[m].
+hipError_t launch_absmax_finish(const float* partials, uint32_t nblocks, uint32_t M, float* scales, hipStream_t s);
+
+// Optional fusion of the scale pass into a gradient launcher: when it can (vector path, at most
+// kAbsmaxMaxBlocks workgroups per worker), its last kernel also leaves the per-workgroup maxima of
+// |normalize(g)| in partials[block][m] and reports the number of rows; otherwise it reports 0 and the
+// caller runs the scale pass itself.  g is then read once instead of twice per iteration.
+struct ScaleFusion {
+  int norm;
+  float eps;
+  const float* gref;
+  const float* gref2;
+  float* partials;
+};
+
 hipError_t launch_quantize_pack(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
                                 const float* gref2, const float* scales, uint32_t* codes, hipStream_t s);
 // vbar = denorm(mean_m decode).  If w != nullptr also w -= lr * vbar; if ref_out != nullptr also
@@ -52,7 +67,7 @@ hipError_t launch_minibatch_indices(uint32_t k0, uint32_t k1, uint32_t iter, uin
                                     const uint64_t* n_rows, uint32_t* idx, hipStream_t s);
 hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                     const uint32_t* idx, float* resid, const float* w, float* g,
-                                    hipStream_t s);
+                                    const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s);
 // Column tiles of the CSR gradient: 2^kCsrTileShift coordinates (128 KiB of fp64 in LDS).
 constexpr uint32_t kCsrTileShift = 14;
 uint32_t csr_tiles(uint64_t d);
@@ -61,8 +76,9 @@ uint32_t csr_tiles(uint64_t d);
 // Columns must be ascending within each row.
 hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                   const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,
-                                  const float* w, float* g, hipStream_t s);
-hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, float* g,
+                                  const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
                                   hipStream_t s);
+hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, float* g,
+                                  const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s);
 
 }  // namespace tng
