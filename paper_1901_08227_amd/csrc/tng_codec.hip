@@ -341,7 +341,7 @@ __device__ __forceinline__ void store_packed(FragmentBuffer<WPW>& lds, int wave,
   for (int k = 0; k < WPW / kWave; ++k) {
     const uint64_t wi = word_base + (uint64_t)k * kWave + lane;
     const uint32_t word = lds.b32[wave][k * kWave + lane];
-    if (wi < words) __builtin_nontemporal_store(word, row + wi);
+    if (wi < words) store_word_through(row + wi, word);
   }
   wave_lds_fence();
 }

@@ -35,6 +35,15 @@ __device__ __forceinline__ void store_stream(float4* p, const float4& x) {
   __builtin_nontemporal_store(v, reinterpret_cast<v4f_t*>(p));
 }
 
+// Store of a packed word that is not read again by the same kernel.  A small write stream next to a
+// large read stream costs far more HBM time than its bytes; stores marked device-coherent (the sc1
+// cache-policy bit, which is what a relaxed device-scope atomic store compiles to) measured a
+// quarter cheaper for the packed codes than plain or non-temporal stores.  (The same bit on the
+// decoded average made the following quantise pass slower, so that one keeps non-temporal stores.)
+__device__ __forceinline__ void store_word_through(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // a ^ b ^ c in one instruction (three-input bitwise op of gfx950, truth table 0x96).
 __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
   return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
