@@ -500,7 +500,7 @@ __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
         const uint64_t wi = word_base + wl;
         wreg[mm][k] = 0u;
         if ((uint32_t)mm < cnt && wl < (uint32_t)WORDS && wi < words)
-          wreg[mm][k] = __builtin_nontemporal_load(codes + (uint64_t)(m_base + mm) * words + wi);
+          wreg[mm][k] = codes[(uint64_t)(m_base + mm) * words + wi];
       }
     }
     __syncthreads();  // the previous trip's LDS reads are done
