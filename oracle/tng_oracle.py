@@ -48,6 +48,10 @@ NORM_NONE = 0  # v = g                       (reference = zeros: plain compresse
 NORM_SUB = 1   # Eq. 1
 NORM_QUOT = 2  # Eq. 2
 NORM_COMB = 3  # combined two-reference form
+NORM_MEAN = 4  # Eq. 1 with the per-worker reference mean(g_m) * ones(D); mean(g_m) travels as one scalar
+
+SCALE_MAX = 0  # R = max_d |v_d|   (the paper's coder)
+SCALE_L2 = 1   # R = ||v||_2       (the scale of the cited multi-level quantiser, QSGD)
 
 REF_ZERO = 0        # g~ stays zeros (Algorithm 1's initial value; the C_nz = 1 case)
 REF_LAST_AVG = 1    # g~ <- averaged decoded gradient of the last iteration
@@ -71,6 +75,7 @@ class Config:
     l2: float = 0.0
     batch: int = 0
     ref_window: int = 1      # tau_max for REF_WINDOW_AVG
+    scale_kind: int = SCALE_MAX
 
 
 # --------------------------------------------------------------------------------------
@@ -211,6 +216,55 @@ def grad_rosenbrock(x, noise=None):
 
 
 # --------------------------------------------------------------------------------------
+# Sums that decide codes (a per-worker mean, an l2 norm) must not depend on who adds in which
+# order, so their order is part of the definition: float64 terms, added
+#   - within a chunk of 4096 consecutive elements: lane j (0..255) adds elements j, j+256, ...,
+#     j+3840 in that order; then the 256 lane sums are added in lane order;
+#   - chunk sums are added in order within groups of 256 consecutive chunks;
+#   - group sums are added in order.
+# Positions past the end count as +0 (adding +0 is exact).
+# --------------------------------------------------------------------------------------
+TREE_CHUNK = 4096
+TREE_LANES = 256
+TREE_GROUP = 256
+
+
+def tree_sum64(x):
+    """Sum of a vector of float64 terms in the fixed order described above."""
+    x = np.asarray(x, dtype=np.float64).reshape(-1)
+    n = x.size
+    if n == 0:
+        return np.float64(0.0)
+    nch = -(-n // TREE_CHUNK)
+    xp = np.zeros(nch * TREE_CHUNK, dtype=np.float64)
+    xp[:n] = x
+    xp = xp.reshape(nch, TREE_CHUNK // TREE_LANES, TREE_LANES)
+    lane = np.zeros((nch, TREE_LANES), dtype=np.float64)
+    for k in range(TREE_CHUNK // TREE_LANES):
+        lane = lane + xp[:, k, :]
+    chunk = np.zeros(nch, dtype=np.float64)
+    for j in range(TREE_LANES):
+        chunk = chunk + lane[:, j]
+    ngr = -(-nch // TREE_GROUP)
+    cp = np.zeros(ngr * TREE_GROUP, dtype=np.float64)
+    cp[:nch] = chunk
+    cp = cp.reshape(ngr, TREE_GROUP)
+    group = np.zeros(ngr, dtype=np.float64)
+    for j in range(TREE_GROUP):
+        group = group + cp[:, j]
+    total = np.float64(0.0)
+    for q in range(ngr):
+        total = total + group[q]
+    return total
+
+
+def worker_mean(g_row):
+    """mean(g) of section "Reference Vectors" (first option): float32(tree sum of the elements / D)."""
+    g_row = np.asarray(g_row, dtype=F32)
+    return F32(tree_sum64(g_row.astype(np.float64)) / np.float64(g_row.size))
+
+
+# --------------------------------------------------------------------------------------
 # Normalisation  (section "Normalized Gradients")
 # --------------------------------------------------------------------------------------
 def clamp_reference(gref, eps):
@@ -220,11 +274,13 @@ def clamp_reference(gref, eps):
     return np.where(np.abs(gref) < eps, np.copysign(eps, gref), gref).astype(F32)
 
 
-def normalize(g, gref, norm: int, eps=1e-8, gref2=None):
-    """The vector that is handed to the coder Q: g, g - g~, g ./ g~ or (g - g~) ./ g~'."""
+def normalize(g, gref, norm: int, eps=1e-8, gref2=None, mu=None):
+    """The vector that is handed to the coder Q: g, g - g~, g ./ g~, (g - g~) ./ g~' or g - mean(g)."""
     g = np.asarray(g, dtype=F32)
     if norm == NORM_NONE:
         return g.copy()
+    if norm == NORM_MEAN:
+        return g - F32(worker_mean(g) if mu is None else mu)
     if norm == NORM_SUB:
         return g - np.asarray(gref, dtype=F32)
     if norm == NORM_QUOT:
@@ -237,7 +293,7 @@ def normalize(g, gref, norm: int, eps=1e-8, gref2=None):
 def denormalize(mean, gref, norm: int, eps=1e-8, gref2=None):
     """v = mean, g~ + mean, g~ (.) mean or g~' (.) mean + g~  (the decode halves of Eqs. 1, 2)."""
     mean = np.asarray(mean, dtype=F32)
-    if norm == NORM_NONE:
+    if norm == NORM_NONE or norm == NORM_MEAN:   # NORM_MEAN: each worker's mean is added back before averaging
         return mean.copy()
     if norm == NORM_SUB:
         return np.asarray(gref, dtype=F32) + mean
@@ -257,10 +313,15 @@ def levels_of(bits: int) -> int:
     return (1 << (bits - 1)) - 1
 
 
-def scale_of(v):
-    """R = max_d |v_d|; a scale below the smallest normal number is taken as 0."""
+def scale_of(v, kind: int = SCALE_MAX):
+    """R = max_d |v_d|, or ||v||_2 = float32(sqrt(tree sum of the exact squares)); a scale below
+    the smallest normal number is taken as 0."""
     v = np.asarray(v, dtype=F32)
-    R = F32(np.max(np.abs(v))) if v.size else F32(0.0)
+    if kind == SCALE_L2:
+        v64 = v.astype(np.float64)
+        R = F32(np.sqrt(tree_sum64(v64 * v64)))       # squares of binary32 values are exact in binary64
+    else:
+        R = F32(np.max(np.abs(v))) if v.size else F32(0.0)
     return F32(0.0) if R < FLT_MIN else R
 
 
@@ -328,18 +389,26 @@ def dequantize(level, neg, R, bits: int):
 # --------------------------------------------------------------------------------------
 # The five operations of the iteration
 # --------------------------------------------------------------------------------------
-def normalize_encode(cfg: Config, it: int, g, gref, gref2=None):
+def worker_means(g):
+    """Per-worker scalars of NORM_MEAN, float32[M]."""
+    return np.array([worker_mean(row) for row in np.asarray(g, dtype=F32)], dtype=F32)
+
+
+def normalize_encode(cfg: Config, it: int, g, gref, gref2=None, means=None):
     """Workers' side of Algorithm 1: for each m, normalise, R_m, sample, pack.
 
-    g float32[M][d] -> (codes uint32[M][words], scales float32[M]).
+    g float32[M][d] -> (codes uint32[M][words], scales float32[M]).  For NORM_MEAN the per-worker
+    means (worker_means(g) unless given) are the third thing a worker transmits.
     """
     g = np.asarray(g, dtype=F32)
     M, d = g.shape
     codes = np.zeros((M, words_per_row(d, cfg.bits)), dtype=U32)
     scales = np.zeros(M, dtype=F32)
+    if cfg.norm == NORM_MEAN and means is None:
+        means = worker_means(g)
     for m in range(M):
-        v = normalize(g[m], gref, cfg.norm, cfg.quot_eps, gref2)
-        R = scale_of(v)
+        v = normalize(g[m], gref, cfg.norm, cfg.quot_eps, gref2, None if means is None else means[m])
+        R = scale_of(v, cfg.scale_kind)
         u = uniform_from_word(quant_draw_words(cfg.seed, it, m, d))
         level, neg = quantize(v, R, cfg.bits, u)
         codes[m] = pack(level, neg, cfg.bits)
@@ -347,13 +416,17 @@ def normalize_encode(cfg: Config, it: int, g, gref, gref2=None):
     return codes, scales
 
 
-def decode_aggregate(cfg: Config, codes, scales, gref, d: int, gref2=None):
-    """Server's side: decode every worker, average in worker order, undo the normalisation."""
+def decode_aggregate(cfg: Config, codes, scales, gref, d: int, gref2=None, means=None):
+    """Server's side: decode every worker, average in worker order, undo the normalisation.
+    NORM_MEAN: worker m's value is mean_m + decoded (one rounding) before it is added."""
     M = codes.shape[0]
     acc = np.zeros(d, dtype=F32)
     for m in range(M):
         level, neg = unpack(codes[m], d, cfg.bits)
-        acc = acc + dequantize(level, neg, scales[m], cfg.bits)
+        val = dequantize(level, neg, scales[m], cfg.bits)
+        if cfg.norm == NORM_MEAN:
+            val = F32(means[m]) + val
+        acc = acc + val
     mean = acc * (F32(1.0) / F32(M))
     return denormalize(mean, gref, cfg.norm, cfg.quot_eps, gref2)
 
@@ -390,8 +463,9 @@ def step(cfg: Config, it: int, w, gref, g, gref2=None, history=None):
     history: the decoded averages of the earlier iterations, oldest first (only read by the
     window-average reference).  Returns (w_next, gref_next, codes, scales, vbar).
     """
-    codes, scales = normalize_encode(cfg, it, g, gref, gref2)
-    vbar = decode_aggregate(cfg, codes, scales, gref, g.shape[1], gref2)
+    means = worker_means(g) if cfg.norm == NORM_MEAN else None
+    codes, scales = normalize_encode(cfg, it, g, gref, gref2, means)
+    vbar = decode_aggregate(cfg, codes, scales, gref, g.shape[1], gref2, means)
     w_next = update_iterate(w, vbar, cfg.lr)
     past = None if history is None else list(history) + [vbar]
     gref_next = update_reference(cfg, it, vbar, gref, past)

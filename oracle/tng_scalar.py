@@ -62,16 +62,53 @@ def normalized(gd, rd, norm, eps, r2d=None):
     raise ValueError(norm)
 
 
-def encode_row(g_row, gref, norm, eps, bits, seed, it, m, gref2=None):
+def ordered_sum(terms):
+    """Sum of Python floats (binary64) in the fixed order: 4096-element chunks, inside a chunk 256
+    strided lanes each added in order, the lanes added in order; chunks added in order inside groups
+    of 256; groups added in order."""
+    n = len(terms)
+    chunk_sums = []
+    for c0 in range(0, n, 4096):
+        lanes = [0.0] * 256
+        for k in range(16):
+            for j in range(256):
+                e = c0 + 256 * k + j
+                if e < n:
+                    lanes[j] = lanes[j] + float(terms[e])
+        acc = 0.0
+        for j in range(256):
+            acc = acc + lanes[j]
+        chunk_sums.append(acc)
+    total = 0.0
+    for g0 in range(0, len(chunk_sums), 256):
+        acc = 0.0
+        for c in chunk_sums[g0:g0 + 256]:
+            acc = acc + c
+        total = total + acc
+    return total
+
+
+def row_mean(g_row):
+    return f32(ordered_sum([float(f32(x)) for x in g_row]) / float(len(g_row)))
+
+
+def encode_row(g_row, gref, norm, eps, bits, seed, it, m, gref2=None, scale_kind=0):
     """One worker: returns (list of packed 32-bit words, R)."""
     d = len(g_row)
     s = (1 << (bits - 1)) - 1
-    v = [normalized(g_row[e], gref[e], norm, eps, None if gref2 is None else gref2[e])
-         for e in range(d)]
+    if norm == 4:
+        mu = row_mean(g_row)
+        v = [f32(f32(g_row[e]) - mu) for e in range(d)]
+    else:
+        v = [normalized(g_row[e], gref[e], norm, eps, None if gref2 is None else gref2[e])
+             for e in range(d)]
     R = f32(0.0)
-    for e in range(d):
-        if abs(v[e]) > R:
-            R = f32(abs(v[e]))
+    if scale_kind == 1:
+        R = f32(np.sqrt(ordered_sum([float(x) * float(x) for x in v])))
+    else:
+        for e in range(d):
+            if abs(v[e]) > R:
+                R = f32(abs(v[e]))
     if R < f32(1.17549435e-38):
         R = f32(0.0)
     per = 32 // bits
@@ -92,7 +129,7 @@ def encode_row(g_row, gref, norm, eps, bits, seed, it, m, gref2=None):
     return words, R
 
 
-def decode_mean(words_rows, scales, gref, norm, eps, bits, d, gref2=None):
+def decode_mean(words_rows, scales, gref, norm, eps, bits, d, gref2=None, means=None):
     """Server: decode all rows, add in worker order, scale by 1/M, undo the normalisation."""
     M = len(words_rows)
     s = (1 << (bits - 1)) - 1
@@ -112,9 +149,11 @@ def decode_mean(words_rows, scales, gref, norm, eps, bits, d, gref2=None):
                 mag = f32(f32(R / f32(s)) * f32(lvl))
             if sign and lvl > 0:
                 mag = f32(-mag)
+            if norm == 4:
+                mag = f32(f32(means[m]) + mag)
             acc = f32(acc + mag)
         mean = f32(acc * inv_m)
-        if norm == 0:
+        if norm == 0 or norm == 4:
             vb = mean
         elif norm == 1:
             vb = f32(f32(gref[e]) + mean)

@@ -465,7 +465,7 @@ __device__ __forceinline__ void stage_scales(const float* __restrict__ scales, u
 constexpr int kDecodeLoads = 4;
 constexpr int kDecodeWorkers = 8;
 
-template <int NORM, int BITS, int V>
+template <int NORM, int BITS, int V, bool STREAM_CODES>
 __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
     const uint32_t* __restrict__ codes, const float* __restrict__ scales, const float4* ref4,
     const float4* __restrict__ ref24, float4* __restrict__ vbar4, float4* w4, float4* refout4,
@@ -500,7 +500,8 @@ __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
         const uint64_t wi = word_base + wl;
         wreg[mm][k] = 0u;
         if ((uint32_t)mm < cnt && wl < (uint32_t)WORDS && wi < words)
-          wreg[mm][k] = codes[(uint64_t)(m_base + mm) * words + wi];
+          wreg[mm][k] = STREAM_CODES ? __builtin_nontemporal_load(codes + (uint64_t)(m_base + mm) * words + wi)
+                                     : codes[(uint64_t)(m_base + mm) * words + wi];
       }
     }
     __syncthreads();  // the previous trip's LDS reads are done
@@ -692,18 +693,25 @@ hipError_t decode_dispatch(const CodecShape& c, const uint32_t* codes, const flo
   if (vec_ok(c.d, gref, gref2, vbar) && vec_ok(c.d, w, ref_out, nullptr)) {
     const uint64_t nvec = c.d / 4;
     const uint64_t big_tiles = (nvec + kBlock * kDecodeLoads - 1) / (kBlock * kDecodeLoads);
+    // Codes that fit the 256 MiB last-level cache were just written by the quantiser and are rewritten
+    // by the next iteration: ordinary loads keep the lines resident (measured 4 % faster, and the
+    // following quantise pass too); larger code arrays are streamed (measured 17 % faster at 512 MiB).
+    const bool stream_codes = (uint64_t)c.M * c.words * sizeof(uint32_t) > (256ull << 20);
+#define TNG_DECODE_LAUNCH(V, SC, GRID)                                                                          \
+  hipLaunchKernelGGL((decode_vec_kernel<NORM, BITS, V, SC>), dim3((uint32_t)(GRID)), dim3(kBlock), 0, s, codes,  \
+                     scales, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2),      \
+                     reinterpret_cast<float4*>(vbar), reinterpret_cast<float4*>(w),                              \
+                     reinterpret_cast<float4*>(ref_out), nvec, c.words, c.M, c.eps, inv_m, lr)
     if (big_tiles >= 2048) {
-      hipLaunchKernelGGL((decode_vec_kernel<NORM, BITS, kDecodeLoads>), dim3((uint32_t)big_tiles), dim3(kBlock), 0, s,
-                         codes, scales, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2),
-                         reinterpret_cast<float4*>(vbar), reinterpret_cast<float4*>(w),
-                         reinterpret_cast<float4*>(ref_out), nvec, c.words, c.M, c.eps, inv_m, lr);
+      if (stream_codes) {
+        TNG_DECODE_LAUNCH(kDecodeLoads, true, big_tiles);
+      } else {
+        TNG_DECODE_LAUNCH(kDecodeLoads, false, big_tiles);
+      }
     } else {  // few coordinates: small tiles so that every compute unit still gets work
-      hipLaunchKernelGGL((decode_vec_kernel<NORM, BITS, 1>), dim3((uint32_t)((nvec + kBlock - 1) / kBlock)),
-                         dim3(kBlock), 0, s, codes, scales, reinterpret_cast<const float4*>(gref),
-                         reinterpret_cast<const float4*>(gref2), reinterpret_cast<float4*>(vbar),
-                         reinterpret_cast<float4*>(w), reinterpret_cast<float4*>(ref_out), nvec, c.words, c.M, c.eps,
-                         inv_m, lr);
+      TNG_DECODE_LAUNCH(1, false, (nvec + kBlock - 1) / kBlock);
     }
+#undef TNG_DECODE_LAUNCH
     return hipGetLastError();
   }
   const uint64_t blocks = (c.d + kBlock - 1) / kBlock;

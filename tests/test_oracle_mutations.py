@@ -58,8 +58,8 @@ def _m_round_up_on_tie(mp):
 def _m_sign_of_g_instead_of_normalised(mp):          # Algorithm 1 as printed: sign(g), not sign(g - g~)
     orig_ne = O.normalize_encode
 
-    def normalize_encode(cfg, it, g, gref, gref2=None):
-        codes, scales = orig_ne(cfg, it, g, gref, gref2)
+    def normalize_encode(cfg, it, g, gref, gref2=None, means=None):
+        codes, scales = orig_ne(cfg, it, g, gref, gref2, means)
         for m in range(g.shape[0]):
             level, _ = O.unpack(codes[m], g.shape[1], cfg.bits)
             codes[m] = O.pack(level, (g[m] < 0) & (level > 0), cfg.bits)
@@ -72,14 +72,14 @@ def _m_server_forgets_reference(mp):                 # Algorithm 1 as printed: a
 
 
 def _m_signed_max(mp):
-    mp.setattr(O, "scale_of", lambda v: F32(np.max(v)) if np.size(v) else F32(0))
+    mp.setattr(O, "scale_of", lambda v, kind=0: F32(np.max(v)) if np.size(v) else F32(0))
 
 
 def _m_subtraction_reversed(mp):
     orig = O.normalize
-    mp.setattr(O, "normalize", lambda g, gref, norm, eps=1e-8, gref2=None:
+    mp.setattr(O, "normalize", lambda g, gref, norm, eps=1e-8, gref2=None, mu=None:
                (np.asarray(gref, dtype=F32) - np.asarray(g, dtype=F32)) if norm == O.NORM_SUB
-               else orig(g, gref, norm, eps, gref2))
+               else orig(g, gref, norm, eps, gref2, mu))
 
 
 def _m_top_level_through_step(mp):
@@ -108,9 +108,9 @@ def _m_clamp_loses_sign(mp):
 def _m_mean_over_wrong_count(mp):
     orig = O.decode_aggregate
 
-    def decode_aggregate(cfg, codes, scales, gref, d, gref2=None):
+    def decode_aggregate(cfg, codes, scales, gref, d, gref2=None, means=None):
         extra = np.concatenate([codes, np.zeros_like(codes[:1])])
-        return orig(cfg, extra, np.concatenate([scales, np.zeros(1, dtype=F32)]), gref, d, gref2)
+        return orig(cfg, extra, np.concatenate([scales, np.zeros(1, dtype=F32)]), gref, d, gref2, means)
     mp.setattr(O, "decode_aggregate", decode_aggregate)
 
 
