@@ -5,7 +5,8 @@
  * One iteration is Algorithm 1 of the paper with the normalisation of Eqs. 1-2:
  *   every worker m: local gradient g^m(w_t); normalise against the shared reference g~
  *   (v = g - g~, Eq. 1; v = g ./ g~, Eq. 2; v = (g - g~) ./ g~', the combined form given
- *   after Eq. 2); scale R_m = max_d |v_d|; stochastic low-bit code of v/R_m (section
+ *   after Eq. 2; or against the worker's own scalar reference mean(g^m) 1, first entry of the
+ *   list in "Reference Vectors"); scale R_m = max_d |v_d|; stochastic low-bit code of v/R_m (section
  *   "Gradient Compression"); pack;  server: decode, average over m, undo the
  *   normalisation, w <- w - eta v (Background, Eq. "qsgd"), refresh g~ from the decoded
  *   average (sections "Reference Vectors", "Convex Problems").
@@ -59,8 +60,19 @@ typedef enum {
   TNG_NORM_NONE = 0, /* v = g: zero reference, plain compressed SGD (remark after Proposition 2) */
   TNG_NORM_SUB = 1,  /* Eq. 1: v = g - g~,         decoded as g~ + r                           */
   TNG_NORM_QUOT = 2, /* Eq. 2: v = g ./ g~,        decoded as g~ (.) r                         */
-  TNG_NORM_COMB = 3  /* combined: v = (g - g~) ./ g~', decoded as g~' (.) r + g~               */
+  TNG_NORM_COMB = 3, /* combined: v = (g - g~) ./ g~', decoded as g~' (.) r + g~               */
+  TNG_NORM_MEAN = 4  /* per-worker reference mean(g^m) 1 ("Reference Vectors", first entry):
+                        v = g^m - mu_m, mu_m = float(sum_e g^m_e / d) sent along with R_m (32 more
+                        bits per worker); decoded as mu_m + r per worker before averaging.  The
+                        shared reference g~ is not used by the coder.                             */
 } tng_norm;
+
+/* The coder's scale R (section "Gradient Compression": R = max_d |v_d|; the same coder with the
+ * l2 norm as R is the one of the QSGD/TernGrad family the section builds on). */
+typedef enum {
+  TNG_SCALE_MAX = 0, /* R = max_d |v_d|                                                          */
+  TNG_SCALE_L2 = 1   /* R = float(sqrt(sum_d v_d^2)); |v_d| / R <= 1 still holds                  */
+} tng_scale;
 
 /* How the reference is refreshed (section "Reference Vectors"; "Convex Problems"). */
 typedef enum {
@@ -91,6 +103,7 @@ typedef struct {
   uint32_t batch;      /* minibatch rows per worker (logistic problems), >= 1 there             */
   int32_t problem;     /* tng_problem                                                           */
   uint32_t ref_window; /* tau_max >= 1 of TNG_REF_WINDOW_AVG (ignored by the other policies)            */
+  int32_t scale;       /* tng_scale                                                             */
 } tng_config;
 
 /* ceil(d * bits / 32); 0 if bits is not 2 or 4. */
@@ -128,6 +141,15 @@ tng_status tng_set_noise(tng_ctx* ctx, const float* noise);
 tng_status tng_set_reference_history(tng_ctx* ctx, float* history);
 /* Second reference g~' of TNG_NORM_COMB, device [d]; must be set before encode / decode. */
 tng_status tng_set_second_reference(tng_ctx* ctx, const float* gref2);
+/* Per-worker means of TNG_NORM_MEAN, device float[M], 4-byte aligned, owned by the caller: written
+ * by tng_normalize_encode (and the encode part of tng_step), read by tng_decode_aggregate; the third
+ * array, next to codes and scales, that travels from the workers to the server.  Must be set before
+ * encode / decode / step in that mode.
+ * Sums over a row (this mean, and the l2 scale) are taken in binary64 in a fixed order, so that their
+ * float32 rounding is reproducible: chunks of 4096 elements; inside a chunk 256 lanes, lane j adding
+ * elements 256 k + j for k = 0..15 in order, then the lanes in order; chunk sums in order inside
+ * groups of 256 chunks; group sums in order. */
+tng_status tng_set_worker_means(tng_ctx* ctx, float* means);
 
 /* Raw 32-bit draws first .. first+count-1 of the sequence (seed, iter, worker, stream) of the
  * counter-based generator Philox4x32-10 (Salmon et al., SC'11): draw j is output word j & 3 of
@@ -148,7 +170,8 @@ tng_status tng_local_grad(tng_ctx* ctx, uint32_t iter, const float* w, float* g)
 
 /* Workers' side of Algorithm 1 (normalise, R_m, sample, pack).  g: device [M][d]; gref: device
  * [d] (ignored, may be NULL, for TNG_NORM_NONE); codes: device [M][words] (out); scales:
- * device [M] (out), scales[m] = R_m = max_d |v_d| of worker m, taken as 0 below FLT_MIN. */
+ * device [M] (out), scales[m] = R_m of worker m (max_d |v_d|, or the l2 norm for TNG_SCALE_L2),
+ * taken as 0 below FLT_MIN. */
 tng_status tng_normalize_encode(tng_ctx* ctx, uint32_t iter, const float* g, const float* gref,
                                 uint32_t* codes, float* scales);
 

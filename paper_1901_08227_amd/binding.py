@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libtng.so")
 
 TNG_OK = 0
 TNG_ERR_INVALID_ARG, TNG_ERR_BAD_STATE, TNG_ERR_WORKSPACE, TNG_ERR_UNSUPPORTED, TNG_ERR_HIP = 1, 2, 3, 4, 5
-NORM_NONE, NORM_SUB, NORM_QUOT, NORM_COMB = 0, 1, 2, 3
+NORM_NONE, NORM_SUB, NORM_QUOT, NORM_COMB, NORM_MEAN = 0, 1, 2, 3, 4
+SCALE_MAX, SCALE_L2 = 0, 1
 REF_ZERO, REF_LAST_AVG, REF_WINDOW_AVG = 0, 1, 2
 PROB_EXTERNAL, PROB_LOGREG_DENSE, PROB_LOGREG_CSR, PROB_ROSENBROCK = 0, 1, 2, 3
 
@@ -29,6 +30,7 @@ class TngConfig(ctypes.Structure):
         ("ref_policy", ctypes.c_int32), ("ref_period", ctypes.c_uint32),
         ("seed", ctypes.c_uint64), ("lr", ctypes.c_float), ("l2", ctypes.c_float),
         ("batch", ctypes.c_uint32), ("problem", ctypes.c_int32), ("ref_window", ctypes.c_uint32),
+        ("scale", ctypes.c_int32),
     ]
 
 
@@ -60,6 +62,7 @@ def lib() -> ctypes.CDLL:
                                    ctypes.POINTER(vp), ctypes.POINTER(u64)],
             "tng_set_noise": [vp, vp],
             "tng_set_second_reference": [vp, vp],
+            "tng_set_worker_means": [vp, vp],
             "tng_set_reference_history": [vp, vp],
             "tng_set_profile_events": [vp, ctypes.POINTER(vp), u32],
             "tng_rng_draws": [vp, u32, u32, u32, u64, u64, vp],
@@ -111,10 +114,11 @@ class Context:
     """A tng_ctx plus the device workspace it was created on (torch owns the memory)."""
 
     def __init__(self, *, d, M, bits=2, norm=NORM_SUB, quot_eps=1e-8, ref_policy=REF_LAST_AVG, ref_period=1,
-                 seed=0, lr=0.1, l2=0.0, batch=0, problem=PROB_EXTERNAL, ref_window=1, device="cuda:0", stream=None):
+                 seed=0, lr=0.1, l2=0.0, batch=0, problem=PROB_EXTERNAL, ref_window=1, scale=SCALE_MAX, device="cuda:0",
+                 stream=None):
         self.cfg = TngConfig(d=d, M=M, bits=bits, norm=norm, quot_eps=quot_eps, ref_policy=ref_policy,
                              ref_period=ref_period, seed=seed, lr=lr, l2=l2, batch=batch, problem=problem,
-                             ref_window=ref_window)
+                             ref_window=ref_window, scale=scale)
         nbytes = tng_workspace_bytes(self.cfg)
         if nbytes == 0:
             raise TngError(TNG_ERR_INVALID_ARG, "tng_workspace_bytes")
@@ -185,6 +189,12 @@ class Context:
         self._keep["gref2"] = gref2
         _check(lib().tng_set_second_reference(self.handle, _ptr(gref2, torch.float32, self.d, "gref2")),
                "tng_set_second_reference")
+
+    def set_worker_means(self, means):
+        """means: float32 tensor [M]; written by encode, read by decode (per-worker mean reference)."""
+        self._keep["means"] = means
+        _check(lib().tng_set_worker_means(self.handle, _ptr(means, torch.float32, self.M, "means")),
+               "tng_set_worker_means")
 
     def set_profile_events(self, events, slots):
         """events: list of 5*slots hipEvent_t handles (ints), or None to switch the hook off."""

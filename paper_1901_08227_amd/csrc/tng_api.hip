@@ -25,6 +25,7 @@ struct tng_ctx {
   const float* noise;     // Rosenbrock noise, may be null
   const float* gref2;     // second reference of the combined normalisation
   float* history;         // [ref_window][d] ring of decoded averages (window-average reference)
+  double* sums;           // chunk and group sums of the order-pinned row sums (mean reference, l2 scale)
   std::vector<hipEvent_t> prof;  // optional timing events, 5 per slot
   uint32_t prof_slots;
   uint64_t enc_calls, dec_calls;
@@ -41,7 +42,8 @@ bool config_valid(const tng_config* c) {
   if (c->d == 0 || c->d > (1ull << 34)) return false;
   if (c->M == 0 || c->M > 65535u) return false;
   if (c->bits != 2 && c->bits != 4) return false;
-  if (c->norm < TNG_NORM_NONE || c->norm > TNG_NORM_COMB) return false;
+  if (c->norm < TNG_NORM_NONE || c->norm > TNG_NORM_MEAN) return false;
+  if (c->scale != TNG_SCALE_MAX && c->scale != TNG_SCALE_L2) return false;
   if (!(c->quot_eps > 0.0f) || !std::isfinite(c->quot_eps)) return false;
   if (c->ref_policy < TNG_REF_ZERO || c->ref_policy > TNG_REF_WINDOW_AVG) return false;
   if (c->ref_policy == TNG_REF_WINDOW_AVG && (c->ref_window == 0 || c->ref_window > 65536u)) return false;
@@ -54,7 +56,7 @@ bool config_valid(const tng_config* c) {
 }
 
 struct Partition {
-  size_t idx_off, resid_off, tables_off, partials_off, rowbase_off, bounds_off, zpart_off, total;
+  size_t idx_off, resid_off, tables_off, partials_off, rowbase_off, bounds_off, zpart_off, sums_off, total;
 };
 
 Partition partition(const tng_config* c) {
@@ -78,6 +80,9 @@ Partition partition(const tng_config* c) {
   p.zpart_off = off;
   if (c->problem == TNG_PROB_LOGREG_CSR)
     off += round_up((size_t)c->M * c->batch * tng::csr_tiles(c->d) * sizeof(float));
+  p.sums_off = off;
+  if (c->norm == TNG_NORM_MEAN || c->scale == TNG_SCALE_L2)
+    off += round_up(tng::tree_sum_scratch(c->d, c->M) * sizeof(double));
   p.total = off;
   return p;
 }
@@ -123,7 +128,7 @@ tng::LogregData logreg_tables(const tng_ctx* ctx) {
   return p;
 }
 
-bool needs_ref(const tng_config& c) { return c.norm != TNG_NORM_NONE; }
+bool needs_ref(const tng_config& c) { return c.norm != TNG_NORM_NONE && c.norm != TNG_NORM_MEAN; }
 
 inline void mark(tng_ctx* ctx, uint64_t call, int which) {
   if (ctx->prof_slots != 0) (void)hipEventRecord(ctx->prof[5 * (call % ctx->prof_slots) + which], ctx->stream);
@@ -135,9 +140,18 @@ tng_status encode_impl(tng_ctx* ctx, uint32_t iter, const float* g, const float*
                        float* scales, uint32_t fused_rows = 0) {
   const uint64_t call = ctx->enc_calls++;
   mark(ctx, call, 0);
-  hipError_t e = fused_rows > 0
-                     ? tng::launch_absmax_finish(ctx->partials, fused_rows, ctx->cfg.M, scales, ctx->stream)
-                     : tng::launch_absmax(ctx->shape, g, gref, ctx->gref2, ctx->partials, scales, ctx->stream);
+  hipError_t e = hipSuccess;
+  if (ctx->cfg.norm == TNG_NORM_MEAN) {  // the worker's own reference comes first: the scale is taken of g - mu
+    e = tng::launch_worker_means(ctx->shape, g, ctx->sums, ctx->shape.means, ctx->stream);
+    if (e != hipSuccess) return TNG_ERR_HIP;
+  }
+  if (ctx->cfg.scale == TNG_SCALE_L2) {
+    e = tng::launch_l2_scales(ctx->shape, g, gref, ctx->gref2, ctx->sums, scales, ctx->stream);
+  } else if (fused_rows > 0) {
+    e = tng::launch_absmax_finish(ctx->partials, fused_rows, ctx->cfg.M, scales, ctx->stream);
+  } else {
+    e = tng::launch_absmax(ctx->shape, g, gref, ctx->gref2, ctx->partials, scales, ctx->stream);
+  }
   if (e != hipSuccess) return TNG_ERR_HIP;
   mark(ctx, call, 1);
   e = tng::launch_quantize_pack(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, ctx->stream);
@@ -164,6 +178,7 @@ tng_status check_codec_args(const tng_ctx* ctx, const float* g, const float* gre
   if (!aligned(g, 16) || !aligned(gref, 16) || !aligned(vbar, 16)) return TNG_ERR_INVALID_ARG;
   if (!aligned(codes, 4) || !aligned(scales, 4)) return TNG_ERR_INVALID_ARG;
   if (ctx->cfg.norm == TNG_NORM_COMB && ctx->gref2 == nullptr) return TNG_ERR_BAD_STATE;
+  if (ctx->cfg.norm == TNG_NORM_MEAN && ctx->shape.means == nullptr) return TNG_ERR_BAD_STATE;
   return TNG_OK;
 }
 
@@ -268,6 +283,8 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->shape.eps = cfg->quot_eps;
   ctx->shape.k0 = (uint32_t)(cfg->seed & 0xFFFFFFFFull);
   ctx->shape.k1 = (uint32_t)(cfg->seed >> 32);
+  ctx->shape.scale_l2 = cfg->scale == TNG_SCALE_L2 ? 1 : 0;
+  ctx->shape.means = nullptr;
   char* base = static_cast<char*>(workspace);
   ctx->idx = reinterpret_cast<uint32_t*>(base + p.idx_off);
   ctx->resid = reinterpret_cast<float*>(base + p.resid_off);
@@ -276,6 +293,7 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->rowbase = reinterpret_cast<int64_t*>(base + p.rowbase_off);
   ctx->bounds = reinterpret_cast<uint32_t*>(base + p.bounds_off);
   ctx->zpart = reinterpret_cast<float*>(base + p.zpart_off);
+  ctx->sums = reinterpret_cast<double*>(base + p.sums_off);
   ctx->have_dense = ctx->have_csr = false;
   ctx->noise = nullptr;
   ctx->gref2 = nullptr;
@@ -335,6 +353,13 @@ tng_status tng_set_reference_history(tng_ctx* ctx, float* history) {
 tng_status tng_set_second_reference(tng_ctx* ctx, const float* gref2) {
   if (ctx == nullptr || gref2 == nullptr || !aligned(gref2, 16)) return TNG_ERR_INVALID_ARG;
   ctx->gref2 = gref2;
+  return TNG_OK;
+}
+
+tng_status tng_set_worker_means(tng_ctx* ctx, float* means) {
+  if (ctx == nullptr || means == nullptr || !aligned(means, 4)) return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.norm != TNG_NORM_MEAN) return TNG_ERR_BAD_STATE;
+  ctx->shape.means = means;
   return TNG_OK;
 }
 
@@ -408,7 +433,10 @@ tng_status tng_step(tng_ctx* ctx, uint32_t iter, float* w, float* gref, float* g
   uint32_t fused_rows = 0;
   if (ctx->cfg.problem != TNG_PROB_EXTERNAL) {
     const tng::ScaleFusion fuse{ctx->cfg.norm, ctx->cfg.quot_eps, gref, ctx->gref2, ctx->partials};
-    s = local_grad_impl(ctx, iter, w, g, &fuse, &fused_rows);
+    // the maximum can ride along with the gradient kernel; a scale that needs the row mean or an
+    // ordered sum cannot
+    const bool can_fuse = ctx->cfg.norm != TNG_NORM_MEAN && ctx->cfg.scale == TNG_SCALE_MAX;
+    s = local_grad_impl(ctx, iter, w, g, can_fuse ? &fuse : nullptr, can_fuse ? &fused_rows : nullptr);
     if (s != TNG_OK) return s;
   }
   s = encode_impl(ctx, iter, g, gref, codes, scales, fused_rows);

@@ -162,15 +162,15 @@ __device__ __forceinline__ void absmax_load(const float4* __restrict__ row, cons
 
 template <int NORM, bool FULL>
 __device__ __forceinline__ float absmax_reduce(const float4 (&x)[kAbsmaxLoads], const RefTile<NORM> (&rt)[kAbsmaxLoads],
-                                               const uint64_t (&iv)[kAbsmaxLoads], uint64_t nvec) {
+                                               const uint64_t (&iv)[kAbsmaxLoads], uint64_t nvec, float mu) {
   float mx = 0.f;
 #pragma unroll
   for (int j = 0; j < kAbsmaxLoads; ++j) {
     if (FULL || iv[j] < nvec) {
-      const float a0 = fabsf(normalize<NORM>(x[j].x, rt[j].r1.x, rt[j].r2.x));
-      const float a1 = fabsf(normalize<NORM>(x[j].y, rt[j].r1.y, rt[j].r2.y));
-      const float a2 = fabsf(normalize<NORM>(x[j].z, rt[j].r1.z, rt[j].r2.z));
-      const float a3 = fabsf(normalize<NORM>(x[j].w, rt[j].r1.w, rt[j].r2.w));
+      const float a0 = fabsf(normalize_w<NORM>(x[j].x, rt[j].r1.x, rt[j].r2.x, mu));
+      const float a1 = fabsf(normalize_w<NORM>(x[j].y, rt[j].r1.y, rt[j].r2.y, mu));
+      const float a2 = fabsf(normalize_w<NORM>(x[j].z, rt[j].r1.z, rt[j].r2.z, mu));
+      const float a3 = fabsf(normalize_w<NORM>(x[j].w, rt[j].r1.w, rt[j].r2.w, mu));
       mx = fmaxf(mx, fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)));
     }
   }
@@ -180,19 +180,20 @@ __device__ __forceinline__ float absmax_reduce(const float4 (&x)[kAbsmaxLoads], 
 template <int NORM, int MC, bool FULL>
 __device__ __forceinline__ void absmax_rows(const float4* __restrict__ g4, const RefTile<NORM> (&rt)[kAbsmaxLoads],
                                             const uint64_t (&iv)[kAbsmaxLoads], uint64_t nvec, uint32_t m0,
-                                            uint32_t M, float (&mx)[MC]) {
+                                            uint32_t M, const float* __restrict__ means, float (&mx)[MC]) {
   constexpr int L = kAbsmaxLoads;
   float4 xa[L], xb[L];
   // rows past M (only when MC does not divide M) repeat the last row, which leaves its maximum unchanged
   auto row = [&](int mm) { return g4 + (uint64_t)min(m0 + (uint32_t)mm, M - 1) * nvec; };
+  auto mean_of = [&](int mm) { return NORM == kNormMean ? means[min(m0 + (uint32_t)mm, M - 1)] : 0.f; };
   absmax_load<NORM, FULL>(row(0), iv, nvec, xa);
 #pragma unroll
   for (int mm = 0; mm < MC; mm += 2) {
     if (mm + 1 < MC) absmax_load<NORM, FULL>(row(mm + 1), iv, nvec, xb);
-    mx[mm] = fmaxf(mx[mm], absmax_reduce<NORM, FULL>(xa, rt, iv, nvec));
+    mx[mm] = fmaxf(mx[mm], absmax_reduce<NORM, FULL>(xa, rt, iv, nvec, mean_of(mm)));
     if (mm + 1 < MC) {
       if (mm + 2 < MC) absmax_load<NORM, FULL>(row(mm + 2), iv, nvec, xa);
-      mx[mm + 1] = fmaxf(mx[mm + 1], absmax_reduce<NORM, FULL>(xb, rt, iv, nvec));
+      mx[mm + 1] = fmaxf(mx[mm + 1], absmax_reduce<NORM, FULL>(xb, rt, iv, nvec, mean_of(mm + 1)));
     }
   }
 }
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(kBlock) void absmax_vec_kernel(const float4* __rest
                                                             const float4* __restrict__ ref4,
                                                             const float4* __restrict__ ref24,
                                                             float* partials, uint64_t nvec,
-                                                            uint32_t M, float eps) {
+                                                            uint32_t M, float eps, const float* __restrict__ means) {
   constexpr int L = kAbsmaxLoads;
   constexpr uint64_t kWaveTile = (uint64_t)kWave * L;
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -222,9 +223,9 @@ __global__ __launch_bounds__(kBlock) void absmax_vec_kernel(const float4* __rest
       if (full || iv[j] < nvec) rt[j].load(ref4, ref24, iv[j], eps);
     }
     if (full) {
-      absmax_rows<NORM, MC, true>(g4, rt, iv, nvec, m0, M, mx);
+      absmax_rows<NORM, MC, true>(g4, rt, iv, nvec, m0, M, means, mx);
     } else {
-      absmax_rows<NORM, MC, false>(g4, rt, iv, nvec, m0, M, mx);
+      absmax_rows<NORM, MC, false>(g4, rt, iv, nvec, m0, M, means, mx);
     }
   }
   block_max_to_partials<MC>(mx, m0, M, partials);
@@ -235,14 +236,15 @@ __global__ __launch_bounds__(kBlock) void absmax_scalar_kernel(const float* __re
                                                                const float* __restrict__ ref,
                                                                const float* __restrict__ ref2,
                                                                float* partials, uint64_t d, uint32_t M,
-                                                               float eps) {
+                                                               float eps, const float* __restrict__ means) {
   const uint32_t m = blockIdx.y;
+  const float mu = NORM == kNormMean ? means[m] : 0.f;
   float mx[1] = {0.f};
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
   for (uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x; e < d; e += stride) {
     float r1, r2;
     load_ref_scalar<NORM>(ref, ref2, e, eps, r1, r2);
-    mx[0] = fmaxf(mx[0], fabsf(normalize<NORM>(g[(uint64_t)m * d + e], r1, r2)));
+    mx[0] = fmaxf(mx[0], fabsf(normalize_w<NORM>(g[(uint64_t)m * d + e], r1, r2, mu)));
   }
   block_max_to_partials<1>(mx, m, M, partials);
 }
@@ -282,8 +284,8 @@ __device__ __forceinline__ void load_worker_tile(const QuantLane<NORM>& q, const
 // Codes of one worker for this lane's 16 coordinates: four fragments of 4 codes each.
 template <int NORM, int BITS, bool FULL>
 __device__ __forceinline__ void quantize_worker_tile(const QuantLane<NORM>& q, const float4 (&x)[kLoadsPerLane],
-                                                     float R, uint32_t m, uint32_t iter, uint32_t k0, uint32_t k1,
-                                                     uint32_t (&frag)[kLoadsPerLane]) {
+                                                     float R, float mu, uint32_t m, uint32_t iter, uint32_t k0,
+                                                     uint32_t k1, uint32_t (&frag)[kLoadsPerLane]) {
   if (R == 0.f) {
 #pragma unroll
     for (int j = 0; j < kLoadsPerLane; ++j) frag[j] = 0u;
@@ -296,10 +298,10 @@ __device__ __forceinline__ void quantize_worker_tile(const QuantLane<NORM>& q, c
     if (FULL || q.ok[j]) {
       const U32x4 rnd = philox4x32_10((uint32_t)q.iv[j], m, iter, 0u, k0, k1);
       const RefTile<NORM>& rt = q.rt[j];
-      const uint32_t c0 = quantize_code<BITS>(normalize<NORM>(x[j].x, rt.r1.x, rt.r2.x), inv_r, rnd.x);
-      const uint32_t c1 = quantize_code<BITS>(normalize<NORM>(x[j].y, rt.r1.y, rt.r2.y), inv_r, rnd.y);
-      const uint32_t c2 = quantize_code<BITS>(normalize<NORM>(x[j].z, rt.r1.z, rt.r2.z), inv_r, rnd.z);
-      const uint32_t c3 = quantize_code<BITS>(normalize<NORM>(x[j].w, rt.r1.w, rt.r2.w), inv_r, rnd.w);
+      const uint32_t c0 = quantize_code<BITS>(normalize_w<NORM>(x[j].x, rt.r1.x, rt.r2.x, mu), inv_r, rnd.x);
+      const uint32_t c1 = quantize_code<BITS>(normalize_w<NORM>(x[j].y, rt.r1.y, rt.r2.y, mu), inv_r, rnd.y);
+      const uint32_t c2 = quantize_code<BITS>(normalize_w<NORM>(x[j].z, rt.r1.z, rt.r2.z, mu), inv_r, rnd.z);
+      const uint32_t c3 = quantize_code<BITS>(normalize_w<NORM>(x[j].w, rt.r1.w, rt.r2.w, mu), inv_r, rnd.w);
       frag[j] = c0 | (c1 << BITS) | (c2 << (2 * BITS)) | (c3 << (3 * BITS));
     }
   }
@@ -354,18 +356,19 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
                                               const float4* __restrict__ g4, const float* __restrict__ scales,
                                               uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words,
                                               uint64_t word_base, uint32_t m0, uint32_t m_end, uint32_t iter,
-                                              uint32_t k0, uint32_t k1) {
+                                              uint32_t k0, uint32_t k1, const float* __restrict__ means) {
   constexpr int L = kLoadsPerLane;
   float4 xa[L], xb[L];
   uint32_t frag[L];
   load_worker_tile<NORM, FULL>(q, g4, nvec, m0, xa);
   for (uint32_t m = m0; m < m_end; m += 2) {
     if (m + 1 < m_end) load_worker_tile<NORM, FULL>(q, g4, nvec, m + 1, xb);
-    quantize_worker_tile<NORM, BITS, FULL>(q, xa, scales[m], m, iter, k0, k1, frag);
+    quantize_worker_tile<NORM, BITS, FULL>(q, xa, scales[m], NORM == kNormMean ? means[m] : 0.f, m, iter, k0, k1, frag);
     store_packed<BITS, WPW>(lds, wave, lane, frag, codes + (uint64_t)m * words, word_base, words);
     if (m + 1 >= m_end) break;
     if (m + 2 < m_end) load_worker_tile<NORM, FULL>(q, g4, nvec, m + 2, xa);
-    quantize_worker_tile<NORM, BITS, FULL>(q, xb, scales[m + 1], m + 1, iter, k0, k1, frag);
+    quantize_worker_tile<NORM, BITS, FULL>(q, xb, scales[m + 1], NORM == kNormMean ? means[m + 1] : 0.f, m + 1, iter, k0,
+                                           k1, frag);
     store_packed<BITS, WPW>(lds, wave, lane, frag, codes + (uint64_t)(m + 1) * words, word_base, words);
   }
 }
@@ -374,7 +377,7 @@ template <int NORM, int BITS, int MC>
 __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
     const float4* __restrict__ g4, const float4* __restrict__ ref4, const float4* __restrict__ ref24,
     const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words,
-    uint32_t M, float eps, uint32_t k0, uint32_t k1, uint32_t iter) {
+    uint32_t M, float eps, uint32_t k0, uint32_t k1, uint32_t iter, const float* __restrict__ means) {
   constexpr int L = kLoadsPerLane;
   constexpr int WPW = kWave * L * 4 * BITS / 32;  // packed words per wavefront tile
   __shared__ FragmentBuffer<WPW> lds;
@@ -394,10 +397,10 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
   const uint32_t m_end = min(m0 + MC, M);
   if ((wave_tile + 1) * (kWave * L) <= nvec) {  // wave-uniform
     quantize_rows<NORM, BITS, WPW, true>(q, lds, wave, lane, g4, scales, codes, nvec, words, word_base, m0, m_end,
-                                         iter, k0, k1);
+                                         iter, k0, k1, means);
   } else {
     quantize_rows<NORM, BITS, WPW, false>(q, lds, wave, lane, g4, scales, codes, nvec, words, word_base, m0, m_end,
-                                          iter, k0, k1);
+                                          iter, k0, k1, means);
   }
 }
 
@@ -406,9 +409,10 @@ template <int NORM, int BITS>
 __global__ __launch_bounds__(kBlock) void quantize_pack_scalar_kernel(
     const float* __restrict__ g, const float* __restrict__ ref, const float* __restrict__ ref2,
     const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t d, uint64_t words, uint32_t M,
-    float eps, uint32_t k0, uint32_t k1, uint32_t iter) {
+    float eps, uint32_t k0, uint32_t k1, uint32_t iter, const float* __restrict__ means) {
   constexpr int PER = 32 / BITS;
   const uint32_t m = blockIdx.y;
+  const float mu = NORM == kNormMean ? means[m] : 0.f;
   const float R = scales[m];
   const float inv_r = R != 0.f ? 1.0f / R : 0.f;
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
@@ -427,7 +431,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_scalar_kernel(
           if (e < d) {
             float r1, r2;
             load_ref_scalar<NORM>(ref, ref2, e, eps, r1, r2);
-            const float v = normalize<NORM>(g[(uint64_t)m * d + e], r1, r2);
+            const float v = normalize_w<NORM>(g[(uint64_t)m * d + e], r1, r2, mu);
             word |= quantize_code<BITS>(v, inv_r, rw[k]) << ((q * 4 + k) * BITS);
           }
         }
@@ -469,7 +473,7 @@ template <int NORM, int BITS, int V, bool STREAM_CODES>
 __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
     const uint32_t* __restrict__ codes, const float* __restrict__ scales, const float4* ref4,
     const float4* __restrict__ ref24, float4* __restrict__ vbar4, float4* w4, float4* refout4,
-    uint64_t nvec, uint64_t words, uint32_t M, float eps, float inv_m, float lr) {
+    uint64_t nvec, uint64_t words, uint32_t M, float eps, float inv_m, float lr, const float* __restrict__ means) {
   constexpr int MCH = kDecodeWorkers;
   constexpr int FPW = 32 / (4 * BITS);     // 4-code fragments per packed word: 4 (ternary) or 2
   constexpr int WPT = (V + FPW - 1) / FPW; // packed words per thread and worker (some threads idle when V < FPW)
@@ -514,7 +518,8 @@ __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
     if (threadIdx.x < cnt * TAB) {
       const uint32_t mm = threadIdx.x / TAB, code = threadIdx.x % TAB;
       const float R = scales[m_base + mm];
-      table[threadIdx.x] = decode_code<BITS>(code, R, R / S);
+      const float val = decode_code<BITS>(code, R, R / S);
+      table[threadIdx.x] = NORM == kNormMean ? means[m_base + mm] + val : val;  // the worker's mean is added back
     }
     __syncthreads();
     for (uint32_t mm = 0; mm < cnt; ++mm) {
@@ -561,7 +566,7 @@ template <int NORM, int BITS>
 __global__ __launch_bounds__(kBlock) void decode_scalar_kernel(
     const uint32_t* __restrict__ codes, const float* __restrict__ scales, const float* ref,
     const float* __restrict__ ref2, float* __restrict__ vbar, float* __restrict__ w, float* refout, uint64_t d,
-    uint64_t words, uint32_t M, float eps, float inv_m, float lr) {
+    uint64_t words, uint32_t M, float eps, float inv_m, float lr, const float* __restrict__ means) {
   __shared__ float sR[kScaleChunk], sStep[kScaleChunk];
   constexpr int PER = 32 / BITS;
   constexpr uint32_t MASK = (1u << BITS) - 1u;
@@ -576,7 +581,8 @@ __global__ __launch_bounds__(kBlock) void decode_scalar_kernel(
       const uint32_t cnt = min((uint32_t)kScaleChunk, M - m_base);
       for (uint32_t mm = 0; mm < cnt; ++mm) {
         const uint32_t word = codes[(uint64_t)(m_base + mm) * words + wi];
-        acc = acc + decode_code<BITS>((word >> sh) & MASK, sR[mm], sStep[mm]);
+        const float val = decode_code<BITS>((word >> sh) & MASK, sR[mm], sStep[mm]);
+        acc = acc + (NORM == kNormMean ? means[m_base + mm] + val : val);
       }
     }
   }
@@ -590,6 +596,122 @@ __global__ __launch_bounds__(kBlock) void decode_scalar_kernel(
     w[e] = w[e] - p;
   }
   if (refout != nullptr) refout[e] = v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Order-pinned float64 sums per worker: the mean of the per-worker mean reference (section
+// "Reference Vectors", first option) and the l2 norm as the coder's scale.
+// ------------------------------------------------------------------------------------------
+// The sum of a row is defined with a fixed association so that its float32 rounding is reproducible:
+// elements are cut into chunks of 4096; inside a chunk lane j (0..255) adds the elements 256 k + j,
+// k = 0..15 in order, and the 256 lane sums are added in lane order; chunk sums are added in order
+// inside groups of 256 chunks, group sums in order.  One wavefront owns a chunk: thread t holds
+// lanes 4t..4t+3 (one float4 per k), so every load instruction covers 1 KiB of contiguous memory.
+constexpr int kTreeChunk = 4096;
+constexpr int kTreeLanes = 256;
+constexpr int kTreeGroup = 256;
+
+template <int NORM, bool SQUARE, bool VEC>
+__global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restrict__ g, const float* __restrict__ ref,
+                                                            const float* __restrict__ ref2,
+                                                            const float* __restrict__ means,
+                                                            double* __restrict__ chunk_sums, uint64_t d,
+                                                            uint64_t nchunks, float eps) {
+  __shared__ double lanes[kWavesPerBlock][kTreeLanes];
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const uint32_t m = blockIdx.y;
+  const uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (chunk >= nchunks) return;  // whole wavefront; no workgroup barrier below
+  const float* __restrict__ row = g + (uint64_t)m * d;
+  const float mu = (SQUARE && NORM == kNormMean) ? means[m] : 0.f;
+  const uint64_t base = chunk * kTreeChunk + 4u * (uint32_t)lane;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  constexpr int K = kTreeChunk / kTreeLanes;
+  if (VEC) {
+    const bool full = (chunk + 1) * kTreeChunk <= d;
+    float4 x[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const uint64_t e = base + (uint64_t)k * kTreeLanes;
+      x[k] = (full || e < d) ? load_stream(reinterpret_cast<const float4*>(row + e)) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const uint64_t e = base + (uint64_t)k * kTreeLanes;
+      float4 v = x[k];
+      if (SQUARE && (full || e < d)) {
+        RefTile<NORM> rt;
+        rt.load(reinterpret_cast<const float4*>(ref), reinterpret_cast<const float4*>(ref2), e / 4, eps);
+        v.x = normalize_w<NORM>(v.x, rt.r1.x, rt.r2.x, mu);
+        v.y = normalize_w<NORM>(v.y, rt.r1.y, rt.r2.y, mu);
+        v.z = normalize_w<NORM>(v.z, rt.r1.z, rt.r2.z, mu);
+        v.w = normalize_w<NORM>(v.w, rt.r1.w, rt.r2.w, mu);
+      }
+      const double t0 = (double)v.x, t1 = (double)v.y, t2 = (double)v.z, t3 = (double)v.w;
+      acc[0] = acc[0] + (SQUARE ? t0 * t0 : t0);  // the square of a binary32 value is exact in binary64
+      acc[1] = acc[1] + (SQUARE ? t1 * t1 : t1);
+      acc[2] = acc[2] + (SQUARE ? t2 * t2 : t2);
+      acc[3] = acc[3] + (SQUARE ? t3 * t3 : t3);
+    }
+  } else {
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint64_t e = base + (uint64_t)k * kTreeLanes + i;
+        if (e < d) {
+          float v = row[e];
+          if (SQUARE) {
+            float r1, r2;
+            load_ref_scalar<NORM>(ref, ref2, e, eps, r1, r2);
+            v = normalize_w<NORM>(v, r1, r2, mu);
+          }
+          const double t = (double)v;
+          acc[i] = acc[i] + (SQUARE ? t * t : t);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) lanes[wave][4 * lane + i] = acc[i];
+  wave_lds_fence();
+  if (lane == 0) {
+    double total = 0.0;
+#pragma unroll 16
+    for (int j = 0; j < kTreeLanes; ++j) total = total + lanes[wave][j];
+    chunk_sums[(uint64_t)m * nchunks + chunk] = total;
+  }
+}
+
+// One workgroup per worker: group sums (thread q adds the chunks of groups q, q + 256, ... in order),
+// then thread 0 adds the groups in order.  MEAN: out[m] = float(total / d).  Otherwise
+// out[m] = float(sqrt(total)), 0 when below FLT_MIN.  Division and square root of binary64 are
+// correctly rounded on the device, so the float32 result is the same as on any IEEE host.
+template <bool MEAN>
+__global__ __launch_bounds__(kBlock) void tree_finish_kernel(const double* __restrict__ chunk_sums,
+                                                             double* __restrict__ group_sums, uint64_t nchunks,
+                                                             uint64_t ngroups, uint64_t d, float* __restrict__ out) {
+  const uint32_t m = blockIdx.x;
+  const double* __restrict__ cs = chunk_sums + (uint64_t)m * nchunks;
+  double* __restrict__ gs = group_sums + (uint64_t)m * ngroups;
+  for (uint64_t q = threadIdx.x; q < ngroups; q += kBlock) {
+    const uint64_t c0 = q * kTreeGroup;
+    const uint64_t c1 = c0 + kTreeGroup < nchunks ? c0 + kTreeGroup : nchunks;
+    double a = 0.0;
+    for (uint64_t c = c0; c < c1; ++c) a = a + cs[c];
+    gs[q] = a;
+  }
+  __threadfence_block();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double total = 0.0;
+    for (uint64_t q = 0; q < ngroups; ++q) total = total + gs[q];
+    if (MEAN) {
+      out[m] = (float)(total / (double)d);
+    } else {
+      const float r = (float)sqrt(total);
+      out[m] = r < FLT_MIN ? 0.f : r;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -623,7 +745,7 @@ hipError_t absmax_vec_launch(const CodecShape& c, const float* g, const float* g
   dim3 grid(gx, (c.M + MC - 1) / MC);
   hipLaunchKernelGGL((absmax_vec_kernel<NORM, MC>), grid, dim3(kBlock), 0, s,
                      reinterpret_cast<const float4*>(g), reinterpret_cast<const float4*>(gref),
-                     reinterpret_cast<const float4*>(gref2), partials, nvec, c.M, c.eps);
+                     reinterpret_cast<const float4*>(gref2), partials, nvec, c.M, c.eps, c.means);
   return hipGetLastError();
 }
 
@@ -644,7 +766,7 @@ hipError_t absmax_dispatch(const CodecShape& c, const float* g, const float* gre
     const uint32_t per_y = div_up_u32(c.d, kBlock);
     nblocks = per_y < kAbsmaxMaxBlocks ? per_y : kAbsmaxMaxBlocks;
     hipLaunchKernelGGL((absmax_scalar_kernel<NORM>), dim3(nblocks, c.M), dim3(kBlock), 0, s, g, gref, gref2,
-                       partials, c.d, c.M, c.eps);
+                       partials, c.d, c.M, c.eps, c.means);
     e = hipGetLastError();
   }
   if (e != hipSuccess) return e;
@@ -661,7 +783,7 @@ hipError_t quantize_vec_launch(const CodecShape& c, uint32_t iter, const float* 
   hipLaunchKernelGGL((quantize_pack_vec_kernel<NORM, BITS, MC>), grid, dim3(kBlock), 0, s,
                      reinterpret_cast<const float4*>(g), reinterpret_cast<const float4*>(gref),
                      reinterpret_cast<const float4*>(gref2), scales, codes, nvec, c.words, c.M, c.eps, c.k0,
-                     c.k1, iter);
+                     c.k1, iter, c.means);
   return hipGetLastError();
 }
 
@@ -681,7 +803,7 @@ hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g,
   const uint32_t per_y = div_up_u32(c.words, kBlock);
   dim3 grid(per_y < 65536u ? per_y : 65536u, c.M);
   hipLaunchKernelGGL((quantize_pack_scalar_kernel<NORM, BITS>), grid, dim3(kBlock), 0, s, g, gref, gref2,
-                     scales, codes, c.d, c.words, c.M, c.eps, c.k0, c.k1, iter);
+                     scales, codes, c.d, c.words, c.M, c.eps, c.k0, c.k1, iter, c.means);
   return hipGetLastError();
 }
 
@@ -701,7 +823,7 @@ hipError_t decode_dispatch(const CodecShape& c, const uint32_t* codes, const flo
   hipLaunchKernelGGL((decode_vec_kernel<NORM, BITS, V, SC>), dim3((uint32_t)(GRID)), dim3(kBlock), 0, s, codes,  \
                      scales, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2),      \
                      reinterpret_cast<float4*>(vbar), reinterpret_cast<float4*>(w),                              \
-                     reinterpret_cast<float4*>(ref_out), nvec, c.words, c.M, c.eps, inv_m, lr)
+                     reinterpret_cast<float4*>(ref_out), nvec, c.words, c.M, c.eps, inv_m, lr, c.means)
     if (big_tiles >= 2048) {
       if (stream_codes) {
         TNG_DECODE_LAUNCH(kDecodeLoads, true, big_tiles);
@@ -716,7 +838,7 @@ hipError_t decode_dispatch(const CodecShape& c, const uint32_t* codes, const flo
   }
   const uint64_t blocks = (c.d + kBlock - 1) / kBlock;
   hipLaunchKernelGGL((decode_scalar_kernel<NORM, BITS>), dim3((uint32_t)blocks), dim3(kBlock), 0, s, codes,
-                     scales, gref, gref2, vbar, w, ref_out, c.d, c.words, c.M, c.eps, inv_m, lr);
+                     scales, gref, gref2, vbar, w, ref_out, c.d, c.words, c.M, c.eps, inv_m, lr, c.means);
   return hipGetLastError();
 }
 
@@ -770,7 +892,52 @@ hipError_t launch_absmax(const CodecShape& c, const float* g, const float* gref,
     case kNormNone: return absmax_dispatch<kNormNone>(c, g, nullptr, nullptr, partials, scales, s);
     case kNormSub: return absmax_dispatch<kNormSub>(c, g, gref, nullptr, partials, scales, s);
     case kNormQuot: return absmax_dispatch<kNormQuot>(c, g, gref, nullptr, partials, scales, s);
+    case kNormMean: return absmax_dispatch<kNormMean>(c, g, nullptr, nullptr, partials, scales, s);
     default: return absmax_dispatch<kNormComb>(c, g, gref, gref2, partials, scales, s);
+  }
+}
+
+size_t tree_sum_scratch(uint64_t d, uint32_t M) {
+  const uint64_t nchunks = (d + kTreeChunk - 1) / kTreeChunk;
+  const uint64_t ngroups = (nchunks + kTreeGroup - 1) / kTreeGroup;
+  return (size_t)((nchunks + ngroups) * M);
+}
+
+namespace {
+template <int NORM, bool SQUARE>
+hipError_t tree_sum_launch(const CodecShape& c, const float* g, const float* gref, const float* gref2, double* sums,
+                           float* out, hipStream_t s) {
+  const uint64_t nchunks = (c.d + kTreeChunk - 1) / kTreeChunk;
+  const uint64_t ngroups = (nchunks + kTreeGroup - 1) / kTreeGroup;
+  double* group_sums = sums + nchunks * c.M;
+  dim3 grid((uint32_t)((nchunks + kWavesPerBlock - 1) / kWavesPerBlock), c.M);
+  if (vec_ok(c.d, g, gref, gref2)) {
+    hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, true>), grid, dim3(kBlock), 0, s, g, gref, gref2, c.means,
+                       sums, c.d, nchunks, c.eps);
+  } else {
+    hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, false>), grid, dim3(kBlock), 0, s, g, gref, gref2, c.means,
+                       sums, c.d, nchunks, c.eps);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((tree_finish_kernel<!SQUARE>), dim3(c.M), dim3(kBlock), 0, s, sums, group_sums, nchunks,
+                     ngroups, c.d, out);
+  return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_worker_means(const CodecShape& c, const float* g, double* sums, float* means, hipStream_t s) {
+  return tree_sum_launch<kNormNone, false>(c, g, nullptr, nullptr, sums, means, s);
+}
+
+hipError_t launch_l2_scales(const CodecShape& c, const float* g, const float* gref, const float* gref2, double* sums,
+                            float* scales, hipStream_t s) {
+  switch (c.norm) {
+    case kNormNone: return tree_sum_launch<kNormNone, true>(c, g, nullptr, nullptr, sums, scales, s);
+    case kNormSub: return tree_sum_launch<kNormSub, true>(c, g, gref, nullptr, sums, scales, s);
+    case kNormQuot: return tree_sum_launch<kNormQuot, true>(c, g, gref, nullptr, sums, scales, s);
+    case kNormMean: return tree_sum_launch<kNormMean, true>(c, g, nullptr, nullptr, sums, scales, s);
+    default: return tree_sum_launch<kNormComb, true>(c, g, gref, gref2, sums, scales, s);
   }
 }
 
@@ -783,6 +950,7 @@ hipError_t launch_quantize_pack(const CodecShape& c, uint32_t iter, const float*
     case kNormNone: TNG_Q(kNormNone, nullptr, nullptr);
     case kNormSub: TNG_Q(kNormSub, gref, nullptr);
     case kNormQuot: TNG_Q(kNormQuot, gref, nullptr);
+    case kNormMean: TNG_Q(kNormMean, nullptr, nullptr);
     default: TNG_Q(kNormComb, gref, gref2);
   }
 #undef TNG_Q
@@ -797,6 +965,7 @@ hipError_t launch_decode(const CodecShape& c, const uint32_t* codes, const float
     case kNormNone: TNG_D(kNormNone, nullptr, nullptr);
     case kNormSub: TNG_D(kNormSub, gref, nullptr);
     case kNormQuot: TNG_D(kNormQuot, gref, nullptr);
+    case kNormMean: TNG_D(kNormMean, nullptr, nullptr);
     default: TNG_D(kNormComb, gref, gref2);
   }
 #undef TNG_D

@@ -10,6 +10,7 @@ constexpr int kNormNone = 0;
 constexpr int kNormSub = 1;
 constexpr int kNormQuot = 2;
 constexpr int kNormComb = 3;
+constexpr int kNormMean = 4;  // per-worker scalar reference mean(g_m)
 
 constexpr int kBlock = 256;  // threads per workgroup: 4 wavefronts of 64
 constexpr int kWave = 64;
@@ -91,6 +92,13 @@ __device__ __forceinline__ float normalize(float g, float r1, float r2) {
   return g;
 }
 
+// The same including the per-worker mean reference (mu = mean of the worker's gradient).
+template <int NORM>
+__device__ __forceinline__ float normalize_w(float g, float r1, float r2, float mu) {
+  if (NORM == kNormMean) return g - mu;
+  return normalize<NORM>(g, r1, r2);
+}
+
 // The same with the kind of normalisation and the raw (unclamped) references as run-time arguments.
 __device__ __forceinline__ float normalize_dyn(int norm, float g, float ref, float ref2, float eps) {
   switch (norm) {
@@ -109,7 +117,7 @@ __device__ __forceinline__ float denormalize(float mean, float r1, float r2) {
     const float p = r2 * mean;
     return p + r1;
   }
-  return mean;
+  return mean;  // none; per-worker mean reference: every worker's mean was added back before averaging
 }
 
 // Stochastic rounding of |v|/R onto {0, 1/S, ..., 1} (section "Gradient Compression"; S = 1 is the

@@ -14,6 +14,8 @@ struct CodecShape {
   int norm;        // kNorm*
   float eps;       // clamp of the divisor reference
   uint32_t k0, k1; // Philox key (seed low, seed high)
+  int scale_l2;    // 0: R = max |v|, 1: R = ||v||_2
+  float* means;    // device [M]: per-worker means of the mean reference (kNormMean), else unused
 };
 
 hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t s);
@@ -31,6 +33,16 @@ constexpr uint32_t kAbsmaxMaxBlocks = 4096;
 // kAbsmaxMaxBlocks * M floats.  Two launches: partial maxima per workgroup, then one reduction.
 hipError_t launch_absmax(const CodecShape& c, const float* g, const float* gref, const float* gref2,
                          float* partials, float* scales, hipStream_t s);
+// Order-pinned float64 sums per worker (4096-element chunks of 256 strided lanes, chunks in groups of
+// 256, everything added in index order).  sums: device scratch of tree_sum_scratch(d, M) doubles.
+// launch_worker_means: means[m] = float(sum_e g[m][e] / d).  launch_l2_scales: scales[m] =
+// float(sqrt(sum_e v^2)), v the normalised gradient (c.means must hold the means for kNormMean),
+// 0 when below FLT_MIN.
+size_t tree_sum_scratch(uint64_t d, uint32_t M);
+hipError_t launch_worker_means(const CodecShape& c, const float* g, double* sums, float* means, hipStream_t s);
+hipError_t launch_l2_scales(const CodecShape& c, const float* g, const float* gref, const float* gref2, double* sums,
+                            float* scales, hipStream_t s);
+
 // Reduction of nblocks rows of per-workgroup partial maxima (partials[block][m]) to scales[m].
 hipError_t launch_absmax_finish(const float* partials, uint32_t nblocks, uint32_t M, float* scales, hipStream_t s);
 

@@ -20,7 +20,8 @@ def oracle_cfg(ctx, **kw):
     c = ctx.cfg
     return O.Config(d=int(c.d), M=int(c.M), bits=int(c.bits), norm=int(c.norm), quot_eps=float(c.quot_eps),
                     ref_policy=int(c.ref_policy), ref_period=int(c.ref_period), seed=int(c.seed), lr=float(c.lr),
-                    l2=float(c.l2), batch=int(c.batch), ref_window=max(int(c.ref_window), 1), **kw)
+                    l2=float(c.l2), batch=int(c.batch), ref_window=max(int(c.ref_window), 1),
+                    scale_kind=int(c.scale), **kw)
 
 
 def buffers(ctx):

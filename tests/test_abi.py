@@ -31,8 +31,8 @@ def test_library_exports_every_declared_entry_point():
 
 
 def test_config_struct_matches_the_header_layout():
-    # d(8) M(4) bits(4) norm(4) eps(4) policy(4) period(4) seed(8) lr(4) l2(4) batch(4) problem(4) window(4) pad(4)
-    assert ctypes.sizeof(B.TngConfig) == 64 and B.TngConfig.ref_window.offset == 56
+    # d(8) M(4) bits(4) norm(4) eps(4) policy(4) period(4) seed(8) lr(4) l2(4) batch(4) problem(4) window(4) scale(4)
+    assert ctypes.sizeof(B.TngConfig) == 64 and B.TngConfig.ref_window.offset == 56 and B.TngConfig.scale.offset == 60
     assert B.TngConfig.seed.offset == 32 and B.TngConfig.problem.offset == 52
 
 
@@ -46,7 +46,7 @@ def test_words_per_row():
 def test_workspace_size_and_config_validation():
     assert B.tng_workspace_bytes(_cfg()) >= 4 * 64 * 8
     assert B.tng_workspace_bytes(_cfg(problem=B.PROB_EXTERNAL, batch=0)) > 0
-    bad = [dict(d=0), dict(M=0), dict(bits=3), dict(bits=8), dict(norm=7), dict(quot_eps=0.0),
+    bad = [dict(d=0), dict(M=0), dict(bits=3), dict(bits=8), dict(norm=7), dict(norm=5), dict(norm=-1), dict(scale=2), dict(scale=-1), dict(quot_eps=0.0),
            dict(quot_eps=float("nan")), dict(ref_policy=5), dict(ref_period=0), dict(lr=float("inf")),
            dict(l2=float("nan")), dict(batch=0), dict(problem=9), dict(d=(1 << 34) + 1), dict(M=70000),
            dict(ref_policy=B.REF_WINDOW_AVG, ref_window=0)]
@@ -55,6 +55,14 @@ def test_workspace_size_and_config_validation():
         h = ctypes.c_void_p()
         st = B.lib().tng_create(ctypes.byref(_cfg(**kw)), ctypes.c_void_p(0x1000), 1 << 20, None, ctypes.byref(h))
         assert st == B.TNG_ERR_INVALID_ARG and not h
+
+
+def test_workspace_grows_by_the_row_sum_scratch():
+    base = B.tng_workspace_bytes(_cfg(d=1 << 22, problem=B.PROB_EXTERNAL, batch=0))
+    for kw in (dict(norm=B.NORM_MEAN), dict(scale=B.SCALE_L2)):
+        more = B.tng_workspace_bytes(_cfg(d=1 << 22, problem=B.PROB_EXTERNAL, batch=0, **kw))
+        # 1024 chunk sums + 4 group sums of 8 bytes for each of the 4 workers
+        assert more - base >= 4 * (1024 + 4) * 8 and more - base < 4 * (1024 + 4) * 8 + 256
 
 
 def _fake_ctx(**kw):
@@ -106,6 +114,16 @@ def test_calls_reject_null_and_misaligned_pointers_before_launching():
     assert L.tng_normalize_encode(h, 0, p, p, p, p) == B.TNG_ERR_BAD_STATE
     assert L.tng_set_second_reference(h, None) == B.TNG_ERR_INVALID_ARG
     assert L.tng_local_grad(h, 0, p, p) == B.TNG_ERR_BAD_STATE                         # external gradients
+    assert L.tng_destroy(h) == B.TNG_OK
+    # the per-worker mean reference needs the array its means travel in; it needs no shared reference
+    h = _fake_ctx(norm=B.NORM_MEAN, problem=B.PROB_EXTERNAL, batch=0)
+    assert L.tng_normalize_encode(h, 0, p, None, p, p) == B.TNG_ERR_BAD_STATE
+    assert L.tng_decode_aggregate(h, p, p, None, p) == B.TNG_ERR_BAD_STATE
+    assert L.tng_set_worker_means(h, None) == B.TNG_ERR_INVALID_ARG
+    assert L.tng_set_worker_means(h, ctypes.c_void_p(0x20002)) == B.TNG_ERR_INVALID_ARG
+    assert L.tng_destroy(h) == B.TNG_OK
+    h = _fake_ctx(problem=B.PROB_EXTERNAL, batch=0)
+    assert L.tng_set_worker_means(h, p) == B.TNG_ERR_BAD_STATE                         # not a mean-reference context
     assert L.tng_destroy(h) == B.TNG_OK
     # update_reference is a no-op (and OK) when no refresh is due
     h = _fake_ctx(ref_period=16, problem=B.PROB_EXTERNAL, batch=0)

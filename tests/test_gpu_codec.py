@@ -11,7 +11,7 @@ from paper_1901_08227_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-NORMS = [B.NORM_NONE, B.NORM_SUB, B.NORM_QUOT, B.NORM_COMB]
+NORMS = [B.NORM_NONE, B.NORM_SUB, B.NORM_QUOT, B.NORM_COMB, B.NORM_MEAN]
 
 
 def _inputs(M, d, seed, scale=1.0):
@@ -21,23 +21,31 @@ def _inputs(M, d, seed, scale=1.0):
 
 
 def _check_encode_decode(ctx, it, g, gref, gref2, tag):
-    say(f"codec case {tag}: d={ctx.d} M={ctx.M} bits={ctx.bits} norm={ctx.cfg.norm} it={it}")
+    say(f"codec case {tag}: d={ctx.d} M={ctx.M} bits={ctx.bits} norm={ctx.cfg.norm} scale={ctx.cfg.scale} it={it}")
     buf = buffers(ctx)
     if ctx.cfg.norm == B.NORM_COMB:
         ctx.set_second_reference(gref2)
+    means_dev = None
+    if ctx.cfg.norm == B.NORM_MEAN:
+        means_dev = torch.full((ctx.M,), float("nan"), device=DEV)
+        ctx.set_worker_means(means_dev)
     ctx.normalize_encode(it, g, gref, buf["codes"], buf["scales"])
     ctx.decode_aggregate(buf["codes"], buf["scales"], gref, buf["vbar"])
     torch.cuda.synchronize()
     cfg = oracle_cfg(ctx)
     gh, rh, r2h = g.cpu().numpy(), gref.cpu().numpy(), gref2.cpu().numpy()
-    codes, scales = O.normalize_encode(cfg, it, gh, rh, r2h)
+    means = None
+    if means_dev is not None:
+        means = O.worker_means(gh)
+        assert np.array_equal(means_dev.cpu().numpy(), means), f"{tag}: worker means"
+    codes, scales = O.normalize_encode(cfg, it, gh, rh, r2h, means)
     assert np.array_equal(buf["scales"].cpu().numpy(), scales), f"{tag}: scales"
     got = u32(buf["codes"])
     if not np.array_equal(got, codes):
         bad = np.argwhere(got != codes)
         raise AssertionError(f"{tag}: {len(bad)} packed words differ, first at {bad[0]}: "
                              f"{got[tuple(bad[0])]:#x} vs {codes[tuple(bad[0])]:#x}")
-    vbar = O.decode_aggregate(cfg, codes, scales, rh, ctx.d, r2h)
+    vbar = O.decode_aggregate(cfg, codes, scales, rh, ctx.d, r2h, means)
     assert np.array_equal(buf["vbar"].cpu().numpy(), vbar), f"{tag}: decoded average"
 
 
@@ -63,13 +71,41 @@ def test_several_tiles_and_ragged_last_tile(bits, norm):
         ctx.close()
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("norm", NORMS)
+def test_l2_scale(bits, norm):
+    # R = ||v||_2 from the order-pinned float64 sum: one chunk, a ragged chunk, several chunks, more
+    # than one group of 256 chunks (d > 2^20), and sizes that take the element-at-a-time kernels
+    for d, M in [(1, 2), (5, 2), (257, 3), (4096, 2), (4096 * 3 + 20, 3), (4099, 2), ((1 << 20) + 4096 * 2 + 8, 2)]:
+        g, gref, gref2 = _inputs(M, d, seed=d % 977 + M)
+        ctx = make_ctx(d, M, bits, norm, seed=21, scale=B.SCALE_L2)
+        _check_encode_decode(ctx, 2, g, gref, gref2, "l2 scale")
+        ctx.close()
+
+
+def test_mean_reference_with_a_large_common_offset():
+    # gradients that share a large offset per worker: the case the scalar reference is meant for;
+    # also rows whose mean is exactly zero and a constant row (v = 0, R = 0)
+    d, M = 4096 * 6 + 36, 4
+    g, gref, gref2 = _inputs(M, d, seed=31)
+    g = g * 0.01 + torch.tensor([5.0, -3.0, 0.0, 100.0], device=DEV)[:, None]
+    g[2] = g[2] - g[2].double().mean().float()
+    g[3] = 7.25
+    for bits in (2, 4):
+        for scale in (B.SCALE_MAX, B.SCALE_L2):
+            ctx = make_ctx(d, M, bits, B.NORM_MEAN, seed=17, scale=scale)
+            _check_encode_decode(ctx, 9, g, gref, gref2, "mean reference, offsets")
+            ctx.close()
+
+
 def test_many_workers_and_chunked_scales():
     d, M = 2048, 300          # decode stages scales in chunks of 256 workers
     g, gref, gref2 = _inputs(M, d, seed=4)
     for bits in (2, 4):
-        ctx = make_ctx(d, M, bits, B.NORM_SUB, seed=5)
-        _check_encode_decode(ctx, 2, g, gref, gref2, "many workers")
-        ctx.close()
+        for norm in (B.NORM_SUB, B.NORM_MEAN):
+            ctx = make_ctx(d, M, bits, norm, seed=5)
+            _check_encode_decode(ctx, 2, g, gref, gref2, "many workers")
+            ctx.close()
 
 
 @pytest.mark.parametrize("bits", [2, 4])

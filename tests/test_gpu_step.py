@@ -130,19 +130,24 @@ def test_rosenbrock_small_and_ragged():
 
 
 def test_every_normalisation_through_the_fused_step():
-    # tng_step takes the scale from the gradient kernel's own partial maxima: all four normalisations,
-    # vector (d = 8192) and scalar (d = 8191) paths, against the oracle
+    # tng_step takes the scale from the gradient kernel's own partial maxima where it can: every
+    # normalisation and both scales, vector (d = 8192) and scalar (d = 8191) paths, against the oracle
     M, seed = 3, 21
+    cases = [(n, B.SCALE_MAX) for n in (B.NORM_NONE, B.NORM_SUB, B.NORM_QUOT, B.NORM_COMB, B.NORM_MEAN)]
+    cases += [(B.NORM_SUB, B.SCALE_L2), (B.NORM_MEAN, B.SCALE_L2)]
     for d in (8192, 8191):
-        for norm in (B.NORM_NONE, B.NORM_SUB, B.NORM_QUOT, B.NORM_COMB):
-            say(f"fused step d={d} norm={norm}")
-            ctx = make_ctx(d, M, 4, norm, seed=seed, lr=1e-5, problem=B.PROB_ROSENBROCK)
+        for norm, scale in cases:
+            say(f"fused step d={d} norm={norm} scale={scale}")
+            ctx = make_ctx(d, M, 4, norm, seed=seed, lr=1e-5, problem=B.PROB_ROSENBROCK, scale=scale)
             cfg = oracle_cfg(ctx)
             x = synth.rosenbrock_start(d, seed, device=DEV)
             gref = synth.rosenbrock_start(d, seed + 1, device=DEV) * 100.0
             gref2 = torch.rand(d, device=DEV, generator=torch.Generator(device=DEV).manual_seed(3)) + 0.5
             if norm == B.NORM_COMB:
                 ctx.set_second_reference(gref2)
+            if norm == B.NORM_MEAN:
+                means = torch.zeros(M, device=DEV)
+                ctx.set_worker_means(means)
             buf = buffers(ctx)
             for it in range(2):
                 noise = synth.gradient_noise(M, d, seed, it, device=DEV)
@@ -155,6 +160,8 @@ def test_every_normalisation_through_the_fused_step():
                 assert np.array_equal(gh, np.stack([O.grad_rosenbrock(w0, nh[m]) for m in range(M)]))
                 w1, r1, c1, s1, v1 = O.step(cfg, it, w0, r0, gh, gref2.cpu().numpy())
                 assert np.array_equal(buf["scales"].cpu().numpy(), s1), "scales from the fused partial maxima"
+                if norm == B.NORM_MEAN:
+                    assert np.array_equal(means.cpu().numpy(), O.worker_means(gh))
                 assert np.array_equal(u32(buf["codes"]), c1) and np.array_equal(buf["vbar"].cpu().numpy(), v1)
                 assert np.array_equal(x.cpu().numpy(), w1) and np.array_equal(gref.cpu().numpy(), r1)
             ctx.close()
