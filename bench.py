@@ -58,10 +58,12 @@ class HipEvents:
         self.ev = []
 
 
-def time_codec(torch, B, g, gref, bits, norm, steps, warmup, seed):
+def time_codec(torch, B, g, gref, bits, norm, steps, warmup, seed, scale=0):
     """Times `steps` encode+decode passes; returns whole-loop ms/step and per-kernel mean ms."""
     M, d = g.shape
-    ctx = B.Context(d=d, M=M, bits=bits, norm=norm, seed=seed, device=g.device)
+    ctx = B.Context(d=d, M=M, bits=bits, norm=norm, seed=seed, scale=scale, device=g.device)
+    if norm == B.NORM_MEAN:
+        ctx.set_worker_means(torch.empty(M, device=g.device))
     codes = torch.empty((M, ctx.words), dtype=torch.int32, device=g.device)
     scales = torch.empty(M, device=g.device)
     vbar = torch.empty(d, device=g.device)
@@ -86,10 +88,12 @@ def time_codec(torch, B, g, gref, bits, norm, steps, warmup, seed):
     ctx.close()
     del codes, scales, vbar
     ms = (t1 - t0) * 1e3 / steps
-    # algorithmic bytes per launch: each operand once per kernel
-    b_scale = 4 * M * d + 4 * d
-    b_quant = 4 * M * d + 4 * d + 4 * M * words
-    b_dec = 4 * M * words + 4 * d + 4 * d
+    # algorithmic bytes per launch: each operand once per kernel (the mean reference reads no shared
+    # reference; its mean and its scale come out of one pass)
+    b_ref = {B.NORM_NONE: 0, B.NORM_MEAN: 0, B.NORM_COMB: 8 * d}.get(norm, 4 * d)
+    b_scale = (2 if norm == B.NORM_MEAN and scale == B.SCALE_L2 else 1) * 4 * M * d + b_ref
+    b_quant = 4 * M * d + b_ref + 4 * M * words
+    b_dec = 4 * M * words + b_ref + 4 * d
     return {
         "ms_per_step": ms,
         "fp32_in_GBps": 4.0 * M * d / (ms * 1e-3) / 1e9,
@@ -276,9 +280,13 @@ def main():
     head = time_codec(torch, B, g, gref, 2, B.NORM_SUB, args.steps, args.warmup, seed)
     variants = []
     if not args.no_variants:
-        for bits, norm, name in [(4, B.NORM_SUB, "4bit/sub"), (2, B.NORM_QUOT, "ternary/quot"), (4, B.NORM_QUOT, "4bit/quot")]:
+        for bits, norm, scale, name in [(4, B.NORM_SUB, B.SCALE_MAX, "4bit/sub"),
+                                        (2, B.NORM_QUOT, B.SCALE_MAX, "ternary/quot"),
+                                        (4, B.NORM_QUOT, B.SCALE_MAX, "4bit/quot"),
+                                        (2, B.NORM_MEAN, B.SCALE_MAX, "ternary/mean"),
+                                        (2, B.NORM_SUB, B.SCALE_L2, "ternary/sub/l2")]:
             log(f"timing {name}")
-            r = time_codec(torch, B, g, gref, bits, norm, args.steps, args.warmup, seed)
+            r = time_codec(torch, B, g, gref, bits, norm, args.steps, args.warmup, seed, scale)
             variants.append({"variant": name, "ms_per_step": round(r["ms_per_step"], 4),
                              "fp32_in_GBps": round(r["fp32_in_GBps"], 1),
                              "two_pass_GBps": round(r["two_pass_GBps"], 1),

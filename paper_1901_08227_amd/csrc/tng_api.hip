@@ -141,11 +141,15 @@ tng_status encode_impl(tng_ctx* ctx, uint32_t iter, const float* g, const float*
   const uint64_t call = ctx->enc_calls++;
   mark(ctx, call, 0);
   hipError_t e = hipSuccess;
-  if (ctx->cfg.norm == TNG_NORM_MEAN) {  // the worker's own reference comes first: the scale is taken of g - mu
-    e = tng::launch_worker_means(ctx->shape, g, ctx->sums, ctx->shape.means, ctx->stream);
+  const bool mean_ref = ctx->cfg.norm == TNG_NORM_MEAN;
+  if (mean_ref) {  // the worker's own reference comes first; the maximum of |g - mu| comes out of the same pass
+    e = tng::launch_worker_means(ctx->shape, g, ctx->sums, ctx->shape.means,
+                                 ctx->cfg.scale == TNG_SCALE_MAX ? scales : nullptr, ctx->stream);
     if (e != hipSuccess) return TNG_ERR_HIP;
   }
-  if (ctx->cfg.scale == TNG_SCALE_L2) {
+  if (mean_ref && ctx->cfg.scale == TNG_SCALE_MAX) {
+    // nothing left of the scale pass
+  } else if (ctx->cfg.scale == TNG_SCALE_L2) {
     e = tng::launch_l2_scales(ctx->shape, g, gref, ctx->gref2, ctx->sums, scales, ctx->stream);
   } else if (fused_rows > 0) {
     e = tng::launch_absmax_finish(ctx->partials, fused_rows, ctx->cfg.M, scales, ctx->stream);

@@ -74,16 +74,19 @@ __global__ __launch_bounds__(kBlock) void rng_draws_kernel(uint32_t k0, uint32_t
 template <int NORM>
 struct RefTile {
   float4 r1, r2;
+  // STREAM: the tile is read once by this kernel (non-temporal); otherwise it is re-read soon and
+  // should stay in cache.
+  template <bool STREAM = true>
   __device__ __forceinline__ void load(const float4* ref, const float4* ref2, uint64_t i, float eps) {
     r1 = make_float4(0.f, 0.f, 0.f, 0.f);
     r2 = make_float4(1.f, 1.f, 1.f, 1.f);
-    if (NORM == kNormSub || NORM == kNormComb) r1 = load_stream(ref + i);
+    if (NORM == kNormSub || NORM == kNormComb) r1 = STREAM ? load_stream(ref + i) : ref[i];
     if (NORM == kNormQuot) {
-      const float4 r = load_stream(ref + i);
+      const float4 r = STREAM ? load_stream(ref + i) : ref[i];
       r1 = make_float4(clamp_ref(r.x, eps), clamp_ref(r.y, eps), clamp_ref(r.z, eps), clamp_ref(r.w, eps));
     }
     if (NORM == kNormComb) {
-      const float4 r = load_stream(ref2 + i);
+      const float4 r = STREAM ? load_stream(ref2 + i) : ref2[i];
       r2 = make_float4(clamp_ref(r.x, eps), clamp_ref(r.y, eps), clamp_ref(r.z, eps), clamp_ref(r.w, eps));
     }
   }
@@ -611,47 +614,71 @@ constexpr int kTreeChunk = 4096;
 constexpr int kTreeLanes = 256;
 constexpr int kTreeGroup = 256;
 
-template <int NORM, bool SQUARE, bool VEC>
+// MINMAX (mean pass only): the smallest and largest element of every chunk ride along.  Rounding is
+// monotone, so max_e |fl(g_e - mu)| = max(|fl(min g - mu)|, |fl(max g - mu)|) exactly: the scale of
+// the mean-referenced gradient needs no pass of its own.
+template <int NORM, bool SQUARE, bool VEC, bool MINMAX>
 __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restrict__ g, const float* __restrict__ ref,
                                                             const float* __restrict__ ref2,
                                                             const float* __restrict__ means,
-                                                            double* __restrict__ chunk_sums, uint64_t d,
-                                                            uint64_t nchunks, float eps) {
+                                                            double* __restrict__ chunk_sums,
+                                                            float2* __restrict__ chunk_minmax, uint64_t d,
+                                                            uint64_t nchunks, float eps, uint32_t M,
+                                                            uint32_t workers_per_block) {
   __shared__ double lanes[kWavesPerBlock][kTreeLanes];
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-  const uint32_t m = blockIdx.y;
   const uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
   if (chunk >= nchunks) return;  // whole wavefront; no workgroup barrier below
+  const uint64_t base = chunk * kTreeChunk + 4u * (uint32_t)lane;
+  constexpr int K = kTreeChunk / kTreeLanes;
+  // A wavefront takes its chunk of several workers in turn: the reference tile of the chunk is then
+  // fetched from HBM once and found in cache by the following workers.
+  const uint32_t m_first = blockIdx.y * workers_per_block;
+  const uint32_t m_last = m_first + workers_per_block < M ? m_first + workers_per_block : M;
+  for (uint32_t m = m_first; m < m_last; ++m) {
   const float* __restrict__ row = g + (uint64_t)m * d;
   const float mu = (SQUARE && NORM == kNormMean) ? means[m] : 0.f;
-  const uint64_t base = chunk * kTreeChunk + 4u * (uint32_t)lane;
   double acc[4] = {0.0, 0.0, 0.0, 0.0};
-  constexpr int K = kTreeChunk / kTreeLanes;
+  float lo = INFINITY, hi = -INFINITY;
   if (VEC) {
+    // loads in batches: all 16 rows of the chunk at once, or 8 rows plus their reference tiles
+    constexpr bool kHasRef = SQUARE && (NORM == kNormSub || NORM == kNormQuot || NORM == kNormComb);
+    constexpr int KB = kHasRef ? 8 : K;
     const bool full = (chunk + 1) * kTreeChunk <= d;
-    float4 x[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      const uint64_t e = base + (uint64_t)k * kTreeLanes;
-      x[k] = (full || e < d) ? load_stream(reinterpret_cast<const float4*>(row + e)) : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int k0 = 0; k0 < K; k0 += KB) {
+      float4 x[KB];
+      RefTile<NORM> rt[KB];
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      const uint64_t e = base + (uint64_t)k * kTreeLanes;
-      float4 v = x[k];
-      if (SQUARE && (full || e < d)) {
-        RefTile<NORM> rt;
-        rt.load(reinterpret_cast<const float4*>(ref), reinterpret_cast<const float4*>(ref2), e / 4, eps);
-        v.x = normalize_w<NORM>(v.x, rt.r1.x, rt.r2.x, mu);
-        v.y = normalize_w<NORM>(v.y, rt.r1.y, rt.r2.y, mu);
-        v.z = normalize_w<NORM>(v.z, rt.r1.z, rt.r2.z, mu);
-        v.w = normalize_w<NORM>(v.w, rt.r1.w, rt.r2.w, mu);
+      for (int k = 0; k < KB; ++k) {
+        const uint64_t e = base + (uint64_t)(k0 + k) * kTreeLanes;
+        const bool in = full || e < d;
+        x[k] = in ? load_stream(reinterpret_cast<const float4*>(row + e)) : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (SQUARE && in)
+          rt[k].template load<false>(reinterpret_cast<const float4*>(ref), reinterpret_cast<const float4*>(ref2), e / 4,
+                                     eps);
       }
-      const double t0 = (double)v.x, t1 = (double)v.y, t2 = (double)v.z, t3 = (double)v.w;
-      acc[0] = acc[0] + (SQUARE ? t0 * t0 : t0);  // the square of a binary32 value is exact in binary64
-      acc[1] = acc[1] + (SQUARE ? t1 * t1 : t1);
-      acc[2] = acc[2] + (SQUARE ? t2 * t2 : t2);
-      acc[3] = acc[3] + (SQUARE ? t3 * t3 : t3);
+#pragma unroll
+      for (int k = 0; k < KB; ++k) {
+        const uint64_t e = base + (uint64_t)(k0 + k) * kTreeLanes;
+        const bool in = full || e < d;
+        float4 v = x[k];
+        if (SQUARE && in) {
+          v.x = normalize_w<NORM>(v.x, rt[k].r1.x, rt[k].r2.x, mu);
+          v.y = normalize_w<NORM>(v.y, rt[k].r1.y, rt[k].r2.y, mu);
+          v.z = normalize_w<NORM>(v.z, rt[k].r1.z, rt[k].r2.z, mu);
+          v.w = normalize_w<NORM>(v.w, rt[k].r1.w, rt[k].r2.w, mu);
+        }
+        if (MINMAX && in) {
+          lo = fminf(lo, fminf(fminf(v.x, v.y), fminf(v.z, v.w)));
+          hi = fmaxf(hi, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+        }
+        const double t0 = (double)v.x, t1 = (double)v.y, t2 = (double)v.z, t3 = (double)v.w;
+        acc[0] = acc[0] + (SQUARE ? t0 * t0 : t0);  // the square of a binary32 value is exact in binary64
+        acc[1] = acc[1] + (SQUARE ? t1 * t1 : t1);
+        acc[2] = acc[2] + (SQUARE ? t2 * t2 : t2);
+        acc[3] = acc[3] + (SQUARE ? t3 * t3 : t3);
+      }
     }
   } else {
     for (int k = 0; k < K; ++k) {
@@ -665,6 +692,10 @@ __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restr
             load_ref_scalar<NORM>(ref, ref2, e, eps, r1, r2);
             v = normalize_w<NORM>(v, r1, r2, mu);
           }
+          if (MINMAX) {
+            lo = fminf(lo, v);
+            hi = fmaxf(hi, v);
+          }
           const double t = (double)v;
           acc[i] = acc[i] + (SQUARE ? t * t : t);
         }
@@ -673,23 +704,34 @@ __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restr
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) lanes[wave][4 * lane + i] = acc[i];
+  if (MINMAX) {
+    hi = wave_max(hi);
+    lo = -wave_max(-lo);
+  }
   wave_lds_fence();
   if (lane == 0) {
     double total = 0.0;
 #pragma unroll 16
     for (int j = 0; j < kTreeLanes; ++j) total = total + lanes[wave][j];
     chunk_sums[(uint64_t)m * nchunks + chunk] = total;
+    if (MINMAX) chunk_minmax[(uint64_t)m * nchunks + chunk] = make_float2(lo, hi);
+  }
+  wave_lds_fence();  // the lane sums are read before the next worker overwrites them
   }
 }
 
 // One workgroup per worker: group sums (thread q adds the chunks of groups q, q + 256, ... in order),
-// then thread 0 adds the groups in order.  MEAN: out[m] = float(total / d).  Otherwise
+// then thread 0 adds the groups in order.  MEAN: out[m] = float(total / d), and, when chunk_minmax is
+// given, scales[m] = max |g - out[m]| from the smallest and the largest element.  Otherwise
 // out[m] = float(sqrt(total)), 0 when below FLT_MIN.  Division and square root of binary64 are
 // correctly rounded on the device, so the float32 result is the same as on any IEEE host.
 template <bool MEAN>
 __global__ __launch_bounds__(kBlock) void tree_finish_kernel(const double* __restrict__ chunk_sums,
-                                                             double* __restrict__ group_sums, uint64_t nchunks,
-                                                             uint64_t ngroups, uint64_t d, float* __restrict__ out) {
+                                                             double* __restrict__ group_sums,
+                                                             const float2* __restrict__ chunk_minmax,
+                                                             uint64_t nchunks, uint64_t ngroups, uint64_t d,
+                                                             float* __restrict__ out, float* __restrict__ scales) {
+  __shared__ float red_lo[kWavesPerBlock], red_hi[kWavesPerBlock];
   const uint32_t m = blockIdx.x;
   const double* __restrict__ cs = chunk_sums + (uint64_t)m * nchunks;
   double* __restrict__ gs = group_sums + (uint64_t)m * ngroups;
@@ -700,13 +742,38 @@ __global__ __launch_bounds__(kBlock) void tree_finish_kernel(const double* __res
     for (uint64_t c = c0; c < c1; ++c) a = a + cs[c];
     gs[q] = a;
   }
+  if (MEAN && chunk_minmax != nullptr) {
+    float lo = INFINITY, hi = -INFINITY;
+    for (uint64_t c = threadIdx.x; c < nchunks; c += kBlock) {
+      const float2 mm = chunk_minmax[(uint64_t)m * nchunks + c];
+      lo = fminf(lo, mm.x);
+      hi = fmaxf(hi, mm.y);
+    }
+    lo = -wave_max(-lo);
+    hi = wave_max(hi);
+    if (threadIdx.x % kWave == 0) {
+      red_lo[threadIdx.x / kWave] = lo;
+      red_hi[threadIdx.x / kWave] = hi;
+    }
+  }
   __threadfence_block();
   __syncthreads();
   if (threadIdx.x == 0) {
     double total = 0.0;
     for (uint64_t q = 0; q < ngroups; ++q) total = total + gs[q];
     if (MEAN) {
-      out[m] = (float)(total / (double)d);
+      const float mu = (float)(total / (double)d);
+      out[m] = mu;
+      if (chunk_minmax != nullptr) {
+        float lo = red_lo[0], hi = red_hi[0];
+#pragma unroll
+        for (int k = 1; k < kWavesPerBlock; ++k) {
+          lo = fminf(lo, red_lo[k]);
+          hi = fmaxf(hi, red_hi[k]);
+        }
+        const float r = fmaxf(fabsf(lo - mu), fabsf(hi - mu));
+        scales[m] = r < FLT_MIN ? 0.f : r;
+      }
     } else {
       const float r = (float)sqrt(total);
       out[m] = r < FLT_MIN ? 0.f : r;
@@ -900,44 +967,52 @@ hipError_t launch_absmax(const CodecShape& c, const float* g, const float* gref,
 size_t tree_sum_scratch(uint64_t d, uint32_t M) {
   const uint64_t nchunks = (d + kTreeChunk - 1) / kTreeChunk;
   const uint64_t ngroups = (nchunks + kTreeGroup - 1) / kTreeGroup;
-  return (size_t)((nchunks + ngroups) * M);
+  return (size_t)((2 * nchunks + ngroups) * M);  // chunk sums, chunk (min, max) pairs, group sums
 }
 
 namespace {
-template <int NORM, bool SQUARE>
+template <int NORM, bool SQUARE, bool MINMAX>
 hipError_t tree_sum_launch(const CodecShape& c, const float* g, const float* gref, const float* gref2, double* sums,
-                           float* out, hipStream_t s) {
+                           float* out, float* scales, hipStream_t s) {
   const uint64_t nchunks = (c.d + kTreeChunk - 1) / kTreeChunk;
   const uint64_t ngroups = (nchunks + kTreeGroup - 1) / kTreeGroup;
-  double* group_sums = sums + nchunks * c.M;
-  dim3 grid((uint32_t)((nchunks + kWavesPerBlock - 1) / kWavesPerBlock), c.M);
+  float2* minmax = reinterpret_cast<float2*>(sums + nchunks * c.M);
+  double* group_sums = sums + 2 * nchunks * c.M;
+  const uint32_t gx = (uint32_t)((nchunks + kWavesPerBlock - 1) / kWavesPerBlock);
+  // workers per workgroup: as many as leave 2048 workgroups (only worth it when a reference is shared)
+  uint32_t wpb = 1;
+  if (SQUARE && gref != nullptr)
+    while (wpb < 8 && wpb < c.M && (uint64_t)gx * ((c.M + 2 * wpb - 1) / (2 * wpb)) >= 2048) wpb *= 2;
+  dim3 grid(gx, (c.M + wpb - 1) / wpb);
   if (vec_ok(c.d, g, gref, gref2)) {
-    hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, true>), grid, dim3(kBlock), 0, s, g, gref, gref2, c.means,
-                       sums, c.d, nchunks, c.eps);
+    hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, true, MINMAX>), grid, dim3(kBlock), 0, s, g, gref, gref2,
+                       c.means, sums, minmax, c.d, nchunks, c.eps, c.M, wpb);
   } else {
-    hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, false>), grid, dim3(kBlock), 0, s, g, gref, gref2, c.means,
-                       sums, c.d, nchunks, c.eps);
+    hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, false, MINMAX>), grid, dim3(kBlock), 0, s, g, gref, gref2,
+                       c.means, sums, minmax, c.d, nchunks, c.eps, c.M, wpb);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((tree_finish_kernel<!SQUARE>), dim3(c.M), dim3(kBlock), 0, s, sums, group_sums, nchunks,
-                     ngroups, c.d, out);
+  hipLaunchKernelGGL((tree_finish_kernel<!SQUARE>), dim3(c.M), dim3(kBlock), 0, s, sums, group_sums,
+                     MINMAX ? minmax : nullptr, nchunks, ngroups, c.d, out, scales);
   return hipGetLastError();
 }
 }  // namespace
 
-hipError_t launch_worker_means(const CodecShape& c, const float* g, double* sums, float* means, hipStream_t s) {
-  return tree_sum_launch<kNormNone, false>(c, g, nullptr, nullptr, sums, means, s);
+hipError_t launch_worker_means(const CodecShape& c, const float* g, double* sums, float* means, float* scales,
+                               hipStream_t s) {
+  if (scales != nullptr) return tree_sum_launch<kNormNone, false, true>(c, g, nullptr, nullptr, sums, means, scales, s);
+  return tree_sum_launch<kNormNone, false, false>(c, g, nullptr, nullptr, sums, means, nullptr, s);
 }
 
 hipError_t launch_l2_scales(const CodecShape& c, const float* g, const float* gref, const float* gref2, double* sums,
                             float* scales, hipStream_t s) {
   switch (c.norm) {
-    case kNormNone: return tree_sum_launch<kNormNone, true>(c, g, nullptr, nullptr, sums, scales, s);
-    case kNormSub: return tree_sum_launch<kNormSub, true>(c, g, gref, nullptr, sums, scales, s);
-    case kNormQuot: return tree_sum_launch<kNormQuot, true>(c, g, gref, nullptr, sums, scales, s);
-    case kNormMean: return tree_sum_launch<kNormMean, true>(c, g, nullptr, nullptr, sums, scales, s);
-    default: return tree_sum_launch<kNormComb, true>(c, g, gref, gref2, sums, scales, s);
+    case kNormNone: return tree_sum_launch<kNormNone, true, false>(c, g, nullptr, nullptr, sums, scales, nullptr, s);
+    case kNormSub: return tree_sum_launch<kNormSub, true, false>(c, g, gref, nullptr, sums, scales, nullptr, s);
+    case kNormQuot: return tree_sum_launch<kNormQuot, true, false>(c, g, gref, nullptr, sums, scales, nullptr, s);
+    case kNormMean: return tree_sum_launch<kNormMean, true, false>(c, g, nullptr, nullptr, sums, scales, nullptr, s);
+    default: return tree_sum_launch<kNormComb, true, false>(c, g, gref, gref2, sums, scales, nullptr, s);
   }
 }
 

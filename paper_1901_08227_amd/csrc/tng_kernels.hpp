@@ -35,11 +35,13 @@ hipError_t launch_absmax(const CodecShape& c, const float* g, const float* gref,
                          float* partials, float* scales, hipStream_t s);
 // Order-pinned float64 sums per worker (4096-element chunks of 256 strided lanes, chunks in groups of
 // 256, everything added in index order).  sums: device scratch of tree_sum_scratch(d, M) doubles.
-// launch_worker_means: means[m] = float(sum_e g[m][e] / d).  launch_l2_scales: scales[m] =
-// float(sqrt(sum_e v^2)), v the normalised gradient (c.means must hold the means for kNormMean),
-// 0 when below FLT_MIN.
+// launch_worker_means: means[m] = float(sum_e g[m][e] / d); if scales != nullptr also
+// scales[m] = max_e |g[m][e] - means[m]| (0 when below FLT_MIN), from the row's extremes in the same
+// pass.  launch_l2_scales: scales[m] = float(sqrt(sum_e v^2)), v the normalised gradient (c.means
+// must hold the means for kNormMean), 0 when below FLT_MIN.
 size_t tree_sum_scratch(uint64_t d, uint32_t M);
-hipError_t launch_worker_means(const CodecShape& c, const float* g, double* sums, float* means, hipStream_t s);
+hipError_t launch_worker_means(const CodecShape& c, const float* g, double* sums, float* means, float* scales,
+                               hipStream_t s);
 hipError_t launch_l2_scales(const CodecShape& c, const float* g, const float* gref, const float* gref2, double* sums,
                             float* scales, hipStream_t s);
 

@@ -61,8 +61,8 @@ def test_workspace_grows_by_the_row_sum_scratch():
     base = B.tng_workspace_bytes(_cfg(d=1 << 22, problem=B.PROB_EXTERNAL, batch=0))
     for kw in (dict(norm=B.NORM_MEAN), dict(scale=B.SCALE_L2)):
         more = B.tng_workspace_bytes(_cfg(d=1 << 22, problem=B.PROB_EXTERNAL, batch=0, **kw))
-        # 1024 chunk sums + 4 group sums of 8 bytes for each of the 4 workers
-        assert more - base >= 4 * (1024 + 4) * 8 and more - base < 4 * (1024 + 4) * 8 + 256
+        # 1024 chunk sums, 1024 (min, max) pairs and 4 group sums of 8 bytes for each of the 4 workers
+        assert more - base >= 4 * (2048 + 4) * 8 and more - base < 4 * (2048 + 4) * 8 + 256
 
 
 def _fake_ctx(**kw):
