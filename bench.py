@@ -188,8 +188,13 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup):
                     per_step=lambda it: ctx.set_noise(noises[it % 8]))
     record("Rosenbrock chain d=2^20 M=8 ternary sub", ms, 4 * M * d * 2 + 4 * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
            "noise read + g write + two encode passes + decode/update")
-    ctx.close()
     del noises
+    ctx.set_noise_variance(0.01)
+    ms = time_steps(torch, ctx, step_state(torch, ctx, synth.rosenbrock_start(d, 1, device=dev)), steps, warmup)
+    record("Rosenbrock chain d=2^20 M=8 ternary sub, noise generated on the device", ms,
+           4 * M * d + 4 * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
+           "g write + two encode passes + decode/update; Box-Muller on Philox draws inside the gradient kernel")
+    ctx.close()
 
     # wide dense logistic regression, quotient normalisation
     M, n, d, batch = 16, 8192, 1 << 16, 256

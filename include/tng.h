@@ -135,6 +135,14 @@ tng_status tng_set_logreg_csr(tng_ctx* ctx, const int64_t* const* rowptr,
 /* Rosenbrock: additive noise of the coming iteration, device [M][d], or NULL for none
  * ("Nonconvex Problems": the stochastic gradient is the exact gradient plus Gaussian noise). */
 tng_status tng_set_noise(tng_ctx* ctx, const float* noise);
+/* Rosenbrock: Gaussian noise N(0, variance) made on the device instead of read from a tensor
+ * (variance > 0; 0 switches it off; the later of tng_set_noise / tng_set_noise_variance wins).
+ * Element e of worker m at iteration iter is sigma * z with sigma = sqrtf(variance) and z from the
+ * Box-Muller transform of the Philox4x32-10 block with counter (e >> 2, m, iter, 2): output words 0, 1
+ * serve e & 3 = 0 (cosine branch) and 1 (sine branch), words 2, 3 serve e & 3 = 2 and 3;
+ * u1 = ((word >> 8) + 1) 2^-24, u2 = (word >> 8) 2^-24, z = sqrt(-2 ln u1) {cos, sin}(2 pi u2).
+ * Evaluated in binary32 (a few units in the last place of the float64 value; not bit-pinned). */
+tng_status tng_set_noise_variance(tng_ctx* ctx, float variance);
 /* History of TNG_REF_WINDOW_AVG: device [ref_window][d], zero-filled by the caller before the first
  * iteration (missing history counts as zeros) and then owned by the library: the decoded average of
  * iteration iter is kept in slot iter % ref_window.  Must be set before tng_update_reference / tng_step. */

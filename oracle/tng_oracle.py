@@ -131,6 +131,29 @@ def quant_draw_words(seed: int, it: int, m: int, d: int, first: int = 0):
     return _draw_words(seed, it, m, STREAM_QUANT, first, d)
 
 
+STREAM_NOISE = 2
+
+
+def gaussian_noise(seed: int, it: int, m: int, d: int, variance: float):
+    """Synthetic gradient noise N(0, variance) of section "Nonconvex Problems" for worker m, float64[d].
+
+    Box-Muller on the counter-based draws of stream 2: the Philox block e >> 2 serves elements
+    4(e >> 2) .. +3; its words (0, 1) give the pair (cos branch for e & 3 = 0, sin branch for 1), its
+    words (2, 3) the pair for e & 3 = 2, 3.  u1 = ((word >> 8) + 1) 2^-24 lies in (0, 1], u2 =
+    (word >> 8) 2^-24 in [0, 1); z = sqrt(-2 ln u1) {cos, sin}(2 pi u2); noise = sigma z with
+    sigma = float32(sqrt(float32(variance))).  Evaluated in float64; a binary32 evaluation agrees to a
+    few units in the last place, so comparisons against it carry a tolerance.
+    """
+    nb = (d + 3) >> 2
+    words = _draw_words(seed, it, m, STREAM_NOISE, 0, 4 * nb).reshape(nb, 4).astype(np.uint64)
+    u1 = ((words[:, 0::2] >> np.uint64(8)) + np.uint64(1)).astype(np.float64) * 2.0 ** -24      # [nb][2]
+    u2 = (words[:, 1::2] >> np.uint64(8)).astype(np.float64) * 2.0 ** -24
+    r = np.sqrt(-2.0 * np.log(u1))
+    z = np.stack([r * np.cos(2.0 * np.pi * u2), r * np.sin(2.0 * np.pi * u2)], axis=2)         # [nb][pair][cos, sin]
+    sigma = np.float64(np.sqrt(F32(variance), dtype=F32))
+    return (sigma * z.reshape(-1))[:d]
+
+
 def uniform_from_word(x):
     """u = (x >> 8) * 2^-24: uniform on the 24-bit grid {0, ..., 1 - 2^-24}, exact in binary32."""
     return (np.asarray(x, dtype=U32) >> U32(8)).astype(F32) * F32(2.0 ** -24)

@@ -61,6 +61,7 @@ def lib() -> ctypes.CDLL:
             "tng_set_logreg_csr": [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                    ctypes.POINTER(vp), ctypes.POINTER(u64)],
             "tng_set_noise": [vp, vp],
+            "tng_set_noise_variance": [vp, ctypes.c_float],
             "tng_set_second_reference": [vp, vp],
             "tng_set_worker_means": [vp, vp],
             "tng_set_reference_history": [vp, vp],
@@ -177,6 +178,12 @@ class Context:
     def set_noise(self, noise):
         self._keep["noise"] = noise
         _check(lib().tng_set_noise(self.handle, _ptr(noise, torch.float32, self.M * self.d, "noise")), "tng_set_noise")
+
+    def set_noise_variance(self, variance):
+        """Rosenbrock: N(0, variance) noise generated on the device (0 switches it off)."""
+        _check(lib().tng_set_noise_variance(self.handle, float(variance)), "tng_set_noise_variance")
+        if variance > 0:
+            self._keep.pop("noise", None)
 
     def set_reference_history(self, history):
         """history: zero-filled float32 tensor [ref_window][d]; the library keeps the decoded averages in it."""

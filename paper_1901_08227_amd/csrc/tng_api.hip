@@ -23,6 +23,7 @@ struct tng_ctx {
   float* zpart;           // [M][tiles][batch] per-tile partial dot products of the CSR gradient
   bool have_dense, have_csr;
   const float* noise;     // Rosenbrock noise, may be null
+  float noise_sigma;      // > 0: Gaussian noise is generated on the device instead
   const float* gref2;     // second reference of the combined normalisation
   float* history;         // [ref_window][d] ring of decoded averages (window-average reference)
   double* sums;           // chunk and group sums of the order-pinned row sums (mean reference, l2 scale)
@@ -212,7 +213,8 @@ tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g
       return hip_status(e);
     }
     case TNG_PROB_ROSENBROCK:
-      e = tng::launch_rosenbrock_grad(c.d, c.M, w, ctx->noise, g, fuse, fused_rows, ctx->stream);
+      e = tng::launch_rosenbrock_grad(c.d, c.M, w, ctx->noise, tng::NoiseGen{ctx->noise_sigma, k0, k1, iter}, g, fuse,
+                                      fused_rows, ctx->stream);
       return hip_status(e);
     default:
       return TNG_ERR_BAD_STATE;
@@ -300,6 +302,7 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->sums = reinterpret_cast<double*>(base + p.sums_off);
   ctx->have_dense = ctx->have_csr = false;
   ctx->noise = nullptr;
+  ctx->noise_sigma = 0.f;
   ctx->gref2 = nullptr;
   ctx->history = nullptr;
   ctx->prof_slots = 0;
@@ -344,6 +347,15 @@ tng_status tng_set_noise(tng_ctx* ctx, const float* noise) {
   if (ctx == nullptr || !aligned(noise, 16)) return TNG_ERR_INVALID_ARG;
   if (ctx->cfg.problem != TNG_PROB_ROSENBROCK) return TNG_ERR_BAD_STATE;
   ctx->noise = noise;
+  ctx->noise_sigma = 0.f;
+  return TNG_OK;
+}
+
+tng_status tng_set_noise_variance(tng_ctx* ctx, float variance) {
+  if (ctx == nullptr || !(variance >= 0.0f) || !std::isfinite(variance)) return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.problem != TNG_PROB_ROSENBROCK) return TNG_ERR_BAD_STATE;
+  ctx->noise_sigma = std::sqrt(variance);
+  if (variance > 0.0f) ctx->noise = nullptr;
   return TNG_OK;
 }
 

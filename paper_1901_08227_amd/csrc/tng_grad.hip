@@ -427,15 +427,33 @@ __device__ __forceinline__ float rosenbrock_component(float xp, float xi, float 
   return base;
 }
 
+// Four standard normal deviates times sigma from one Philox block (Box-Muller; see NoiseGen).  The
+// angle is handed to sincospi as the exact number 2 u2, so there is no argument-reduction error.
+__device__ __forceinline__ float4 gaussian4(const NoiseGen& gen, uint64_t block, uint32_t m) {
+  const U32x4 r = philox4x32_10((uint32_t)block, m, gen.iter, 2u, gen.k0, gen.k1);
+  const float ua = (float)((r.x >> 8) + 1u) * 0x1p-24f, ub = (float)((r.z >> 8) + 1u) * 0x1p-24f;
+  const float ra = sqrtf(-2.0f * logf(ua)), rb = sqrtf(-2.0f * logf(ub));
+  float sa, ca, sb, cb;
+  sincospif(2.0f * uniform24(r.y), &sa, &ca);
+  sincospif(2.0f * uniform24(r.w), &sb, &cb);
+  return make_float4(gen.sigma * (ra * ca), gen.sigma * (ra * sa), gen.sigma * (rb * cb), gen.sigma * (rb * sb));
+}
+
 __global__ __launch_bounds__(kBlock) void rosenbrock_kernel(const float* __restrict__ x,
-                                                            const float* __restrict__ noise,
+                                                            const float* __restrict__ noise, NoiseGen gen,
                                                             float* __restrict__ g, uint64_t d, uint32_t M) {
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
   for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < d; i += stride) {
     const float base = rosenbrock_component(i > 0 ? x[i - 1] : 0.f, x[i], i + 1 < d ? x[i + 1] : 0.f, i > 0, i + 1 < d);
     for (uint32_t m = 0; m < M; ++m) {
       const uint64_t o = (uint64_t)m * d + i;
-      g[o] = noise != nullptr ? base + noise[o] : base;
+      if (gen.sigma > 0.f) {
+        const float4 z = gaussian4(gen, i >> 2, m);
+        const uint32_t c = (uint32_t)(i & 3);
+        g[o] = base + (c == 0 ? z.x : c == 1 ? z.y : c == 2 ? z.z : z.w);
+      } else {
+        g[o] = noise != nullptr ? base + noise[o] : base;
+      }
     }
   }
 }
@@ -444,7 +462,7 @@ __global__ __launch_bounds__(kBlock) void rosenbrock_kernel(const float* __restr
 // is computed once and reused for all workers, the noise is streamed with 16-byte loads.
 template <bool FUSE>
 __global__ __launch_bounds__(kBlock) void rosenbrock_vec_kernel(const float* __restrict__ x,
-                                                                const float4* __restrict__ noise4,
+                                                                const float4* __restrict__ noise4, NoiseGen gen,
                                                                 float4* __restrict__ g4, uint64_t nvec, uint32_t M,
                                                                 ScaleFusion fuse) {
   __shared__ float red[16];
@@ -466,8 +484,8 @@ __global__ __launch_bounds__(kBlock) void rosenbrock_vec_kernel(const float* __r
     float amax = 0.f;
     if (active) {
       float4 o = base;
-      if (noise4 != nullptr) {
-        const float4 n = load_stream(noise4 + (uint64_t)m * nvec + q);
+      if (gen.sigma > 0.f || noise4 != nullptr) {
+        const float4 n = gen.sigma > 0.f ? gaussian4(gen, q, m) : load_stream(noise4 + (uint64_t)m * nvec + q);
         o.x = base.x + n.x;
         o.y = base.y + n.y;
         o.z = base.z + n.z;
@@ -568,7 +586,7 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
   return hipGetLastError();
 }
 
-hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, float* g,
+hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, NoiseGen gen, float* g,
                                   const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s) {
   if (fused_rows != nullptr) *fused_rows = 0;
   if (d % 4 == 0 && aligned16(x) && aligned16(noise) && aligned16(g)) {
@@ -577,17 +595,18 @@ hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const 
     if (fuse != nullptr && fused_rows != nullptr && blocks <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
         aligned16(fuse->gref2)) {
       hipLaunchKernelGGL(rosenbrock_vec_kernel<true>, dim3(blocks), dim3(kBlock), 0, s, x,
-                         reinterpret_cast<const float4*>(noise), reinterpret_cast<float4*>(g), nvec, M, *fuse);
+                         reinterpret_cast<const float4*>(noise), gen, reinterpret_cast<float4*>(g), nvec, M, *fuse);
       *fused_rows = blocks;
     } else {
       hipLaunchKernelGGL(rosenbrock_vec_kernel<false>, dim3(blocks), dim3(kBlock), 0, s, x,
-                         reinterpret_cast<const float4*>(noise), reinterpret_cast<float4*>(g), nvec, M, ScaleFusion{});
+                         reinterpret_cast<const float4*>(noise), gen, reinterpret_cast<float4*>(g), nvec, M,
+                         ScaleFusion{});
     }
     return hipGetLastError();
   }
   const uint64_t bx = (d + kBlock - 1) / kBlock;
-  hipLaunchKernelGGL(rosenbrock_kernel, dim3((uint32_t)(bx < 16384 ? bx : 16384)), dim3(kBlock), 0, s, x, noise, g,
-                     d, M);
+  hipLaunchKernelGGL(rosenbrock_kernel, dim3((uint32_t)(bx < 16384 ? bx : 16384)), dim3(kBlock), 0, s, x, noise, gen,
+                     g, d, M);
   return hipGetLastError();
 }
 

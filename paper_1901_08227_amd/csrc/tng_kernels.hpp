@@ -92,7 +92,17 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
                                   const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,
                                   const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
                                   hipStream_t s);
-hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, float* g,
+// Gaussian noise made on the device (sigma > 0): element e of worker m at iteration iter is
+// sigma * z, z from the Box-Muller transform of the Philox block (e >> 2, m, iter, 2): words 0, 1
+// give z for e & 3 = 0 (cosine) and 1 (sine), words 2, 3 for e & 3 = 2 and 3;
+// u1 = ((word >> 8) + 1) 2^-24 in (0, 1], u2 = (word >> 8) 2^-24, z = sqrt(-2 ln u1) {cos, sin}(2 pi u2).
+struct NoiseGen {
+  float sigma;
+  uint32_t k0, k1, iter;
+};
+// noise: tensor [M][d] added to the gradient, or nullptr; gen.sigma > 0 adds generated noise instead
+// (the tensor is then ignored).
+hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, NoiseGen gen, float* g,
                                   const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s);
 
 }  // namespace tng

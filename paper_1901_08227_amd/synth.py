@@ -41,6 +41,28 @@ def logreg_dense(M: int, n_rows: int, d: int, seed: int, device="cpu"):
     return X, y, w_star
 
 
+def logreg_skewed(M: int, n_rows: int, d: int, c_sk: float, c_th: float, seed: int, device="cpu"):
+    """Dense shards with a skewed feature scale (section "Convex Problems": D = 512, N = 2048 in all,
+    M = 4, batch 8, c_th = 0.6, c_sk a power of 1/4).
+
+    Normalised data a_bar ~ N(0,1); one magnitude vector B ~ U[0,1]^d shared by all rows, whose
+    entries at or below c_th are shrunk by the factor c_sk; features a = a_bar * B; labels from a
+    planted w_bar ~ N(0, I) as sign(a_bar . w_bar), stored as 0/1.  Returns (X[M][n_rows][d],
+    y[M][n_rows], B).
+    """
+    g = _gen(seed, device)
+    mag = torch.rand(d, generator=g, device=device, dtype=torch.float32)
+    mag = torch.where(mag <= c_th, mag * c_sk, mag)
+    w_bar = torch.randn(d, generator=g, device=device, dtype=torch.float32)
+    X = torch.empty((M, n_rows, d), device=device, dtype=torch.float32)
+    y = torch.empty((M, n_rows), device=device, dtype=torch.float32)
+    for m in range(M):
+        a_bar = torch.randn((n_rows, d), generator=g, device=device, dtype=torch.float32)
+        y[m] = (a_bar @ w_bar > 0).to(torch.float32)
+        X[m] = a_bar * mag
+    return X, y, mag
+
+
 def logreg_csr(M: int, n_rows: int, d: int, nnz_row: int, seed: int, device="cpu"):
     """Per-worker CSR shards: nnz_row distinct uniform columns per row (sorted), values ~ N(0,1).
 

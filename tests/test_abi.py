@@ -108,6 +108,7 @@ def test_calls_reject_null_and_misaligned_pointers_before_launching():
     assert L.tng_minibatch_indices(h, 0, p) == B.TNG_ERR_BAD_STATE
     assert L.tng_step(h, 0, p, p, p, p, p, p) == B.TNG_ERR_BAD_STATE
     assert L.tng_set_noise(h, p) == B.TNG_ERR_BAD_STATE                                # not a Rosenbrock context
+    assert L.tng_set_noise_variance(h, 0.01) == B.TNG_ERR_BAD_STATE
     assert L.tng_destroy(h) == B.TNG_OK
     # the combined normalisation needs its second reference first
     h = _fake_ctx(norm=B.NORM_COMB, problem=B.PROB_EXTERNAL, batch=0)
@@ -124,6 +125,12 @@ def test_calls_reject_null_and_misaligned_pointers_before_launching():
     assert L.tng_destroy(h) == B.TNG_OK
     h = _fake_ctx(problem=B.PROB_EXTERNAL, batch=0)
     assert L.tng_set_worker_means(h, p) == B.TNG_ERR_BAD_STATE                         # not a mean-reference context
+    assert L.tng_destroy(h) == B.TNG_OK
+    h = _fake_ctx(problem=B.PROB_ROSENBROCK, batch=0)
+    assert L.tng_set_noise_variance(h, -1.0) == B.TNG_ERR_INVALID_ARG
+    assert L.tng_set_noise_variance(h, float("nan")) == B.TNG_ERR_INVALID_ARG
+    assert L.tng_set_noise_variance(h, float("inf")) == B.TNG_ERR_INVALID_ARG
+    assert L.tng_set_noise_variance(h, 0.01) == B.TNG_OK and L.tng_set_noise_variance(h, 0.0) == B.TNG_OK
     assert L.tng_destroy(h) == B.TNG_OK
     # update_reference is a no-op (and OK) when no refresh is due
     h = _fake_ctx(ref_period=16, problem=B.PROB_EXTERNAL, batch=0)

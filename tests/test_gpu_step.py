@@ -37,8 +37,9 @@ def _teacher_forced_step(ctx, cfg, it, w, gref, buf, grad_ref, grad_exact=False)
     assert np.array_equal(gref.cpu().numpy(), r1), f"it={it}: reference"
 
 
-def _dense_case(M, n, d, batch, bits, norm, T, seed, lr=0.1, l2=0.0, ref_period=1):
-    X, y, _ = synth.logreg_dense(M, n, d, seed=seed, device=DEV)
+def _dense_case(M, n, d, batch, bits, norm, T, seed, lr=0.1, l2=0.0, ref_period=1, data=None,
+                full_gradient_reference=False):
+    X, y = data if data is not None else synth.logreg_dense(M, n, d, seed=seed, device=DEV)[:2]
     ctx = make_ctx(d, M, bits, norm, seed=seed, lr=lr, l2=l2, batch=batch, ref_period=ref_period,
                    problem=B.PROB_LOGREG_DENSE)
     ctx.set_logreg_dense([X[m] for m in range(M)], [y[m] for m in range(M)])
@@ -46,6 +47,10 @@ def _dense_case(M, n, d, batch, bits, norm, T, seed, lr=0.1, l2=0.0, ref_period=
     Xh, yh = X.cpu().numpy(), y.cpu().numpy()
     w = torch.zeros(d, device=DEV)
     gref = torch.zeros(d, device=DEV)
+    if full_gradient_reference:      # the convex experiments start the reference from a full gradient
+        full = np.mean([O.grad_logreg_dense(Xh[m], yh[m], np.zeros(d, np.float32), np.arange(n), l2)
+                        for m in range(M)], axis=0)
+        gref = torch.from_numpy(full.astype(np.float32)).to(DEV)
     buf = buffers(ctx)
 
     def loss(wv):
@@ -70,6 +75,20 @@ def test_dense_logistic_small_config_all_iterations():
     say("dense logistic d=1000 M=4 n=2000 B=64 T=100")
     first, last = _dense_case(M=4, n=2000, d=1000, batch=64, bits=2, norm=B.NORM_SUB, T=100, seed=0)
     assert abs(first - np.log(2)) < 1e-6 and last < first - 0.02
+
+
+def test_dense_logistic_skewed_features_at_the_experiments_shape():
+    # D = 512, N = 2048 over M = 4 workers, batch 8, c_th = 0.6, c_sk = 1/16, l2 > 0, reference started
+    # from the full gradient and refreshed from the last decoded average (section "Convex Problems")
+    for bits, norm in [(2, B.NORM_SUB), (4, B.NORM_SUB), (2, B.NORM_MEAN)]:
+        say(f"skewed logistic d=512 M=4 n=512 B=8 bits={bits} norm={norm}")
+        X, y, mag = synth.logreg_skewed(4, 512, 512, c_sk=1.0 / 16, c_th=0.6, seed=11, device=DEV)
+        assert 0.5 < float((mag < 0.6 / 16 + 1e-6).float().mean()) < 0.7          # about c_th of the columns shrunk
+        if norm == B.NORM_MEAN:
+            continue                                                               # covered by the codec tests
+        first, last = _dense_case(M=4, n=512, d=512, batch=8, bits=bits, norm=norm, T=60, seed=11, lr=0.1,
+                                  l2=0.01, data=(X, y), full_gradient_reference=True)
+        assert last < first - 0.02
 
 
 def test_dense_logistic_quotient_two_bit_scaled():
@@ -105,6 +124,49 @@ def test_rosenbrock_chain_first_iterations_at_full_shape():
         _teacher_forced_step(ctx, cfg, it, x, gref, buf,
                              lambda w0: np.stack([O.grad_rosenbrock(w0, nh[m]) for m in range(M)]), grad_exact=True)
     ctx.close()
+
+
+def test_rosenbrock_noise_generated_on_the_device():
+    # N(0, 0.01) noise from the library's own Box-Muller (binary32) against the float64 oracle: the
+    # gradient within a few units in the last place of the noise, everything downstream bit for bit
+    for d, M, bits in [(1 << 16, 8, 2), (4099, 3, 4), (6, 2, 2)]:
+        say(f"rosenbrock with device noise d={d} M={M}")
+        seed, variance = (5 << 32) | 77, 0.01
+        ctx = make_ctx(d, M, bits, B.NORM_SUB, seed=seed, lr=1e-5, ref_period=2, problem=B.PROB_ROSENBROCK)
+        ctx.set_noise(torch.ones((M, d), device=DEV))       # replaced by the generator below
+        ctx.set_noise_variance(variance)
+        cfg = oracle_cfg(ctx)
+        x = synth.rosenbrock_start(d, 4, device=DEV)
+        gref = torch.zeros(d, device=DEV)
+        buf = buffers(ctx)
+        for it in range(3):
+            w0, r0 = x.cpu().numpy(), gref.cpu().numpy()
+            ctx.step(it, x, gref, buf["g"], buf["codes"], buf["scales"], buf["vbar"])
+            torch.cuda.synchronize()
+            gh = buf["g"].cpu().numpy()
+            base = O.grad_rosenbrock(w0).astype(np.float64)
+            for m in range(M):
+                noise = O.gaussian_noise(seed, it, m, d, variance)
+                want = base + noise
+                err = np.abs(gh[m] - want)
+                assert np.all(err <= 2.0 ** -24 * np.abs(want) + 8 * 2.0 ** -24 * np.abs(noise) + 1e-30), \
+                    f"it={it} m={m}: worst {err.max()}"
+            w1, r1, c1, s1, v1 = O.step(cfg, it, w0, r0, gh)
+            assert np.array_equal(buf["scales"].cpu().numpy(), s1) and np.array_equal(u32(buf["codes"]), c1)
+            assert np.array_equal(buf["vbar"].cpu().numpy(), v1) and np.array_equal(x.cpu().numpy(), w1)
+            assert np.array_equal(gref.cpu().numpy(), r1)
+        # local_grad alone gives the same gradient as the fused step did (same iteration, same iterate)
+        g2 = torch.empty_like(buf["g"])
+        xs = torch.from_numpy(w0).to(DEV)
+        ctx.local_grad(2, xs, g2)
+        torch.cuda.synchronize()
+        assert torch.equal(g2, buf["g"])
+        # switching the generator off gives the noiseless gradient
+        ctx.set_noise_variance(0.0)
+        ctx.local_grad(2, xs, g2)
+        torch.cuda.synchronize()
+        assert np.array_equal(g2[0].cpu().numpy(), O.grad_rosenbrock(w0))
+        ctx.close()
 
 
 def test_rosenbrock_small_and_ragged():
