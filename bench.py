@@ -214,11 +214,12 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup):
     shards, _ = synth.logreg_csr(M, n, d, nnz_row, seed=3, device=dev)
     ctx = B.Context(d=d, M=M, bits=4, norm=B.NORM_SUB, seed=3, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR, device=dev)
     ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    ctx.build_csr_index()          # one-off, depends on the shards only
     ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), max(steps // 2, 5), max(warmup // 2, 2))
     nnz = M * batch * nnz_row
     record("sparse logistic d=2^24 M=64 B=512 nnz/row=16777 4-bit sub", ms,
-           4 * nnz + 2 * 8 * nnz + 4 * M * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
-           f"{n} rows per worker held; bytes: column ids once (segment bounds), (col, val) twice (z pass, g pass), "
+           2 * 8 * nnz + 4 * M * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
+           f"{n} rows per worker held, per-row tile index prebuilt; bytes: (col, val) twice (z pass, g pass), "
            "g written once, two encode passes, decode/update")
     ctx.close()
     return out

@@ -132,6 +132,17 @@ tng_status tng_set_logreg_dense(tng_ctx* ctx, const float* const* X, const float
 tng_status tng_set_logreg_csr(tng_ctx* ctx, const int64_t* const* rowptr,
                               const int32_t* const* col, const float* const* val,
                               const float* const* y, const uint64_t* n_rows);
+/* Optional, CSR problem: a per-row index of where each stored row enters each column tile of the
+ * gradient kernels (the columns are processed in tiles of 2^14 coordinates held in on-chip memory).
+ * Without it every tng_local_grad / tng_step re-derives these offsets with a pass over the column ids
+ * of its minibatch rows; with it that pass becomes a small gather.  The index depends on the shards
+ * only, costs 4 (ceil(d / 2^14) + 1) bytes per row (about 3 % of a row at 0.1 % density) and is built
+ * once: tng_set_csr_index enqueues the build on the context's stream for the shards given to the last
+ * tng_set_logreg_csr (a later tng_set_logreg_csr drops it).  index: device, 256-byte aligned, at least
+ * tng_csr_index_bytes(cfg, n_rows) bytes (0 = not available for this configuration: not the CSR
+ * problem, or a shard of 2^31 rows or more), owned by the caller and kept alive while it is in use. */
+size_t tng_csr_index_bytes(const tng_config* cfg, const uint64_t* n_rows);
+tng_status tng_set_csr_index(tng_ctx* ctx, void* index, size_t bytes);
 /* Rosenbrock: additive noise of the coming iteration, device [M][d], or NULL for none
  * ("Nonconvex Problems": the stochastic gradient is the exact gradient plus Gaussian noise). */
 tng_status tng_set_noise(tng_ctx* ctx, const float* noise);

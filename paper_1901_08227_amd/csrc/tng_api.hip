@@ -16,7 +16,9 @@ struct tng_ctx {
   // workspace partition (device)
   uint32_t* idx;          // [M][batch] minibatch row ids
   float* resid;           // [M][batch] sigma(z) - y
-  const void** tables;    // 5 pointer tables of M entries: X|rowptr, col, val, y, and n_rows
+  const void** tables;    // 6 tables of M entries: X|rowptr, col, val, y, n_rows, per-row tile index (CSR)
+  std::vector<uint64_t> n_rows;  // host copy of the row counts
+  bool have_index;        // the CSR tile index has been built for the current shards
   float* partials;        // [kAbsmaxMaxBlocks][M] partial maxima of the scale pass
   int64_t* rowbase;       // [M][batch] start of each minibatch row in the worker's CSR arrays
   uint32_t* bounds;       // [M][tiles+1][batch] segment bounds of the CSR gradient
@@ -70,7 +72,7 @@ Partition partition(const tng_config* c) {
   p.resid_off = off;
   off += round_up(mb * sizeof(float));
   p.tables_off = off;
-  off += round_up(logreg ? (size_t)c->M * 5 * sizeof(void*) : 0);
+  off += round_up(logreg ? (size_t)c->M * 6 * sizeof(void*) : 0);
   p.partials_off = off;
   off += round_up((size_t)tng::kAbsmaxMaxBlocks * c->M * sizeof(float));
   p.rowbase_off = off;
@@ -126,6 +128,7 @@ tng::LogregData logreg_tables(const tng_ctx* ctx) {
   p.val = reinterpret_cast<const float* const*>(t + 2 * (size_t)M);
   p.y = reinterpret_cast<const float* const*>(t + 3 * (size_t)M);
   p.n_rows = reinterpret_cast<const uint64_t*>(t + 4 * (size_t)M);
+  p.tile_index = ctx->have_index ? reinterpret_cast<const uint32_t* const*>(t + 5 * (size_t)M) : nullptr;
   return p;
 }
 
@@ -240,6 +243,8 @@ tng_status upload_tables(tng_ctx* ctx, const void* const* t0, const void* const*
                      ctx->stream) != hipSuccess)
     return TNG_ERR_HIP;
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TNG_ERR_HIP;
+  ctx->n_rows.assign(n_rows, n_rows + M);
+  ctx->have_index = false;  // an index belongs to the shards it was built from
   return TNG_OK;
 }
 
@@ -301,6 +306,7 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->zpart = reinterpret_cast<float*>(base + p.zpart_off);
   ctx->sums = reinterpret_cast<double*>(base + p.sums_off);
   ctx->have_dense = ctx->have_csr = false;
+  ctx->have_index = false;
   ctx->noise = nullptr;
   ctx->noise_sigma = 0.f;
   ctx->gref2 = nullptr;
@@ -341,6 +347,46 @@ tng_status tng_set_logreg_csr(tng_ctx* ctx, const int64_t* const* rowptr, const 
                                      reinterpret_cast<const void* const*>(y), n_rows);
   if (s == TNG_OK) ctx->have_csr = true;
   return s;
+}
+
+size_t tng_csr_index_bytes(const tng_config* cfg, const uint64_t* n_rows) {
+  if (!config_valid(cfg) || cfg->problem != TNG_PROB_LOGREG_CSR || n_rows == nullptr) return 0;
+  const size_t per_row = ((size_t)tng::csr_tiles(cfg->d) + 1) * sizeof(uint32_t);
+  size_t total = 0;
+  for (uint32_t m = 0; m < cfg->M; ++m) {
+    if (n_rows[m] == 0 || n_rows[m] > 0x7fffffffull) return 0;
+    total += round_up((size_t)n_rows[m] * per_row);
+  }
+  return total;
+}
+
+tng_status tng_set_csr_index(tng_ctx* ctx, void* index, size_t bytes) {
+  if (ctx == nullptr || index == nullptr || !aligned(index, kAlign)) return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.problem != TNG_PROB_LOGREG_CSR || !ctx->have_csr) return TNG_ERR_BAD_STATE;
+  const size_t need = tng_csr_index_bytes(&ctx->cfg, ctx->n_rows.data());
+  if (need == 0) return TNG_ERR_UNSUPPORTED;
+  if (bytes < need) return TNG_ERR_WORKSPACE;
+  const uint32_t M = ctx->cfg.M;
+  const size_t per_row = ((size_t)tng::csr_tiles(ctx->cfg.d) + 1) * sizeof(uint32_t);
+  std::vector<const void*> host(M);
+  uint64_t max_rows = 0;
+  size_t off = 0;
+  for (uint32_t m = 0; m < M; ++m) {
+    host[m] = static_cast<char*>(index) + off;
+    off += round_up((size_t)ctx->n_rows[m] * per_row);
+    if (ctx->n_rows[m] > max_rows) max_rows = ctx->n_rows[m];
+  }
+  if (hipMemcpyAsync(ctx->tables + 5 * (size_t)M, host.data(), M * sizeof(void*), hipMemcpyHostToDevice,
+                     ctx->stream) != hipSuccess)
+    return TNG_ERR_HIP;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TNG_ERR_HIP;
+  ctx->have_index = true;
+  const tng::LogregData p = logreg_tables(ctx);
+  if (tng::launch_csr_tile_index(p, ctx->cfg.d, M, max_rows, ctx->stream) != hipSuccess) {
+    ctx->have_index = false;
+    return TNG_ERR_HIP;
+  }
+  return TNG_OK;
 }
 
 tng_status tng_set_noise(tng_ctx* ctx, const float* noise) {

@@ -36,6 +36,24 @@ __device__ __forceinline__ void store_stream(float4* p, const float4& x) {
   __builtin_nontemporal_store(v, reinterpret_cast<v4f_t*>(p));
 }
 
+// A pointer that was itself loaded from memory (a per-worker table of shard pointers) has no known
+// address space, and loads through it become FLAT instructions: those count against the LDS counter
+// as well, so the compiler drains every outstanding load before the next LDS access and the loads no
+// longer overlap.  All such tables here hold device-memory pointers: say so.
+template <typename T>
+using GlobalPtr = const T __attribute__((address_space(1)))*;
+
+template <typename T>
+__device__ __forceinline__ GlobalPtr<T> as_global(const T* p) {
+  return (GlobalPtr<T>)p;
+}
+
+// float4 number i of a 16-byte aligned global array of floats.
+__device__ __forceinline__ float4 load4(GlobalPtr<float> p, uint64_t i) {
+  const v4f_t v = reinterpret_cast<GlobalPtr<v4f_t>>(p)[i];
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // Store of a packed word that is not read again by the same kernel.  A small write stream next to a
 // large read stream costs far more HBM time than its bytes; stores marked device-coherent (the sc1
 // cache-policy bit, which is what a relaxed device-scope atomic store compiles to) measured a

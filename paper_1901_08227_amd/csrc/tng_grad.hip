@@ -88,16 +88,15 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_resid_kernel(const float*
   __shared__ float red[kWavesPerBlock];
   const uint32_t m = blockIdx.y, i = blockIdx.x;
   const uint32_t row = idx[(uint64_t)m * batch + i];
-  const float* x = Xs[m] + (uint64_t)row * d;
+  const GlobalPtr<float> x = as_global(Xs[m]) + (uint64_t)row * d;
   float acc = 0.f;
   if (VEC) {
-    const float4* x4 = reinterpret_cast<const float4*>(x);
     const float4* w4 = reinterpret_cast<const float4*>(w);
     const uint64_t nvec = d / 4;
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 #pragma unroll 4
     for (uint64_t k = threadIdx.x; k < nvec; k += kBlock) {
-      const float4 xv = x4[k], wv = w4[k];
+      const float4 xv = load4(x, k), wv = w4[k];
       a0 = __builtin_fmaf(xv.x, wv.x, a0);
       a1 = __builtin_fmaf(xv.y, wv.y, a1);
       a2 = __builtin_fmaf(xv.z, wv.z, a2);
@@ -108,7 +107,7 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_resid_kernel(const float*
     for (uint64_t k = threadIdx.x; k < d; k += kBlock) acc = __builtin_fmaf(x[k], w[k], acc);
   }
   const float z = block_sum(acc, red);
-  if (threadIdx.x == 0) resid[(uint64_t)m * batch + i] = logistic_residual(z, ys[m][row]);
+  if (threadIdx.x == 0) resid[(uint64_t)m * batch + i] = logistic_residual(z, as_global(ys[m])[row]);
 }
 
 // g_m[k] = (1/B) sum_i r_i X[idx_i][k] + l2 w[k]; a thread owns 4 (VEC) or 1 columns.
@@ -124,7 +123,7 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
   __shared__ uint32_t sRow[kBlock];
   __shared__ float red[16];
   const uint32_t m = blockIdx.y;
-  const float* X = Xs[m];
+  const GlobalPtr<float> X = as_global(Xs[m]);
   const uint64_t col = (uint64_t)blockIdx.x * kBlock + threadIdx.x;  // float4 (VEC) or float index
   const uint64_t ncol = VEC ? d / 4 : d;
   const bool active = col < ncol;
@@ -141,7 +140,7 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
       if (VEC) {
 #pragma unroll 8
         for (uint32_t i = 0; i < cnt; ++i) {
-          const float4 xv = reinterpret_cast<const float4*>(X + (uint64_t)sRow[i] * d)[col];
+          const float4 xv = load4(X + (uint64_t)sRow[i] * d, col);
           const float r = sR[i];
           acc.x = __builtin_fmaf(r, xv.x, acc.x);
           acc.y = __builtin_fmaf(r, xv.y, acc.y);
@@ -216,9 +215,9 @@ __global__ __launch_bounds__(kBlock) void csr_bounds_kernel(const int64_t* const
                                                             uint32_t ntiles, uint32_t tile_shift) {
   const uint32_t m = blockIdx.y, i = blockIdx.x;
   const uint32_t row = idx[(uint64_t)m * batch + i];
-  const int64_t a = rowptrs[m][row];
-  const uint32_t nnz = (uint32_t)(rowptrs[m][row + 1] - a);
-  const int32_t* __restrict__ c = cols[m] + a;
+  const int64_t a = as_global(rowptrs[m])[row];
+  const uint32_t nnz = (uint32_t)(as_global(rowptrs[m])[row + 1] - a);
+  const GlobalPtr<int32_t> c = as_global(cols[m]) + a;
   if (threadIdx.x == 0) rowbase[(uint64_t)m * batch + i] = a;
   uint32_t* __restrict__ out = bounds + (uint64_t)m * (ntiles + 1) * batch + i;
   // entry k opens every tile after the tile of entry k-1 up to its own tile
@@ -226,6 +225,58 @@ __global__ __launch_bounds__(kBlock) void csr_bounds_kernel(const int64_t* const
     const uint32_t prev = k == 0 ? 0u : ((uint32_t)c[k - 1] >> tile_shift) + 1u;
     const uint32_t cur = k == nnz ? ntiles : ((uint32_t)c[k] >> tile_shift);
     for (uint32_t t = prev; t <= cur; ++t) out[(uint64_t)t * batch] = k;
+  }
+}
+
+// One-off: the same offsets for every row of every shard, row-major (index[m][row][t]).
+__global__ __launch_bounds__(kBlock) void csr_tile_index_kernel(const int64_t* const* __restrict__ rowptrs,
+                                                                const int32_t* const* __restrict__ cols,
+                                                                const uint64_t* __restrict__ n_rows,
+                                                                const uint32_t* const* __restrict__ index,
+                                                                uint32_t ntiles, uint32_t tile_shift) {
+  const uint32_t m = blockIdx.y;
+  const uint64_t row = blockIdx.x;
+  if (row >= n_rows[m]) return;
+  const int64_t a = as_global(rowptrs[m])[row];
+  const uint32_t nnz = (uint32_t)(as_global(rowptrs[m])[row + 1] - a);
+  const GlobalPtr<int32_t> c = as_global(cols[m]) + a;
+  uint32_t* __restrict__ out = const_cast<uint32_t*>(index[m]) + row * (ntiles + 1);
+  for (uint32_t k = threadIdx.x; k <= nnz; k += kBlock) {
+    const uint32_t prev = k == 0 ? 0u : ((uint32_t)c[k - 1] >> tile_shift) + 1u;
+    const uint32_t cur = k == nnz ? ntiles : ((uint32_t)c[k] >> tile_shift);
+    for (uint32_t t = prev; t <= cur; ++t) out[t] = k;
+  }
+}
+
+// Per iteration, with the index: the index rows of the minibatch are transposed into the tile-major
+// bounds array (64 x 64 blocks through LDS, both sides coalesced), and rowbase is filled.
+constexpr int kGatherTile = 64;
+__global__ __launch_bounds__(kBlock) void csr_gather_bounds_kernel(const int64_t* const* __restrict__ rowptrs,
+                                                                   const uint32_t* const* __restrict__ index,
+                                                                   const uint32_t* __restrict__ idx,
+                                                                   int64_t* __restrict__ rowbase,
+                                                                   uint32_t* __restrict__ bounds, uint32_t batch,
+                                                                   uint32_t ntiles) {
+  __shared__ uint32_t tile[kGatherTile][kGatherTile + 1];
+  const uint32_t m = blockIdx.z;
+  const uint32_t t0 = blockIdx.x * kGatherTile, i0 = blockIdx.y * kGatherTile;
+  const uint32_t tx = threadIdx.x % kGatherTile, ty = threadIdx.x / kGatherTile;
+  const GlobalPtr<uint32_t> src = as_global(index[m]);
+  for (uint32_t r = ty; r < (uint32_t)kGatherTile; r += kBlock / kGatherTile) {
+    const uint32_t i = i0 + r;
+    if (i < batch && t0 + tx <= ntiles) {
+      const uint64_t row = idx[(uint64_t)m * batch + i];
+      tile[r][tx] = src[row * (ntiles + 1) + t0 + tx];
+    }
+  }
+  __syncthreads();
+  for (uint32_t r = ty; r < (uint32_t)kGatherTile; r += kBlock / kGatherTile) {
+    const uint32_t t = t0 + r;
+    if (t <= ntiles && i0 + tx < batch) bounds[((uint64_t)m * (ntiles + 1) + t) * batch + i0 + tx] = tile[tx][r];
+  }
+  if (blockIdx.x == 0 && ty == 0 && i0 + tx < batch) {
+    const uint64_t o = (uint64_t)m * batch + i0 + tx;
+    rowbase[o] = as_global(rowptrs[m])[idx[o]];
   }
 }
 
@@ -251,7 +302,7 @@ struct CsrBatch {
   float val[kCsrUnroll];
 };
 
-__device__ __forceinline__ void csr_load_batch(const int32_t* __restrict__ c, const float* __restrict__ v,
+__device__ __forceinline__ void csr_load_batch(GlobalPtr<int32_t> c, GlobalPtr<float> v,
                                                const int64_t* sLo, const uint32_t* sLen, uint32_t j0, uint32_t count,
                                                uint32_t gl, CsrBatch& b) {
 #pragma unroll
@@ -296,8 +347,8 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int32_t* const
   } else {
     for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) wtile[j] = c0 + j < d ? w[c0 + j] : 0.f;
   }
-  const int32_t* __restrict__ c = cols[m];
-  const float* __restrict__ v = vals[m];
+  const GlobalPtr<int32_t> c = as_global(cols[m]);
+  const GlobalPtr<float> v = as_global(vals[m]);
   const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
   for (uint32_t first = 0; first < batch; first += kCsrRows) {
     const uint32_t count = min((uint32_t)kCsrRows, batch - first);
@@ -332,9 +383,12 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int32_t* const
   }
 }
 
-// z[m][i] = sum over the tiles of the partial dot products zpart[m][t][i].
-__global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __restrict__ zpart, float* __restrict__ z,
-                                                              uint32_t batch, uint32_t ntiles) {
+// r[m][i] = (sigma(z_i) - y_i) / B with z_i = sum over the tiles of the partial dot products
+// zpart[m][t][i]: what the gradient pass multiplies every stored entry of row i by.
+__global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __restrict__ zpart,
+                                                              const float* const* __restrict__ ys,
+                                                              const uint32_t* __restrict__ idx, float* __restrict__ r,
+                                                              uint32_t batch, uint32_t ntiles, float inv_b) {
   const uint32_t m = blockIdx.y;
   const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
   if (i >= batch) return;
@@ -348,19 +402,24 @@ __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __res
     a3 += p[(uint64_t)(t + 3) * batch];
   }
   for (; t < ntiles; ++t) a0 += p[(uint64_t)t * batch];
-  z[(uint64_t)m * batch + i] = (a0 + a1) + (a2 + a3);
+  const float z = (a0 + a1) + (a2 + a3);
+  const uint64_t o = (uint64_t)m * batch + i;
+  r[o] = logistic_residual(z, as_global(ys[m])[idx[o]]) * inv_b;
 }
 
+// Gradient pass: one workgroup per (worker, tile); every minibatch row adds (r_i / B) val into the
+// fp64 tile in LDS, and the finished tile is written once (+ l2 w).
+// (A software-pipelined variant that prefetched the next tile's entries while the current tile was
+// written out measured slower: the pass is bound by the number of 128-byte lines its short segments
+// touch, not by latency.)
 __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* const* __restrict__ cols,
                                                                const float* const* __restrict__ vals,
-                                                               const float* const* __restrict__ ys,
-                                                               const uint32_t* __restrict__ idx,
                                                                const int64_t* __restrict__ rowbase,
                                                                const uint32_t* __restrict__ bounds,
-                                                               const float* __restrict__ z, const float* __restrict__ w,
-                                                               float* __restrict__ g, uint64_t d, uint32_t batch,
-                                                               uint32_t ntiles, uint32_t tile_shift, float inv_b,
-                                                               float l2) {
+                                                               const float* __restrict__ resid,
+                                                               const float* __restrict__ w, float* __restrict__ g,
+                                                               uint64_t d, uint32_t batch, uint32_t ntiles,
+                                                               uint32_t tile_shift, float l2) {
   extern __shared__ double gtile[];  // g over the tile's columns, accumulated in fp64
   __shared__ int64_t sLo[kCsrRows];
   __shared__ uint32_t sLen[kCsrRows];
@@ -369,17 +428,14 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
   const uint32_t T = 1u << tile_shift;
   const uint64_t c0 = (uint64_t)t << tile_shift;
   for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) gtile[j] = 0.0;
-  const int32_t* __restrict__ c = cols[m];
-  const float* __restrict__ v = vals[m];
+  const GlobalPtr<int32_t> c = as_global(cols[m]);
+  const GlobalPtr<float> v = as_global(vals[m]);
   const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
   for (uint32_t first = 0; first < batch; first += kCsrRows) {
     const uint32_t count = min((uint32_t)kCsrRows, batch - first);
     __syncthreads();
     csr_stage_segments(rowbase, bounds, m, batch, ntiles, t, first, count, sLo, sLen);
-    for (uint32_t j = threadIdx.x; j < count; j += kCsrThreads) {
-      const uint64_t r = (uint64_t)m * batch + first + j;
-      sR[j] = logistic_residual(z[r], ys[m][idx[r]]) * inv_b;
-    }
+    for (uint32_t j = threadIdx.x; j < count; j += kCsrThreads) sR[j] = resid[(uint64_t)m * batch + first + j];
     __syncthreads();
     const uint32_t j0 = group * kCsrUnroll;
     CsrBatch b;
@@ -554,6 +610,13 @@ uint32_t csr_tiles(uint64_t d) {
   return (uint32_t)((d + (1ull << shift) - 1) >> shift);
 }
 
+hipError_t launch_csr_tile_index(const LogregData& p, uint64_t d, uint32_t M, uint64_t max_rows, hipStream_t s) {
+  if (max_rows == 0 || max_rows > 0x7fffffffull || p.tile_index == nullptr) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(csr_tile_index_kernel, dim3((uint32_t)max_rows, M), dim3(kBlock), 0, s, p.rowptr, p.col, p.n_rows,
+                     p.tile_index, csr_tiles(d), csr_tile_shift(d));
+  return hipGetLastError();
+}
+
 hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                   const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,
                                   const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
@@ -571,18 +634,24 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(csr_bounds_kernel, dim3(batch, M), dim3(kBlock), 0, s, p.rowptr, p.col, idx, rowbase, bounds,
-                     batch, ntiles, shift);
+  if (p.tile_index != nullptr) {
+    dim3 grid((ntiles + 1 + kGatherTile - 1) / kGatherTile, (batch + kGatherTile - 1) / kGatherTile, M);
+    hipLaunchKernelGGL(csr_gather_bounds_kernel, grid, dim3(kBlock), 0, s, p.rowptr, p.tile_index, idx, rowbase, bounds,
+                       batch, ntiles);
+  } else {
+    hipLaunchKernelGGL(csr_bounds_kernel, dim3(batch, M), dim3(kBlock), 0, s, p.rowptr, p.col, idx, rowbase, bounds,
+                       batch, ntiles, shift);
+  }
   hipLaunchKernelGGL(csr_z_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_w, s, p.col, p.val, rowbase, bounds, w,
                      zpart, d, batch, ntiles, shift);
-  hipLaunchKernelGGL(csr_z_reduce_kernel, dim3((batch + kBlock - 1) / kBlock, M), dim3(kBlock), 0, s, zpart, z, batch,
-                     ntiles);
+  hipLaunchKernelGGL(csr_z_reduce_kernel, dim3((batch + kBlock - 1) / kBlock, M), dim3(kBlock), 0, s, zpart, p.y, idx,
+                     z, batch, ntiles, inv_b);
   // The scale pass is not fused here: this kernel runs one workgroup per compute unit with its phases
   // back to back, and the extra reference loads and reduction in its epilogue cost more (+0.8 ms at
   // d = 2^24, M = 64) than the separate scale pass they would replace (0.7 ms).
   (void)fuse;
-  hipLaunchKernelGGL(csr_grad_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, p.y, idx, rowbase,
-                     bounds, z, w, g, d, batch, ntiles, shift, inv_b, l2);
+  hipLaunchKernelGGL(csr_grad_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, rowbase, bounds, z, w,
+                     g, d, batch, ntiles, shift, l2);
   return hipGetLastError();
 }
 

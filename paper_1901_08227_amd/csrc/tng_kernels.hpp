@@ -75,6 +75,7 @@ struct LogregData {
   const float* const* val;
   const float* const* y;        // device table [M]
   const uint64_t* n_rows;       // device [M]
+  const uint32_t* const* tile_index;  // device table [M] of per-row tile indices (CSR), or nullptr
 };
 
 hipError_t launch_minibatch_indices(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t M, uint32_t batch,
@@ -88,6 +89,10 @@ uint32_t csr_tiles(uint64_t d);
 // Device scratch: rowbase int64[M][batch]; bounds uint32[M][csr_tiles(d) + 1][batch];
 // zpart float[M][csr_tiles(d)][batch]; z float[M][batch].
 // Columns must be ascending within each row.
+// p.tile_index (optional): per worker uint32[n_rows][csr_tiles(d) + 1], entry [row][t] = offset within
+// the row of the first stored entry whose column is at or beyond the start of tile t; built once by
+// launch_csr_tile_index.  With it the per-iteration pass over the column ids is replaced by a gather.
+hipError_t launch_csr_tile_index(const LogregData& p, uint64_t d, uint32_t M, uint64_t max_rows, hipStream_t s);
 hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                   const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,
                                   const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,

@@ -132,6 +132,16 @@ def test_calls_reject_null_and_misaligned_pointers_before_launching():
     assert L.tng_set_noise_variance(h, float("inf")) == B.TNG_ERR_INVALID_ARG
     assert L.tng_set_noise_variance(h, 0.01) == B.TNG_OK and L.tng_set_noise_variance(h, 0.0) == B.TNG_OK
     assert L.tng_destroy(h) == B.TNG_OK
+    # the optional CSR tile index: sized from the row counts, needs the shards first
+    rows = (ctypes.c_uint64 * 4)(100, 200, 300, 400)
+    cfg = _cfg(problem=B.PROB_LOGREG_CSR, d=(1 << 15) + 1)
+    assert L.tng_csr_index_bytes(ctypes.byref(cfg), rows) >= 1000 * 4 * 4       # 3 tiles + 1 offsets per row
+    assert L.tng_csr_index_bytes(ctypes.byref(_cfg()), rows) == 0                # dense problem
+    assert L.tng_csr_index_bytes(ctypes.byref(cfg), None) == 0
+    h = _fake_ctx(problem=B.PROB_LOGREG_CSR)
+    assert L.tng_set_csr_index(h, p, 1 << 20) == B.TNG_ERR_BAD_STATE             # no shards yet
+    assert L.tng_set_csr_index(h, None, 1 << 20) == B.TNG_ERR_INVALID_ARG
+    assert L.tng_destroy(h) == B.TNG_OK
     # update_reference is a no-op (and OK) when no refresh is due
     h = _fake_ctx(ref_period=16, problem=B.PROB_EXTERNAL, batch=0)
     assert L.tng_update_reference(h, 3, p, p) == B.TNG_OK

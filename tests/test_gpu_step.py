@@ -229,14 +229,18 @@ def test_every_normalisation_through_the_fused_step():
             ctx.close()
 
 
-def test_csr_logistic_scaled():
-    # shape of the sparse configuration scaled to d=2^16, M=8, 0.1% density, 4-bit, subtraction
+@pytest.mark.parametrize("use_index", [False, True])
+def test_csr_logistic_scaled(use_index):
+    # shape of the sparse configuration scaled to d=2^16, M=8, 0.1% density, 4-bit, subtraction;
+    # with and without the prebuilt per-row tile index
     M, n, d, batch, seed = 8, 1024, 1 << 16, 128, 4
     nnz_row = round(1e-3 * d)
-    say(f"csr logistic d={d} M={M} nnz/row={nnz_row}")
+    say(f"csr logistic d={d} M={M} nnz/row={nnz_row} index={use_index}")
     shards, _ = synth.logreg_csr(M, n, d, nnz_row, seed, device=DEV)
     ctx = make_ctx(d, M, 4, B.NORM_SUB, seed=seed, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR)
     ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    if use_index:
+        ctx.build_csr_index()
     cfg = oracle_cfg(ctx)
     host = [tuple(t.cpu().numpy() for t in s) for s in shards]
     w = torch.zeros(d, device=DEV)
@@ -276,8 +280,9 @@ def _ragged_csr(M, n, d, lengths_fn, seed):
     return shards
 
 
+@pytest.mark.parametrize("use_index", [False, True])
 @pytest.mark.parametrize("case", ["ragged", "tiny_d", "odd_d_many_rows", "dense_rows"])
-def test_csr_logistic_edge_cases(case):
+def test_csr_logistic_edge_cases(case, use_index):
     if case == "ragged":        # empty rows, one-entry rows, rows longer than a lane group inside one tile
         M, n, d, batch = 3, 40, (1 << 15) + 24, 33
         lens = lambda m, i: [0, 1, 2, 700, 33, 5000][(i + m) % 6]
@@ -290,11 +295,13 @@ def test_csr_logistic_edge_cases(case):
     else:                       # nearly dense rows: many entries per (row, tile) segment
         M, n, d, batch = 2, 12, 1 << 14, 12
         lens = lambda m, i: (1 << 14) - 1 - i
-    say(f"csr edge case {case}: d={d} M={M} n={n} B={batch}")
+    say(f"csr edge case {case}: d={d} M={M} n={n} B={batch} index={use_index}")
     seed = 11
     shards = _ragged_csr(M, n, d, lens, seed)
     ctx = make_ctx(d, M, 4, B.NORM_SUB, seed=seed, lr=0.1, l2=0.001, batch=batch, problem=B.PROB_LOGREG_CSR)
     ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    if use_index:
+        ctx.build_csr_index()
     cfg = oracle_cfg(ctx)
     host = [tuple(t.cpu().numpy() for t in s) for s in shards]
     w = 0.1 * torch.randn(d, device=DEV)
@@ -314,6 +321,26 @@ def test_csr_logistic_edge_cases(case):
                 cond[m] = logistic_condition(Xb, host[m][3][ids[m]], w0, 0.001)
             return ref, cond
         _teacher_forced_step(ctx, cfg, it, w, gref, buf, grad_ref)
+    ctx.close()
+
+
+def test_csr_tile_index_changes_nothing_but_the_speed():
+    # same shards, same iterate: the gradient with the prebuilt index equals the one without, bit for bit;
+    # shards with different row counts; setting new shards drops the index
+    M, d, batch, seed = 3, (1 << 16) + 40, 50, 5
+    shards = [synth.logreg_csr(1, n, d, 70, seed + n, device=DEV)[0][0] for n in (60, 200, 33)]
+    ctx = make_ctx(d, M, 2, B.NORM_SUB, seed=seed, batch=batch, problem=B.PROB_LOGREG_CSR)
+    parts = [[s[k] for s in shards] for k in range(4)]
+    ctx.set_logreg_csr(*parts)
+    w = 0.05 * torch.randn(d, device=DEV)
+    g0, g1, g2 = (torch.empty((M, d), device=DEV) for _ in range(3))
+    ctx.local_grad(3, w, g0)
+    ctx.build_csr_index()
+    ctx.local_grad(3, w, g1)
+    ctx.set_logreg_csr(*parts)          # index dropped: back to the pass over the column ids
+    ctx.local_grad(3, w, g2)
+    torch.cuda.synchronize()
+    assert torch.equal(g0, g1) and torch.equal(g0, g2)
     ctx.close()
 
 
