@@ -363,16 +363,40 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
   constexpr int L = kLoadsPerLane;
   float4 xa[L], xb[L];
   uint32_t frag[L];
+  // The scale (and mean) of a worker is fetched before the tile loads that are to stay in flight
+  // during the previous worker's arithmetic: loads return in order, so a scalar fetched after them
+  // would make the wait for it a wait for the whole prefetch.
+  auto mean_of = [&](uint32_t m) { return NORM == kNormMean ? means[m] : 0.f; };
+  float ra = scales[m0], mua = mean_of(m0), rb = 0.f, mub = 0.f;
   load_worker_tile<NORM, FULL>(q, g4, nvec, m0, xa);
-  for (uint32_t m = m0; m < m_end; m += 2) {
-    if (m + 1 < m_end) load_worker_tile<NORM, FULL>(q, g4, nvec, m + 1, xb);
-    quantize_worker_tile<NORM, BITS, FULL>(q, xa, scales[m], NORM == kNormMean ? means[m] : 0.f, m, iter, k0, k1, frag);
+  // Steady state: both prefetches of a trip are unconditional.  A load issued under a condition
+  // makes the compiler wait for all outstanding loads where the paths join (it cannot count what
+  // is in flight), which would drain the prefetch before the arithmetic it is meant to overlap.
+  uint32_t m = m0;
+  for (; m + 2 < m_end; m += 2) {
+    rb = scales[m + 1];
+    mub = mean_of(m + 1);
+    load_worker_tile<NORM, FULL>(q, g4, nvec, m + 1, xb);
+    quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
     store_packed<BITS, WPW>(lds, wave, lane, frag, codes + (uint64_t)m * words, word_base, words);
-    if (m + 1 >= m_end) break;
-    if (m + 2 < m_end) load_worker_tile<NORM, FULL>(q, g4, nvec, m + 2, xa);
-    quantize_worker_tile<NORM, BITS, FULL>(q, xb, scales[m + 1], NORM == kNormMean ? means[m + 1] : 0.f, m + 1, iter, k0,
-                                           k1, frag);
+    ra = scales[m + 2];
+    mua = mean_of(m + 2);
+    load_worker_tile<NORM, FULL>(q, g4, nvec, m + 2, xa);
+    quantize_worker_tile<NORM, BITS, FULL>(q, xb, rb, mub, m + 1, iter, k0, k1, frag);
     store_packed<BITS, WPW>(lds, wave, lane, frag, codes + (uint64_t)(m + 1) * words, word_base, words);
+  }
+  // one or two workers are left, the first of them already in xa
+  if (m + 1 < m_end) {
+    rb = scales[m + 1];
+    mub = mean_of(m + 1);
+    load_worker_tile<NORM, FULL>(q, g4, nvec, m + 1, xb);
+    quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
+    store_packed<BITS, WPW>(lds, wave, lane, frag, codes + (uint64_t)m * words, word_base, words);
+    quantize_worker_tile<NORM, BITS, FULL>(q, xb, rb, mub, m + 1, iter, k0, k1, frag);
+    store_packed<BITS, WPW>(lds, wave, lane, frag, codes + (uint64_t)(m + 1) * words, word_base, words);
+  } else {
+    quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
+    store_packed<BITS, WPW>(lds, wave, lane, frag, codes + (uint64_t)m * words, word_base, words);
   }
 }
 
