@@ -23,24 +23,34 @@ def full_inputs():
     return g, gref
 
 
-@pytest.mark.parametrize("bits,norm", [(2, B.NORM_SUB), (4, B.NORM_SUB), (2, B.NORM_QUOT), (4, B.NORM_QUOT)])
-def test_full_size_windows(full_inputs, bits, norm):
+@pytest.mark.parametrize("bits,norm,scale", [(2, B.NORM_SUB, B.SCALE_MAX), (4, B.NORM_SUB, B.SCALE_MAX),
+                                             (2, B.NORM_QUOT, B.SCALE_MAX), (4, B.NORM_QUOT, B.SCALE_MAX),
+                                             (2, B.NORM_MEAN, B.SCALE_MAX), (4, B.NORM_SUB, B.SCALE_L2)])
+def test_full_size_windows(full_inputs, bits, norm, scale):
     g, gref = full_inputs
     d, M = D_FULL, M_FULL
-    ctx = make_ctx(d, M, bits, norm, seed=1)
+    ctx = make_ctx(d, M, bits, norm, seed=1, scale=scale)
     cfg = oracle_cfg(ctx)
     buf = buffers(ctx)
+    means_dev = None
+    if norm == B.NORM_MEAN:
+        means_dev = torch.zeros(M, device=DEV)
+        ctx.set_worker_means(means_dev)
     it = 3
-    say(f"full size bits={bits} norm={norm}: encode + decode")
+    say(f"full size bits={bits} norm={norm} scale={scale}: encode + decode")
     ctx.normalize_encode(it, g, gref, buf["codes"], buf["scales"])
     ctx.decode_aggregate(buf["codes"], buf["scales"], gref, buf["vbar"])
     torch.cuda.synchronize()
     scales = buf["scales"].cpu().numpy()
     rh = gref.cpu().numpy()
-    say("scales on the host")
+    say("means and scales on the host")
+    means = None
+    if means_dev is not None:
+        means = np.array([O.worker_mean(g[m].cpu().numpy()) for m in range(M)], dtype=np.float32)
+        assert np.array_equal(means_dev.cpu().numpy(), means), "worker means"
     for m in range(M):
-        v = O.normalize(g[m].cpu().numpy(), rh, norm, cfg.quot_eps)
-        assert O.scale_of(v) == scales[m], f"scale of worker {m}"
+        v = O.normalize(g[m].cpu().numpy(), rh, norm, cfg.quot_eps, None, None if means is None else means[m])
+        assert O.scale_of(v, scale) == scales[m], f"scale of worker {m}"
         del v
     rng = np.random.default_rng(bits * 10 + norm)
     win = 4096
@@ -52,13 +62,13 @@ def test_full_size_windows(full_inputs, bits, norm):
         rw = rh[s:s + win]
         words = np.zeros((M, win // per), dtype=np.uint32)
         for m in range(M):
-            v = O.normalize(gw[m], rw, norm, cfg.quot_eps)
+            v = O.normalize(gw[m], rw, norm, cfg.quot_eps, None, None if means is None else means[m])
             u = O.uniform_from_word(O.quant_draw_words(cfg.seed, it, m, win, first=s))
             level, neg = O.quantize(v, scales[m], bits, u)
             words[m] = O.pack(level, neg, bits)
         got = u32(codes_dev[:, s // per:(s + win) // per])
         assert np.array_equal(got, words), f"codes in window at {s}"
-        vb = O.decode_aggregate(cfg, words, scales, rw, win)
+        vb = O.decode_aggregate(cfg, words, scales, rw, win, None, means)
         assert np.array_equal(vbar_dev[s:s + win].cpu().numpy(), vb), f"decoded average in window at {s}"
     # properties that hold at any size: |decoded - mean(g)| is bounded by the mean grid step
     ctx.close()
