@@ -79,9 +79,14 @@ def time_codec(torch, B, g, gref, bits, norm, steps, warmup, seed, scale=0):
         ctx.decode_aggregate(codes, scales, gref, vbar)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    k_scale = sum(ev.elapsed_ms(5 * i + 0, 5 * i + 1) for i in range(steps)) / steps
-    k_quant = sum(ev.elapsed_ms(5 * i + 1, 5 * i + 2) for i in range(steps)) / steps
-    k_dec = sum(ev.elapsed_ms(5 * i + 3, 5 * i + 4) for i in range(steps)) / steps
+    t_scale = [ev.elapsed_ms(5 * i + 0, 5 * i + 1) for i in range(steps)]
+    t_quant = [ev.elapsed_ms(5 * i + 1, 5 * i + 2) for i in range(steps)]
+    t_dec = [ev.elapsed_ms(5 * i + 3, 5 * i + 4) for i in range(steps)]
+    k_scale, k_quant, k_dec = sum(t_scale) / steps, sum(t_quant) / steps, sum(t_dec) / steps
+
+    def spread(ts):
+        ts = sorted(ts)
+        return {"min": round(ts[0], 4), "median": round(ts[len(ts) // 2], 4)}
     ctx.set_profile_events(None, 0)
     ev.destroy()
     words = ctx.words
@@ -98,10 +103,12 @@ def time_codec(torch, B, g, gref, bits, norm, steps, warmup, seed, scale=0):
         "ms_per_step": ms,
         "fp32_in_GBps": 4.0 * M * d / (ms * 1e-3) / 1e9,
         "kernels": {
-            "absmax": {"ms": k_scale, "bytes": b_scale, "GBps": b_scale / (k_scale * 1e-3) / 1e9},
-            "quantize_pack": {"ms": k_quant, "bytes": b_quant, "GBps": b_quant / (k_quant * 1e-3) / 1e9},
-            "decode": {"ms": k_dec, "bytes": b_dec, "GBps": b_dec / (k_dec * 1e-3) / 1e9},
+            "absmax": {"ms": k_scale, "bytes": b_scale, "GBps": b_scale / (k_scale * 1e-3) / 1e9, **spread(t_scale)},
+            "quantize_pack": {"ms": k_quant, "bytes": b_quant, "GBps": b_quant / (k_quant * 1e-3) / 1e9,
+                              **spread(t_quant)},
+            "decode": {"ms": k_dec, "bytes": b_dec, "GBps": b_dec / (k_dec * 1e-3) / 1e9, **spread(t_dec)},
         },
+        "bits_per_element": (32.0 * words * M + 32.0 * M * (2 if norm == B.NORM_MEAN else 1)) / (M * d),
         "two_pass_bytes": b_scale + b_quant + b_dec,
         "two_pass_GBps": (b_scale + b_quant + b_dec) / (ms * 1e-3) / 1e9,
     }
@@ -307,6 +314,20 @@ def main():
         ctx.close()
         log(f"copy calibration: 3 launches of the plain copy kernel, {4 * d} bytes read and written each")
 
+    # practical ceiling: the library's plain float4 copy kernel on the same buffers (reads 4d, writes 4d bytes)
+    ctx = B.Context(d=d, M=M, bits=2, norm=B.NORM_SUB, ref_policy=B.REF_LAST_AVG, ref_period=1, device=dev)
+    dst = torch.empty(d, device=dev)
+    for _ in range(3):
+        ctx.update_reference(0, gref, dst)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        ctx.update_reference(0, gref, dst)
+    torch.cuda.synchronize()
+    copy_gbps = 8.0 * d * 20 / (time.perf_counter() - t0) / 1e9
+    ctx.close()
+    del dst
+
     cpu = None
     if not args.no_cpu:
         log("timing the oracle on the host")
@@ -341,6 +362,10 @@ def main():
         "two_pass_algorithmic_GBps": round(head["two_pass_GBps"], 1),
         "kernel_ms": {k: round(v["ms"], 4) for k, v in head["kernels"].items()},
         "kernel_GBps": {k: round(v["GBps"], 1) for k, v in head["kernels"].items()},
+        "kernel_ms_min_median": {k: [v["min"], v["median"]] for k, v in head["kernels"].items()},
+        "bits_per_element_on_the_wire": round(head["bits_per_element"], 6),
+        "copy_kernel_GBps": round(copy_gbps, 1),
+        "pct_of_copy_kernel_two_pass": round(100.0 * head["two_pass_GBps"] / copy_gbps, 2),
         "variants": variants,
         "iterations": iteration_results,
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(dom["GBps"], 1), "peak": HBM_PEAK_GBPS,
