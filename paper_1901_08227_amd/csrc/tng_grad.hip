@@ -383,6 +383,105 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int32_t* const
   }
 }
 
+// The same pass with two adjacent tiles of w (2^15 columns, 128 KiB) in LDS and two loads per lane and
+// row: the row segments are twice as long, so fewer of the 128-byte memory lines they touch are
+// partial ones.  (Random contiguous segments deliver 2.2 TB/s of useful bytes at 64 bytes per
+// segment and 3.2 TB/s at 128; this pass is bound by exactly that.)  One partial sum per row and pair
+// of tiles: zparts[m][pair][i].
+__global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* const* __restrict__ cols,
+                                                                 const float* const* __restrict__ vals,
+                                                                 const int64_t* __restrict__ rowbase,
+                                                                 const uint32_t* __restrict__ bounds,
+                                                                 const float* __restrict__ w,
+                                                                 float* __restrict__ zparts, uint64_t d,
+                                                                 uint32_t batch, uint32_t ntiles, uint32_t npairs) {
+  extern __shared__ float wtile[];  // w over the columns of both tiles
+  __shared__ int64_t sLo[kCsrRows];
+  __shared__ uint32_t sLen[kCsrRows];
+  const uint32_t m = blockIdx.x, pair = blockIdx.y;
+  const uint32_t t_lo = 2 * pair, t_hi = min(2 * pair + 2, ntiles);
+  constexpr uint32_t T = 2u << kCsrTileShift;
+  const uint64_t c0 = (uint64_t)t_lo << kCsrTileShift;
+  float* __restrict__ zpart = zparts + ((uint64_t)m * npairs + pair) * batch;
+  if (c0 + T <= d && (reinterpret_cast<uintptr_t>(w) & 15u) == 0) {
+    constexpr int kVec = (int)(T / (4 * kCsrThreads));  // 8 float4 per thread, four in flight at a time
+    const float4* __restrict__ w4 = reinterpret_cast<const float4*>(w + c0);
+    float4* tile4 = reinterpret_cast<float4*>(wtile);
+#pragma unroll
+    for (int q0 = 0; q0 < kVec; q0 += 4) {
+      float4 tmp[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) tmp[q] = w4[(q0 + q) * kCsrThreads + threadIdx.x];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) tile4[(q0 + q) * kCsrThreads + threadIdx.x] = tmp[q];
+    }
+  } else {
+    for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) wtile[j] = c0 + j < d ? w[c0 + j] : 0.f;
+  }
+  const GlobalPtr<int32_t> c = as_global(cols[m]);
+  const GlobalPtr<float> v = as_global(vals[m]);
+  const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
+  const uint32_t j0 = group * kCsrUnroll;
+  for (uint32_t first = 0; first < batch; first += kCsrRows) {
+    const uint32_t count = min((uint32_t)kCsrRows, batch - first);
+    __syncthreads();
+    {
+      const uint32_t* __restrict__ b = bounds + (uint64_t)m * (ntiles + 1) * batch + first;
+      const int64_t* __restrict__ base = rowbase + (uint64_t)m * batch + first;
+      for (uint32_t j = threadIdx.x; j < count; j += kCsrThreads) {
+        const uint32_t lo = b[(uint64_t)t_lo * batch + j], hi = b[(uint64_t)t_hi * batch + j];
+        sLo[j] = base[j] + lo;
+        sLen[j] = hi - lo;
+      }
+    }
+    __syncthreads();
+    uint32_t len[kCsrUnroll];
+    int32_t col[kCsrUnroll][2];
+    float val[kCsrUnroll][2];
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u) {  // all loads are issued before any is used
+      const uint32_t j = j0 + u;
+      len[u] = j < count ? sLen[j] : 0u;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        col[u][q] = 0;
+        val[u][q] = 0.f;
+        if (gl + (uint32_t)q * kCsrLanes < len[u]) {
+          const int64_t pos = sLo[j] + gl + q * kCsrLanes;
+          col[u][q] = c[pos];
+          val[u][q] = v[pos];
+        }
+      }
+    }
+    float acc[kCsrUnroll];
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u) {
+      acc[u] = gl < len[u] ? val[u][0] * wtile[(uint32_t)col[u][0] - (uint32_t)c0] : 0.f;
+      if (gl + kCsrLanes < len[u]) acc[u] = __builtin_fmaf(val[u][1], wtile[(uint32_t)col[u][1] - (uint32_t)c0], acc[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u) {
+      if (len[u] > 2u * kCsrLanes) {  // rare: longer than what the registers hold
+        const int64_t lo = sLo[j0 + u];
+        for (uint32_t k = gl + 2 * kCsrLanes; k < len[u]; k += kCsrLanes)
+          acc[u] = __builtin_fmaf(v[lo + k], wtile[(uint32_t)c[lo + k] - (uint32_t)c0], acc[u]);
+      }
+    }
+    float r8[8], r4[4], r2[2];
+    const bool b4 = (gl & 16) != 0, b3 = (gl & 8) != 0, b2 = (gl & 4) != 0, b1 = (gl & 2) != 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) r8[k] = (b4 ? acc[k + 8] : acc[k]) + __shfl_xor(b4 ? acc[k] : acc[k + 8], 16, kWave);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r4[k] = (b3 ? r8[k + 4] : r8[k]) + __shfl_xor(b3 ? r8[k] : r8[k + 4], 8, kWave);
+#pragma unroll
+    for (int k = 0; k < 2; ++k) r2[k] = (b2 ? r4[k + 2] : r4[k]) + __shfl_xor(b2 ? r4[k] : r4[k + 2], 4, kWave);
+    float r1 = (b1 ? r2[1] : r2[0]) + __shfl_xor(b1 ? r2[0] : r2[1], 2, kWave);
+    r1 += __shfl_xor(r1, 1, kWave);
+    const uint32_t u = (b4 ? 8u : 0u) + (b3 ? 4u : 0u) + (b2 ? 2u : 0u) + (b1 ? 1u : 0u);
+    if ((gl & 1u) == 0u && j0 + u < count) zpart[first + j0 + u] = r1;
+  }
+}
+
 // r[m][i] = (sigma(z_i) - y_i) / B with z_i = sum over the tiles of the partial dot products
 // zpart[m][t][i]: what the gradient pass multiplies every stored entry of row i by.
 __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __restrict__ zpart,
@@ -644,6 +743,10 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
                                              hipFuncAttributeMaxDynamicSharedMemorySize,
                                              (int)(sizeof(double) << kCsrTileShift));
     if (e != hipSuccess) return e;
+    const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_z_wide_kernel),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                                              (int)(2 * sizeof(float) << kCsrTileShift));
+    if (e2 != hipSuccess) return e2;
     attr_set = true;
   }
   if (p.tile_index != nullptr) {
@@ -654,10 +757,17 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
     hipLaunchKernelGGL(csr_bounds_kernel, dim3(batch, M), dim3(kBlock), 0, s, p.rowptr, p.col, idx, rowbase, bounds,
                        batch, ntiles, shift);
   }
-  hipLaunchKernelGGL(csr_z_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_w, s, p.col, p.val, rowbase, bounds, w,
-                     zpart, d, batch, ntiles, shift);
+  uint32_t nparts = ntiles;  // partial dot products per row
+  if (shift == kCsrTileShift && ntiles >= 2) {
+    nparts = (ntiles + 1) / 2;
+    hipLaunchKernelGGL(csr_z_wide_kernel, dim3(M, nparts), dim3(kCsrThreads), 2 * lds_w, s, p.col, p.val, rowbase, bounds,
+                       w, zpart, d, batch, ntiles, nparts);
+  } else {
+    hipLaunchKernelGGL(csr_z_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_w, s, p.col, p.val, rowbase, bounds, w,
+                       zpart, d, batch, ntiles, shift);
+  }
   hipLaunchKernelGGL(csr_z_reduce_kernel, dim3((batch + kBlock - 1) / kBlock, M), dim3(kBlock), 0, s, zpart, p.y, idx,
-                     z, batch, ntiles, inv_b);
+                     z, batch, nparts, inv_b);
   // The scale pass is not fused here: this kernel runs one workgroup per compute unit with its phases
   // back to back, and the extra reference loads and reduction in its epilogue cost more (+0.8 ms at
   // d = 2^24, M = 64) than the separate scale pass they would replace (0.7 ms).
