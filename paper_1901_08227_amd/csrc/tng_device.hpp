@@ -54,6 +54,12 @@ __device__ __forceinline__ float4 load4(GlobalPtr<float> p, uint64_t i) {
   return make_float4(v.x, v.y, v.z, v.w);
 }
 
+// The same as a streaming (non-temporal) load: shard rows are touched once per pass.
+__device__ __forceinline__ float4 load4_stream(GlobalPtr<float> p, uint64_t i) {
+  const v4f_t v = __builtin_nontemporal_load(reinterpret_cast<GlobalPtr<v4f_t>>(p) + i);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // Store of a packed word that is not read again by the same kernel.  A small write stream next to a
 // large read stream costs far more HBM time than its bytes; stores marked device-coherent (the sc1
 // cache-policy bit, which is what a relaxed device-scope atomic store compiles to) measured a

@@ -94,9 +94,9 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_resid_kernel(const float*
     const float4* w4 = reinterpret_cast<const float4*>(w);
     const uint64_t nvec = d / 4;
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-#pragma unroll 4
+#pragma unroll 8
     for (uint64_t k = threadIdx.x; k < nvec; k += kBlock) {
-      const float4 xv = load4(x, k), wv = w4[k];
+      const float4 xv = load4_stream(x, k), wv = w4[k];
       a0 = __builtin_fmaf(xv.x, wv.x, a0);
       a1 = __builtin_fmaf(xv.y, wv.y, a1);
       a2 = __builtin_fmaf(xv.z, wv.z, a2);
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
       if (VEC) {
 #pragma unroll 8
         for (uint32_t i = 0; i < cnt; ++i) {
-          const float4 xv = load4(X + (uint64_t)sRow[i] * d, col);
+          const float4 xv = load4_stream(X + (uint64_t)sRow[i] * d, col);
           const float r = sR[i];
           acc.x = __builtin_fmaf(r, xv.x, acc.x);
           acc.y = __builtin_fmaf(r, xv.y, acc.y);
