@@ -156,13 +156,15 @@ tng_status encode_impl(tng_ctx* ctx, uint32_t iter, const float* g, const float*
   } else if (ctx->cfg.scale == TNG_SCALE_L2) {
     e = tng::launch_l2_scales(ctx->shape, g, gref, ctx->gref2, ctx->sums, scales, ctx->stream);
   } else if (fused_rows > 0) {
-    e = tng::launch_absmax_finish(ctx->partials, fused_rows, ctx->cfg.M, scales, ctx->stream);
+    // the reduction of the fused partial maxima is left to the quantise launch
   } else {
     e = tng::launch_absmax(ctx->shape, g, gref, ctx->gref2, ctx->partials, scales, ctx->stream);
   }
   if (e != hipSuccess) return TNG_ERR_HIP;
   mark(ctx, call, 1);
-  e = tng::launch_quantize_pack(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, ctx->stream);
+  const bool fused = fused_rows > 0 && !mean_ref && ctx->cfg.scale == TNG_SCALE_MAX;
+  e = tng::launch_quantize_pack(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, ctx->partials,
+                                fused ? fused_rows : 0u, ctx->stream);
   mark(ctx, call, 2);
   return hip_status(e);
 }
@@ -200,10 +202,8 @@ tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g
     case TNG_PROB_LOGREG_DENSE: {
       if (!ctx->have_dense) return TNG_ERR_BAD_STATE;
       const tng::LogregData p = logreg_tables(ctx);
-      e = tng::launch_minibatch_indices(k0, k1, iter, c.M, c.batch, p.n_rows, ctx->idx, ctx->stream);
-      if (e != hipSuccess) return TNG_ERR_HIP;
-      e = tng::launch_logreg_dense_grad(p, c.d, c.M, c.batch, c.l2, ctx->idx, ctx->resid, w, g, fuse, fused_rows,
-                                        ctx->stream);
+      e = tng::launch_logreg_dense_grad(p, c.d, c.M, c.batch, c.l2, k0, k1, iter, ctx->idx, ctx->resid, w, g, fuse,
+                                        fused_rows, ctx->stream);
       return hip_status(e);
     }
     case TNG_PROB_LOGREG_CSR: {

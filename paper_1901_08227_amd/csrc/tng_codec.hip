@@ -19,6 +19,7 @@ namespace tng {
 namespace {
 
 constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr uint32_t kFusedScaleRows = 8;  // at most this many rows of partial maxima are reduced by the quantiser itself
 constexpr int kLoadsPerLane = 4;  // float4 loads per lane and worker in the quantiser tile
 constexpr uint32_t kMaxGridX = 1u << 20;
 
@@ -354,12 +355,30 @@ __device__ __forceinline__ void store_packed(FragmentBuffer<WPW>& lds, int wave,
 // Worker loop of one wavefront tile, software pipelined two workers per trip so that the two
 // register sets swap roles without copies: the loads of worker m+1 are in flight while the codes
 // of worker m are computed.
-template <int NORM, int BITS, int WPW, bool FULL>
+// Small problems: the scale pass was fused into the gradient kernel and left only a few rows of
+// per-workgroup maxima (partials[row][m]); the quantiser then takes their maximum itself instead of
+// waiting for a reduction kernel of its own, and the first workgroup publishes scales[m].
+struct FusedScale {
+  const float* partials;
+  uint32_t rows;
+  float* out;
+};
+
+__device__ __forceinline__ float fused_scale(const FusedScale& f, uint32_t m, uint32_t M, bool publish) {
+  float v = 0.f;
+  for (uint32_t b = 0; b < f.rows; ++b) v = fmaxf(v, f.partials[(uint64_t)b * M + m]);
+  v = v < FLT_MIN ? 0.f : v;
+  if (publish) f.out[m] = v;
+  return v;
+}
+
+template <int NORM, int BITS, int WPW, bool FULL, bool FUSED>
 __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, FragmentBuffer<WPW>& lds, int wave, int lane,
                                               const float4* __restrict__ g4, const float* __restrict__ scales,
                                               uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words,
                                               uint64_t word_base, uint32_t m0, uint32_t m_end, uint32_t iter,
-                                              uint32_t k0, uint32_t k1, const float* __restrict__ means) {
+                                              uint32_t k0, uint32_t k1, const float* __restrict__ means,
+                                              const FusedScale& fs, uint32_t M) {
   constexpr int L = kLoadsPerLane;
   float4 xa[L], xb[L];
   uint32_t frag[L];
@@ -367,19 +386,22 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
   // during the previous worker's arithmetic: loads return in order, so a scalar fetched after them
   // would make the wait for it a wait for the whole prefetch.
   auto mean_of = [&](uint32_t m) { return NORM == kNormMean ? means[m] : 0.f; };
-  float ra = scales[m0], mua = mean_of(m0), rb = 0.f, mub = 0.f;
+  auto scale_of = [&](uint32_t m) {
+    return FUSED ? fused_scale(fs, m, M, blockIdx.x == 0 && threadIdx.x == 0) : scales[m];
+  };
+  float ra = scale_of(m0), mua = mean_of(m0), rb = 0.f, mub = 0.f;
   load_worker_tile<NORM, FULL>(q, g4, nvec, m0, xa);
   // Steady state: both prefetches of a trip are unconditional.  A load issued under a condition
   // makes the compiler wait for all outstanding loads where the paths join (it cannot count what
   // is in flight), which would drain the prefetch before the arithmetic it is meant to overlap.
   uint32_t m = m0;
   for (; m + 2 < m_end; m += 2) {
-    rb = scales[m + 1];
+    rb = scale_of(m + 1);
     mub = mean_of(m + 1);
     load_worker_tile<NORM, FULL>(q, g4, nvec, m + 1, xb);
     quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
     store_packed<BITS, WPW>(lds, wave, lane, frag, codes + (uint64_t)m * words, word_base, words);
-    ra = scales[m + 2];
+    ra = scale_of(m + 2);
     mua = mean_of(m + 2);
     load_worker_tile<NORM, FULL>(q, g4, nvec, m + 2, xa);
     quantize_worker_tile<NORM, BITS, FULL>(q, xb, rb, mub, m + 1, iter, k0, k1, frag);
@@ -387,7 +409,7 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
   }
   // one or two workers are left, the first of them already in xa
   if (m + 1 < m_end) {
-    rb = scales[m + 1];
+    rb = scale_of(m + 1);
     mub = mean_of(m + 1);
     load_worker_tile<NORM, FULL>(q, g4, nvec, m + 1, xb);
     quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
@@ -400,11 +422,12 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
   }
 }
 
-template <int NORM, int BITS, int MC>
+template <int NORM, int BITS, int MC, bool FUSED>
 __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
     const float4* __restrict__ g4, const float4* __restrict__ ref4, const float4* __restrict__ ref24,
     const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words,
-    uint32_t M, float eps, uint32_t k0, uint32_t k1, uint32_t iter, const float* __restrict__ means) {
+    uint32_t M, float eps, uint32_t k0, uint32_t k1, uint32_t iter, const float* __restrict__ means,
+    FusedScale fs) {
   constexpr int L = kLoadsPerLane;
   constexpr int WPW = kWave * L * 4 * BITS / 32;  // packed words per wavefront tile
   __shared__ FragmentBuffer<WPW> lds;
@@ -423,11 +446,11 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
   const uint32_t m0 = blockIdx.y * MC;
   const uint32_t m_end = min(m0 + MC, M);
   if ((wave_tile + 1) * (kWave * L) <= nvec) {  // wave-uniform
-    quantize_rows<NORM, BITS, WPW, true>(q, lds, wave, lane, g4, scales, codes, nvec, words, word_base, m0, m_end,
-                                         iter, k0, k1, means);
+    quantize_rows<NORM, BITS, WPW, true, FUSED>(q, lds, wave, lane, g4, scales, codes, nvec, words, word_base, m0,
+                                                m_end, iter, k0, k1, means, fs, M);
   } else {
-    quantize_rows<NORM, BITS, WPW, false>(q, lds, wave, lane, g4, scales, codes, nvec, words, word_base, m0, m_end,
-                                          iter, k0, k1, means);
+    quantize_rows<NORM, BITS, WPW, false, FUSED>(q, lds, wave, lane, g4, scales, codes, nvec, words, word_base, m0,
+                                                 m_end, iter, k0, k1, means, fs, M);
   }
 }
 
@@ -436,11 +459,11 @@ template <int NORM, int BITS>
 __global__ __launch_bounds__(kBlock) void quantize_pack_scalar_kernel(
     const float* __restrict__ g, const float* __restrict__ ref, const float* __restrict__ ref2,
     const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t d, uint64_t words, uint32_t M,
-    float eps, uint32_t k0, uint32_t k1, uint32_t iter, const float* __restrict__ means) {
+    float eps, uint32_t k0, uint32_t k1, uint32_t iter, const float* __restrict__ means, FusedScale fs) {
   constexpr int PER = 32 / BITS;
   const uint32_t m = blockIdx.y;
   const float mu = NORM == kNormMean ? means[m] : 0.f;
-  const float R = scales[m];
+  const float R = fs.rows != 0 ? fused_scale(fs, m, M, blockIdx.x == 0 && threadIdx.x == 0) : scales[m];
   const float inv_r = R != 0.f ? 1.0f / R : 0.f;
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
   for (uint64_t wi = (uint64_t)blockIdx.x * kBlock + threadIdx.x; wi < words; wi += stride) {
@@ -865,36 +888,50 @@ hipError_t absmax_dispatch(const CodecShape& c, const float* g, const float* gre
   return hipGetLastError();
 }
 
-template <int NORM, int BITS, int MC>
+template <int NORM, int BITS, int MC, bool FUSED>
 hipError_t quantize_vec_launch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
-                               const float* gref2, const float* scales, uint32_t* codes, hipStream_t s) {
+                               const float* gref2, const float* scales, uint32_t* codes, const FusedScale& fs,
+                               hipStream_t s) {
   const uint64_t nvec = c.d / 4;
   const uint64_t tiles = (nvec + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
   dim3 grid((uint32_t)tiles, (c.M + MC - 1) / MC);
-  hipLaunchKernelGGL((quantize_pack_vec_kernel<NORM, BITS, MC>), grid, dim3(kBlock), 0, s,
+  hipLaunchKernelGGL((quantize_pack_vec_kernel<NORM, BITS, MC, FUSED>), grid, dim3(kBlock), 0, s,
                      reinterpret_cast<const float4*>(g), reinterpret_cast<const float4*>(gref),
                      reinterpret_cast<const float4*>(gref2), scales, codes, nvec, c.words, c.M, c.eps, c.k0,
-                     c.k1, iter, c.means);
+                     c.k1, iter, c.means, fs);
   return hipGetLastError();
 }
 
+// fused_rows > 0: scales is an output and the scale is taken from the first fused_rows rows of
+// partials (see FusedScale); only problems small enough for one worker per workgroup go that way,
+// larger ones get the reduction kernel first.
 template <int NORM, int BITS>
 hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
-                             const float* gref2, const float* scales, uint32_t* codes, hipStream_t s) {
-  if (vec_ok(c.d, g, gref, gref2)) {
-    const uint64_t tiles = (c.d / 4 + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
-    const int mc = pick_workers_per_block(c.M, tiles);
+                             const float* gref2, float* scales, uint32_t* codes, const float* partials,
+                             uint32_t fused_rows, hipStream_t s) {
+  const bool vec = vec_ok(c.d, g, gref, gref2);
+  const uint64_t tiles = (c.d / 4 + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
+  const int mc = vec ? pick_workers_per_block(c.M, tiles) : 1;
+  FusedScale fs{partials, fused_rows, scales};
+  if (fused_rows > kFusedScaleRows || (fused_rows > 0 && mc != 1)) {
+    hipLaunchKernelGGL(absmax_finish_kernel, dim3(c.M), dim3(kBlock), 0, s, partials, fused_rows, c.M, scales);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    fs.rows = 0;
+  }
+  if (vec) {
+    if (fs.rows > 0) return quantize_vec_launch<NORM, BITS, 1, true>(c, iter, g, gref, gref2, scales, codes, fs, s);
     switch (mc) {
-      case 8: return quantize_vec_launch<NORM, BITS, 8>(c, iter, g, gref, gref2, scales, codes, s);
-      case 4: return quantize_vec_launch<NORM, BITS, 4>(c, iter, g, gref, gref2, scales, codes, s);
-      case 2: return quantize_vec_launch<NORM, BITS, 2>(c, iter, g, gref, gref2, scales, codes, s);
-      default: return quantize_vec_launch<NORM, BITS, 1>(c, iter, g, gref, gref2, scales, codes, s);
+      case 8: return quantize_vec_launch<NORM, BITS, 8, false>(c, iter, g, gref, gref2, scales, codes, fs, s);
+      case 4: return quantize_vec_launch<NORM, BITS, 4, false>(c, iter, g, gref, gref2, scales, codes, fs, s);
+      case 2: return quantize_vec_launch<NORM, BITS, 2, false>(c, iter, g, gref, gref2, scales, codes, fs, s);
+      default: return quantize_vec_launch<NORM, BITS, 1, false>(c, iter, g, gref, gref2, scales, codes, fs, s);
     }
   }
   const uint32_t per_y = div_up_u32(c.words, kBlock);
   dim3 grid(per_y < 65536u ? per_y : 65536u, c.M);
   hipLaunchKernelGGL((quantize_pack_scalar_kernel<NORM, BITS>), grid, dim3(kBlock), 0, s, g, gref, gref2,
-                     scales, codes, c.d, c.words, c.M, c.eps, c.k0, c.k1, iter, c.means);
+                     scales, codes, c.d, c.words, c.M, c.eps, c.k0, c.k1, iter, c.means, fs);
   return hipGetLastError();
 }
 
@@ -1041,10 +1078,11 @@ hipError_t launch_l2_scales(const CodecShape& c, const float* g, const float* gr
 }
 
 hipError_t launch_quantize_pack(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
-                                const float* gref2, const float* scales, uint32_t* codes, hipStream_t s) {
-#define TNG_Q(NORM, R1, R2)                                                                    \
-  return c.bits == 2 ? quantize_dispatch<NORM, 2>(c, iter, g, R1, R2, scales, codes, s)        \
-                     : quantize_dispatch<NORM, 4>(c, iter, g, R1, R2, scales, codes, s)
+                                const float* gref2, float* scales, uint32_t* codes, const float* partials,
+                                uint32_t fused_rows, hipStream_t s) {
+#define TNG_Q(NORM, R1, R2)                                                                                      \
+  return c.bits == 2 ? quantize_dispatch<NORM, 2>(c, iter, g, R1, R2, scales, codes, partials, fused_rows, s)    \
+                     : quantize_dispatch<NORM, 4>(c, iter, g, R1, R2, scales, codes, partials, fused_rows, s)
   switch (c.norm) {
     case kNormNone: TNG_Q(kNormNone, nullptr, nullptr);
     case kNormSub: TNG_Q(kNormSub, gref, nullptr);

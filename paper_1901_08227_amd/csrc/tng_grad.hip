@@ -16,6 +16,14 @@ namespace {
 constexpr int kWavesPerBlock = kBlock / kWave;
 
 // Background: index "uniformly sampled" -- idx = (draw * n_rows) >> 32, draws from stream 1.
+__device__ __forceinline__ uint32_t minibatch_row(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t m, uint32_t j,
+                                                  uint64_t n_rows) {
+  const U32x4 r = philox4x32_10(j >> 2, m, iter, 1u, k0, k1);
+  const uint32_t lane = j & 3u;
+  const uint32_t x = lane == 0 ? r.x : lane == 1 ? r.y : lane == 2 ? r.z : r.w;
+  return (uint32_t)(((uint64_t)x * n_rows) >> 32);
+}
+
 __global__ __launch_bounds__(kBlock) void minibatch_indices_kernel(uint32_t k0, uint32_t k1, uint32_t iter,
                                                                    uint32_t batch,
                                                                    const uint64_t* __restrict__ n_rows,
@@ -23,10 +31,7 @@ __global__ __launch_bounds__(kBlock) void minibatch_indices_kernel(uint32_t k0, 
   const uint32_t m = blockIdx.y;
   const uint32_t j = blockIdx.x * kBlock + threadIdx.x;
   if (j >= batch) return;
-  const U32x4 r = philox4x32_10(j >> 2, m, iter, 1u, k0, k1);
-  const uint32_t lane = j & 3u;
-  const uint32_t x = lane == 0 ? r.x : lane == 1 ? r.y : lane == 2 ? r.z : r.w;
-  idx[(uint64_t)m * batch + j] = (uint32_t)(((uint64_t)x * n_rows[m]) >> 32);
+  idx[(uint64_t)m * batch + j] = minibatch_row(k0, k1, iter, m, j, n_rows[m]);
 }
 
 __device__ __forceinline__ float block_sum(float v, float* red) {
@@ -81,13 +86,17 @@ __device__ __forceinline__ float logistic_residual(float z, float y) {
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void logreg_dense_resid_kernel(const float* const* __restrict__ Xs,
                                                                     const float* const* __restrict__ ys,
-                                                                    const uint32_t* __restrict__ idx,
+                                                                    const uint64_t* __restrict__ n_rows,
+                                                                    uint32_t* __restrict__ idx,
                                                                     const float* __restrict__ w,
                                                                     float* __restrict__ resid, uint64_t d,
-                                                                    uint32_t batch) {
+                                                                    uint32_t batch, uint32_t k0, uint32_t k1,
+                                                                    uint32_t iter) {
   __shared__ float red[kWavesPerBlock];
   const uint32_t m = blockIdx.y, i = blockIdx.x;
-  const uint32_t row = idx[(uint64_t)m * batch + i];
+  // the row id is drawn here (one launch fewer) and left in idx for the accumulation pass
+  const uint32_t row = minibatch_row(k0, k1, iter, m, i, n_rows[m]);
+  if (threadIdx.x == 0) idx[(uint64_t)m * batch + i] = row;
   const GlobalPtr<float> x = as_global(Xs[m]) + (uint64_t)row * d;
   float acc = 0.f;
   if (VEC) {
@@ -680,16 +689,17 @@ hipError_t launch_minibatch_indices(uint32_t k0, uint32_t k1, uint32_t iter, uin
 }
 
 hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
-                                    const uint32_t* idx, float* resid, const float* w, float* g,
-                                    const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s) {
+                                    uint32_t k0, uint32_t k1, uint32_t iter, uint32_t* idx, float* resid,
+                                    const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
+                                    hipStream_t s) {
   if (fused_rows != nullptr) *fused_rows = 0;
   // Shards are required to be 16-byte aligned; rows stay aligned only when d is a multiple of 4.
   const bool vec = d % 4 == 0 && aligned16(w) && aligned16(g);
   const float inv_b = 1.0f / (float)batch;
   dim3 grid_r(batch, M);
   if (vec) {
-    hipLaunchKernelGGL((logreg_dense_resid_kernel<true>), grid_r, dim3(kBlock), 0, s, p.X, p.y, idx, w, resid, d,
-                       batch);
+    hipLaunchKernelGGL((logreg_dense_resid_kernel<true>), grid_r, dim3(kBlock), 0, s, p.X, p.y, p.n_rows, idx, w, resid,
+                       d, batch, k0, k1, iter);
     dim3 grid_g((uint32_t)((d / 4 + kBlock - 1) / kBlock), M);
     if (fuse != nullptr && fused_rows != nullptr && grid_g.x <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
         aligned16(fuse->gref2)) {
@@ -701,8 +711,8 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
                          batch, inv_b, l2, ScaleFusion{});
     }
   } else {
-    hipLaunchKernelGGL((logreg_dense_resid_kernel<false>), grid_r, dim3(kBlock), 0, s, p.X, p.y, idx, w, resid,
-                       d, batch);
+    hipLaunchKernelGGL((logreg_dense_resid_kernel<false>), grid_r, dim3(kBlock), 0, s, p.X, p.y, p.n_rows, idx, w, resid,
+                       d, batch, k0, k1, iter);
     dim3 grid_g((uint32_t)((d + kBlock - 1) / kBlock), M);
     hipLaunchKernelGGL((logreg_dense_grad_kernel<false, false>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
                        batch, inv_b, l2, ScaleFusion{});

@@ -60,8 +60,12 @@ struct ScaleFusion {
   float* partials;
 };
 
+// fused_rows == 0: scales[m] is read.  fused_rows > 0: the scale pass was fused into a gradient kernel
+// that left fused_rows rows of partial maxima in partials; scales[m] is then written as well (by the
+// quantiser itself for small problems, by the reduction kernel otherwise).
 hipError_t launch_quantize_pack(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
-                                const float* gref2, const float* scales, uint32_t* codes, hipStream_t s);
+                                const float* gref2, float* scales, uint32_t* codes, const float* partials,
+                                uint32_t fused_rows, hipStream_t s);
 // vbar = denorm(mean_m decode).  If w != nullptr also w -= lr * vbar; if ref_out != nullptr also
 // ref_out = vbar (ref_out may alias gref).
 hipError_t launch_decode(const CodecShape& c, const uint32_t* codes, const float* scales,
@@ -80,9 +84,11 @@ struct LogregData {
 
 hipError_t launch_minibatch_indices(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t M, uint32_t batch,
                                     const uint64_t* n_rows, uint32_t* idx, hipStream_t s);
+// The minibatch row ids of iteration iter are drawn inside (Philox key k0, k1) and left in idx.
 hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
-                                    const uint32_t* idx, float* resid, const float* w, float* g,
-                                    const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s);
+                                    uint32_t k0, uint32_t k1, uint32_t iter, uint32_t* idx, float* resid,
+                                    const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
+                                    hipStream_t s);
 // Column tiles of the CSR gradient: 2^kCsrTileShift coordinates (128 KiB of fp64 in LDS).
 constexpr uint32_t kCsrTileShift = 14;
 uint32_t csr_tiles(uint64_t d);
