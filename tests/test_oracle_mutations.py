@@ -177,3 +177,36 @@ def test_planted_mistakes_in_gradients_and_updates_are_caught(monkeypatch):
     with monkeypatch.context() as mp:                            # ascent instead of descent
         mp.setattr(O, "update_iterate", lambda w, v, lr: np.asarray(w, dtype=F32) + F32(lr) * np.asarray(v, dtype=F32))
         assert _fails([(TS.test_iterate_update_is_plain_sgd_on_the_decoded_average, ())])
+
+
+def test_planted_mistakes_in_row_sums_mean_reference_and_noise_are_caught(monkeypatch):
+    import test_oracle_noise as TN
+    import test_oracle_sums as TSUM
+    with monkeypatch.context() as mp:                            # plain left-to-right float64 sum
+        mp.setattr(O, "tree_sum64", lambda x: np.float64(np.cumsum(np.asarray(x, dtype=np.float64))[-1])
+                   if np.size(x) else np.float64(0.0))
+        assert _fails([(TSUM.test_ordered_sum_is_a_sum_and_has_the_stated_order, ())])
+    with monkeypatch.context() as mp:                            # mean accumulated in float32
+        mp.setattr(O, "worker_mean", lambda g: F32(np.add.reduce(np.asarray(g, dtype=F32), dtype=F32) / F32(len(g))))
+        assert _fails([(TSUM.test_worker_mean_is_the_mean, ())])
+    with monkeypatch.context() as mp:                            # the server does not add the workers' means back
+        orig = O.decode_aggregate
+        mp.setattr(O, "decode_aggregate", lambda cfg, codes, scales, gref, d, gref2=None, means=None:
+                   orig(cfg, codes, scales, gref, d, gref2, None if means is None else np.zeros_like(means)))
+        assert _fails([(TSUM.test_mean_reference_round_trip_is_unbiased_and_matches_elementwise_oracle, (2,))])
+    with monkeypatch.context() as mp:                            # squared norm instead of the norm
+        orig = O.scale_of
+        mp.setattr(O, "scale_of", lambda v, kind=0: orig(v, kind) if kind == 0 else F32(float(orig(v, kind)) ** 2))
+        assert _fails([(TSUM.test_l2_scale, (2,))])
+    with monkeypatch.context() as mp:                            # Box-Muller radius without the factor 2
+        orig = O.gaussian_noise
+        mp.setattr(O, "gaussian_noise", lambda seed, it, m, d, variance: orig(seed, it, m, d, variance) / np.sqrt(2.0))
+        assert _fails([(TN.test_noise_is_normal_with_the_requested_variance, ())])
+    with monkeypatch.context() as mp:                            # cosine and sine branches swapped
+        orig = O.gaussian_noise
+
+        def swapped(seed, it, m, d, variance):
+            z = orig(seed, it, m, d + (d & 1), variance).reshape(-1, 2)[:, ::-1].reshape(-1)
+            return z[:d]
+        mp.setattr(O, "gaussian_noise", swapped)
+        assert _fails([(TN.test_element_to_draw_mapping_with_the_scalar_generator, ())])
