@@ -90,7 +90,7 @@ typedef enum {
 } tng_problem;
 
 typedef struct {
-  uint64_t d;          /* dimension of w, 1 <= d <= 2^34                                        */
+  uint64_t d;          /* dimension of w, 1 <= d <= 2^34 (CSR problem: d <= 65535 * 2^14)       */
   uint32_t M;          /* number of simulated workers, >= 1                                     */
   uint32_t bits;       /* 2: ternary {-1,0,1} x R; 4: sign + 3-bit level, 7 levels              */
   int32_t norm;        /* tng_norm                                                              */

@@ -55,6 +55,8 @@ bool config_valid(const tng_config* c) {
   if (c->problem < TNG_PROB_EXTERNAL || c->problem > TNG_PROB_ROSENBROCK) return false;
   const bool logreg = c->problem == TNG_PROB_LOGREG_DENSE || c->problem == TNG_PROB_LOGREG_CSR;
   if (logreg && c->batch == 0) return false;
+  // CSR columns are int32 and the column tiles of its kernels are one grid dimension (at most 65535)
+  if (c->problem == TNG_PROB_LOGREG_CSR && c->d > (65535ull << tng::kCsrTileShift)) return false;
   return true;
 }
 

@@ -46,10 +46,12 @@ def test_words_per_row():
 def test_workspace_size_and_config_validation():
     assert B.tng_workspace_bytes(_cfg()) >= 4 * 64 * 8
     assert B.tng_workspace_bytes(_cfg(problem=B.PROB_EXTERNAL, batch=0)) > 0
+    assert B.tng_workspace_bytes(_cfg(problem=B.PROB_LOGREG_CSR, d=65535 << 14, M=1, batch=1)) > 0
     bad = [dict(d=0), dict(M=0), dict(bits=3), dict(bits=8), dict(norm=7), dict(norm=5), dict(norm=-1), dict(scale=2), dict(scale=-1), dict(quot_eps=0.0),
            dict(quot_eps=float("nan")), dict(ref_policy=5), dict(ref_period=0), dict(lr=float("inf")),
            dict(l2=float("nan")), dict(batch=0), dict(problem=9), dict(d=(1 << 34) + 1), dict(M=70000),
-           dict(ref_policy=B.REF_WINDOW_AVG, ref_window=0)]
+           dict(ref_policy=B.REF_WINDOW_AVG, ref_window=0),
+           dict(problem=B.PROB_LOGREG_CSR, d=(65535 << 14) + 1)]
     for kw in bad:
         assert B.tng_workspace_bytes(_cfg(**kw)) == 0, kw
         h = ctypes.c_void_p()
