@@ -506,9 +506,14 @@ tng_status tng_step(tng_ctx* ctx, uint32_t iter, float* w, float* gref, float* g
   s = encode_impl(ctx, iter, g, gref, codes, scales, fused_rows);
   if (s != TNG_OK) return s;
   if (ctx->cfg.ref_policy == TNG_REF_WINDOW_AVG) {
-    s = decode_impl(ctx, codes, scales, gref, vbar, w, nullptr);
+    // the decode pass also leaves the decoded average in its slot of the history ring
+    const tng_config& c = ctx->cfg;
+    const uint32_t slot = iter % c.ref_window;
+    s = decode_impl(ctx, codes, scales, gref, vbar, w, ctx->history + (uint64_t)slot * c.d);
     if (s != TNG_OK) return s;
-    return update_reference_impl(ctx, iter, vbar, gref);
+    if (!refresh_now(c, iter)) return TNG_OK;
+    return hip_status(tng::launch_window_mean(ctx->history, c.ref_window, (slot + 1) % c.ref_window, c.d, gref,
+                                              ctx->stream));
   }
   float* ref_out = refresh_now(ctx->cfg, iter) ? gref : nullptr;  // last-average policy: fused into the decode pass
   return decode_impl(ctx, codes, scales, gref, vbar, w, ref_out);

@@ -37,7 +37,8 @@ __global__ __launch_bounds__(kBlock) void copy_f32_kernel(float* __restrict__ ds
 __global__ __launch_bounds__(kBlock) void copy_f32x4_kernel(float4* __restrict__ dst,
                                                             const float4* __restrict__ src, uint64_t n) {
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride)
+    store_stream(dst + i, load_stream(src + i));
 }
 
 // Window-average reference (section "Reference Vectors"): mean of the last `window` decoded
@@ -54,6 +55,26 @@ __global__ __launch_bounds__(kBlock) void window_mean_kernel(const float* __rest
       slot = slot + 1 == window ? 0u : slot + 1;
     }
     out[e] = acc * inv_window;
+  }
+}
+
+// The same, four coordinates per thread (d a multiple of 4, 16-byte aligned operands).
+__global__ __launch_bounds__(kBlock) void window_mean_vec_kernel(const float4* __restrict__ history, uint32_t window,
+                                                                 uint32_t first, uint64_t nvec, float inv_window,
+                                                                 float4* __restrict__ out) {
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x; q < nvec; q += stride) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    uint32_t slot = first;
+    for (uint32_t k = 0; k < window; ++k) {
+      const float4 h = load_stream(history + (uint64_t)slot * nvec + q);
+      acc.x = acc.x + h.x;
+      acc.y = acc.y + h.y;
+      acc.z = acc.z + h.z;
+      acc.w = acc.w + h.w;
+      slot = slot + 1 == window ? 0u : slot + 1;
+    }
+    store_stream(out + q, make_float4(acc.x * inv_window, acc.y * inv_window, acc.z * inv_window, acc.w * inv_window));
   }
 }
 
@@ -1036,9 +1057,16 @@ hipError_t launch_copy_f32(float* dst, const float* src, uint64_t n, hipStream_t
 
 hipError_t launch_window_mean(const float* history, uint32_t window, uint32_t first, uint64_t d, float* out,
                               hipStream_t s) {
-  const uint32_t gx = div_up_u32(d, kBlock);
-  hipLaunchKernelGGL(window_mean_kernel, dim3(gx < 16384u ? gx : 16384u), dim3(kBlock), 0, s, history, window, first,
-                     d, 1.0f / (float)window, out);
+  if (vec_ok(d, history, out, nullptr)) {
+    const uint32_t gx = div_up_u32(d / 4, kBlock);
+    hipLaunchKernelGGL(window_mean_vec_kernel, dim3(gx < 16384u ? gx : 16384u), dim3(kBlock), 0, s,
+                       reinterpret_cast<const float4*>(history), window, first, d / 4, 1.0f / (float)window,
+                       reinterpret_cast<float4*>(out));
+  } else {
+    const uint32_t gx = div_up_u32(d, kBlock);
+    hipLaunchKernelGGL(window_mean_kernel, dim3(gx < 16384u ? gx : 16384u), dim3(kBlock), 0, s, history, window, first,
+                       d, 1.0f / (float)window, out);
+  }
   return hipGetLastError();
 }
 
