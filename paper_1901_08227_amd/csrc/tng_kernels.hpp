@@ -93,7 +93,8 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
 constexpr uint32_t kCsrTileShift = 14;
 uint32_t csr_tiles(uint64_t d);
 // Device scratch: rowbase int64[M][batch]; bounds uint32[M][csr_tiles(d) + 1][batch];
-// zpart float[M][csr_tiles(d)][batch]; z float[M][batch].
+// zpart float[M][csr_tiles(d)][batch] (partial dot products per tile, or per pair of tiles in the
+// first half of it); z float[M][batch], which receives (sigma(z_i) - y_i) / batch.
 // Columns must be ascending within each row.
 // p.tile_index (optional): per worker uint32[n_rows][csr_tiles(d) + 1], entry [row][t] = offset within
 // the row of the first stored entry whose column is at or beyond the start of tile t; built once by
