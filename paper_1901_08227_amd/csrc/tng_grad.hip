@@ -82,8 +82,9 @@ __device__ __forceinline__ float logistic_residual(float z, float y) {
   return sig - y;
 }
 
-// z_i = x_i . w and r_i = sigma(z_i) - y_i for one minibatch row per workgroup.
-template <bool VEC>
+// z_i = x_i . w and r_i = sigma(z_i) - y_i for ROWS minibatch rows per workgroup (w is fetched once
+// for all of them; each row keeps the accumulation order it has with ROWS = 1).
+template <bool VEC, int ROWS>
 __global__ __launch_bounds__(kBlock) void logreg_dense_resid_kernel(const float* const* __restrict__ Xs,
                                                                     const float* const* __restrict__ ys,
                                                                     const uint64_t* __restrict__ n_rows,
@@ -93,30 +94,53 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_resid_kernel(const float*
                                                                     uint32_t batch, uint32_t k0, uint32_t k1,
                                                                     uint32_t iter) {
   __shared__ float red[kWavesPerBlock];
-  const uint32_t m = blockIdx.y, i = blockIdx.x;
-  // the row id is drawn here (one launch fewer) and left in idx for the accumulation pass
-  const uint32_t row = minibatch_row(k0, k1, iter, m, i, n_rows[m]);
-  if (threadIdx.x == 0) idx[(uint64_t)m * batch + i] = row;
-  const GlobalPtr<float> x = as_global(Xs[m]) + (uint64_t)row * d;
-  float acc = 0.f;
+  const uint32_t m = blockIdx.y, i0 = blockIdx.x * ROWS;
+  // the row ids are drawn here (one launch fewer) and left in idx for the accumulation pass
+  uint32_t row[ROWS];
+  GlobalPtr<float> x[ROWS];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    row[r] = minibatch_row(k0, k1, iter, m, min(i0 + r, batch - 1), n_rows[m]);  // a short last group repeats its last row
+    if (threadIdx.x == 0 && i0 + r < batch) idx[(uint64_t)m * batch + i0 + r] = row[r];
+    x[r] = as_global(Xs[m]) + (uint64_t)row[r] * d;
+  }
+  float acc[ROWS];
   if (VEC) {
     const float4* w4 = reinterpret_cast<const float4*>(w);
     const uint64_t nvec = d / 4;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-#pragma unroll 8
+    float a0[ROWS], a1[ROWS], a2[ROWS], a3[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) a0[r] = a1[r] = a2[r] = a3[r] = 0.f;
+#pragma unroll 8 / ROWS
     for (uint64_t k = threadIdx.x; k < nvec; k += kBlock) {
-      const float4 xv = load4_stream(x, k), wv = w4[k];
-      a0 = __builtin_fmaf(xv.x, wv.x, a0);
-      a1 = __builtin_fmaf(xv.y, wv.y, a1);
-      a2 = __builtin_fmaf(xv.z, wv.z, a2);
-      a3 = __builtin_fmaf(xv.w, wv.w, a3);
+      const float4 wv = w4[k];
+#pragma unroll
+      for (int r = 0; r < ROWS; ++r) {
+        const float4 xv = load4_stream(x[r], k);
+        a0[r] = __builtin_fmaf(xv.x, wv.x, a0[r]);
+        a1[r] = __builtin_fmaf(xv.y, wv.y, a1[r]);
+        a2[r] = __builtin_fmaf(xv.z, wv.z, a2[r]);
+        a3[r] = __builtin_fmaf(xv.w, wv.w, a3[r]);
+      }
     }
-    acc = (a0 + a1) + (a2 + a3);
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) acc[r] = (a0[r] + a1[r]) + (a2[r] + a3[r]);
   } else {
-    for (uint64_t k = threadIdx.x; k < d; k += kBlock) acc = __builtin_fmaf(x[k], w[k], acc);
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) acc[r] = 0.f;
+    for (uint64_t k = threadIdx.x; k < d; k += kBlock) {
+      const float wk = w[k];
+#pragma unroll
+      for (int r = 0; r < ROWS; ++r) acc[r] = __builtin_fmaf(x[r][k], wk, acc[r]);
+    }
   }
-  const float z = block_sum(acc, red);
-  if (threadIdx.x == 0) resid[(uint64_t)m * batch + i] = logistic_residual(z, as_global(ys[m])[row]);
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    if (r > 0) __syncthreads();  // red is reused
+    const float z = block_sum(acc[r], red);
+    if (threadIdx.x == 0 && i0 + r < batch)
+      resid[(uint64_t)m * batch + i0 + r] = logistic_residual(z, as_global(ys[m])[row[r]]);
+  }
 }
 
 // g_m[k] = (1/B) sum_i r_i X[idx_i][k] + l2 w[k]; a thread owns 4 (VEC) or 1 columns.
@@ -697,9 +721,14 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
   const bool vec = d % 4 == 0 && aligned16(w) && aligned16(g);
   const float inv_b = 1.0f / (float)batch;
   dim3 grid_r(batch, M);
-  if (vec) {
-    hipLaunchKernelGGL((logreg_dense_resid_kernel<true>), grid_r, dim3(kBlock), 0, s, p.X, p.y, p.n_rows, idx, w, resid,
+  if (vec && (uint64_t)M * (batch / 4) >= 1024) {  // enough rows to keep the chip busy four at a time
+    hipLaunchKernelGGL((logreg_dense_resid_kernel<true, 4>), dim3((batch + 3) / 4, M), dim3(kBlock), 0, s, p.X, p.y,
+                       p.n_rows, idx, w, resid, d, batch, k0, k1, iter);
+  } else if (vec) {
+    hipLaunchKernelGGL((logreg_dense_resid_kernel<true, 1>), grid_r, dim3(kBlock), 0, s, p.X, p.y, p.n_rows, idx, w, resid,
                        d, batch, k0, k1, iter);
+  }
+  if (vec) {
     dim3 grid_g((uint32_t)((d / 4 + kBlock - 1) / kBlock), M);
     if (fuse != nullptr && fused_rows != nullptr && grid_g.x <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
         aligned16(fuse->gref2)) {
@@ -711,8 +740,8 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
                          batch, inv_b, l2, ScaleFusion{});
     }
   } else {
-    hipLaunchKernelGGL((logreg_dense_resid_kernel<false>), grid_r, dim3(kBlock), 0, s, p.X, p.y, p.n_rows, idx, w, resid,
-                       d, batch, k0, k1, iter);
+    hipLaunchKernelGGL((logreg_dense_resid_kernel<false, 1>), grid_r, dim3(kBlock), 0, s, p.X, p.y, p.n_rows, idx, w,
+                       resid, d, batch, k0, k1, iter);
     dim3 grid_g((uint32_t)((d + kBlock - 1) / kBlock), M);
     hipLaunchKernelGGL((logreg_dense_grad_kernel<false, false>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
                        batch, inv_b, l2, ScaleFusion{});
