@@ -427,15 +427,15 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
                                                                  const uint32_t* __restrict__ bounds,
                                                                  const float* __restrict__ w,
                                                                  float* __restrict__ zparts, uint64_t d,
-                                                                 uint32_t batch, uint32_t ntiles, uint32_t npairs) {
+                                                                 uint32_t batch, uint32_t ntiles, uint32_t npairs,
+                                                                 uint32_t M, uint32_t workers_per_block) {
   extern __shared__ float wtile[];  // w over the columns of both tiles
   __shared__ int64_t sLo[kCsrRows];
   __shared__ uint32_t sLen[kCsrRows];
-  const uint32_t m = blockIdx.x, pair = blockIdx.y;
+  const uint32_t pair = blockIdx.y;
   const uint32_t t_lo = 2 * pair, t_hi = min(2 * pair + 2, ntiles);
   constexpr uint32_t T = 2u << kCsrTileShift;
   const uint64_t c0 = (uint64_t)t_lo << kCsrTileShift;
-  float* __restrict__ zpart = zparts + ((uint64_t)m * npairs + pair) * batch;
   if (c0 + T <= d && (reinterpret_cast<uintptr_t>(w) & 15u) == 0) {
     constexpr int kVec = (int)(T / (4 * kCsrThreads));  // 8 float4 per thread, four in flight at a time
     const float4* __restrict__ w4 = reinterpret_cast<const float4*>(w + c0);
@@ -451,10 +451,14 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
   } else {
     for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) wtile[j] = c0 + j < d ? w[c0 + j] : 0.f;
   }
-  const GlobalPtr<int32_t> c = as_global(cols[m]);
-  const GlobalPtr<float> v = as_global(vals[m]);
   const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
   const uint32_t j0 = group * kCsrUnroll;
+  // the tiles of w serve several workers in turn
+  const uint32_t m_first = blockIdx.x * workers_per_block, m_last = min(m_first + workers_per_block, M);
+  for (uint32_t m = m_first; m < m_last; ++m) {
+  float* __restrict__ zpart = zparts + ((uint64_t)m * npairs + pair) * batch;
+  const GlobalPtr<int32_t> c = as_global(cols[m]);
+  const GlobalPtr<float> v = as_global(vals[m]);
   for (uint32_t first = 0; first < batch; first += kCsrRows) {
     const uint32_t count = min((uint32_t)kCsrRows, batch - first);
     __syncthreads();
@@ -512,6 +516,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
     r1 += __shfl_xor(r1, 1, kWave);
     const uint32_t u = (b4 ? 8u : 0u) + (b3 ? 4u : 0u) + (b2 ? 2u : 0u) + (b1 ? 1u : 0u);
     if ((gl & 1u) == 0u && j0 + u < count) zpart[first + j0 + u] = r1;
+  }
   }
 }
 
@@ -799,8 +804,10 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
   uint32_t nparts = ntiles;  // partial dot products per row
   if (shift == kCsrTileShift && ntiles >= 2) {
     nparts = (ntiles + 1) / 2;
-    hipLaunchKernelGGL(csr_z_wide_kernel, dim3(M, nparts), dim3(kCsrThreads), 2 * lds_w, s, p.col, p.val, rowbase, bounds,
-                       w, zpart, d, batch, ntiles, nparts);
+    uint32_t wpb = 1;  // workers per workgroup while 2048 workgroups remain
+    while (wpb < 8 && wpb * 2 <= M && (uint64_t)nparts * (M / (wpb * 2)) >= 2048) wpb *= 2;
+    hipLaunchKernelGGL(csr_z_wide_kernel, dim3((M + wpb - 1) / wpb, nparts), dim3(kCsrThreads), 2 * lds_w, s, p.col, p.val,
+                       rowbase, bounds, w, zpart, d, batch, ntiles, nparts, M, wpb);
   } else {
     hipLaunchKernelGGL(csr_z_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_w, s, p.col, p.val, rowbase, bounds, w,
                        zpart, d, batch, ntiles, shift);
