@@ -546,8 +546,9 @@ __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __res
 
 // Gradient pass: one workgroup per (worker, tile); every minibatch row adds (r_i / B) val into the
 // fp64 tile in LDS, and the finished tile is written once (+ l2 w).
-// Cycle stamps inside this kernel at d = 2^24, M = 64, B = 512 (22 k clocks per tile): clearing the
-// tile 5 %, staging 11 %, waiting for the entries 33 %, the adds 37 %, writing the tile out 14 %.
+// Where the time goes at d = 2^24, M = 64, B = 512 (2.47 ms): without the adds 2.32 ms, without the
+// write-out of g 1.96 ms -- the rest is reading the entries in 66-byte segments, at the rate such
+// segments are delivered at all (see the paired dot-product pass).
 // Variants that measured slower or no faster: prefetching the next tile's entries during the
 // write-out (software pipelining over a run of tiles); fetching the entries of two adjacent tiles
 // at once into registers and working through them in two phases (longer segments, fewer partial
