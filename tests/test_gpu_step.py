@@ -335,6 +335,13 @@ def test_csr_tile_index_changes_nothing_but_the_speed():
     w = 0.05 * torch.randn(d, device=DEV)
     g0, g1, g2 = (torch.empty((M, d), device=DEV) for _ in range(3))
     ctx.local_grad(3, w, g0)
+    # an index buffer that is too small or misaligned is refused before anything is built
+    import ctypes
+    rows = (ctypes.c_uint64 * M)(*ctx.n_rows)
+    need = B.lib().tng_csr_index_bytes(ctypes.byref(ctx.cfg), rows)
+    small = torch.empty(need, dtype=torch.uint8, device=DEV)
+    assert B.lib().tng_set_csr_index(ctx.handle, ctypes.c_void_p(small.data_ptr()), need - 1) == B.TNG_ERR_WORKSPACE
+    assert B.lib().tng_set_csr_index(ctx.handle, ctypes.c_void_p(small.data_ptr() + 8), need) == B.TNG_ERR_INVALID_ARG
     ctx.build_csr_index()
     ctx.local_grad(3, w, g1)
     ctx.set_logreg_csr(*parts)          # index dropped: back to the pass over the column ids
