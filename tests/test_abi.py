@@ -36,6 +36,18 @@ def test_config_struct_matches_the_header_layout():
     assert B.TngConfig.seed.offset == 32 and B.TngConfig.problem.offset == 52
 
 
+def test_binding_constants_match_the_header_enums():
+    header = open(os.path.join(ROOT, "include", "tng.h")).read()
+    enums = {k: int(v) for k, v in re.findall(r"\b(TNG_[A-Z0-9_]+)\s*=\s*(-?\d+)", header)}
+    for name, value in enums.items():
+        short = name[len("TNG_"):]
+        if short.startswith("ERR_") or short == "OK":
+            assert getattr(B, name) == value, name
+        else:
+            assert getattr(B, short) == value, name
+    assert {"TNG_NORM_MEAN", "TNG_SCALE_L2", "TNG_REF_WINDOW_AVG", "TNG_PROB_ROSENBROCK", "TNG_ERR_HIP"} <= set(enums)
+
+
 def test_words_per_row():
     for d in (1, 15, 16, 17, 1000, 1 << 27):
         assert B.tng_words_per_row(d, 2) == -(-d // 16)
