@@ -830,6 +830,67 @@ __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restr
   }
 }
 
+// Chunk sums of the squares for the normalisations with a shared reference, whole chunks only: the
+// reference tile of a quarter chunk stays in registers while MC workers use it (as in the maximum
+// pass), so the reference is read from memory once per MC workers.  Lane sums still add their
+// elements in the order k = 0..15: the quarters and the rows inside a quarter are walked in order.
+template <int NORM, int MC>
+__global__ __launch_bounds__(kBlock) void l2_chunk_kernel(const float4* __restrict__ g4,
+                                                          const float4* __restrict__ ref4,
+                                                          const float4* __restrict__ ref24,
+                                                          double* __restrict__ chunk_sums, uint64_t nvec,
+                                                          uint64_t nchunks, float eps, uint32_t M) {
+  __shared__ double lanes[kWavesPerBlock][kTreeLanes];
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (chunk >= nchunks) return;  // whole wavefront; no workgroup barrier below
+  const uint32_t m0 = blockIdx.y * MC;
+  constexpr int Q = 4;                                  // rows (k) per quarter chunk
+  constexpr int K = kTreeChunk / kTreeLanes;            // 16 rows of 64 float4 per chunk
+  const uint64_t v0 = chunk * (kTreeChunk / 4) + lane;  // float4 index of row k = 0
+  double acc[MC][4];
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) acc[mm][0] = acc[mm][1] = acc[mm][2] = acc[mm][3] = 0.0;
+#pragma unroll 1
+  for (int k0 = 0; k0 < K; k0 += Q) {
+    RefTile<NORM> rt[Q];
+#pragma unroll
+    for (int k = 0; k < Q; ++k) rt[k].load(ref4, ref24, v0 + (uint64_t)(k0 + k) * kWave, eps);
+#pragma unroll
+    for (int mm = 0; mm < MC; ++mm) {
+      // rows past M (MC not dividing M) repeat the last row; their sums are not stored
+      const float4* __restrict__ row = g4 + (uint64_t)min(m0 + (uint32_t)mm, M - 1) * nvec;
+      float4 x[Q];
+#pragma unroll
+      for (int k = 0; k < Q; ++k) x[k] = load_stream(row + v0 + (uint64_t)(k0 + k) * kWave);
+#pragma unroll
+      for (int k = 0; k < Q; ++k) {
+        const double t0 = (double)normalize<NORM>(x[k].x, rt[k].r1.x, rt[k].r2.x);
+        const double t1 = (double)normalize<NORM>(x[k].y, rt[k].r1.y, rt[k].r2.y);
+        const double t2 = (double)normalize<NORM>(x[k].z, rt[k].r1.z, rt[k].r2.z);
+        const double t3 = (double)normalize<NORM>(x[k].w, rt[k].r1.w, rt[k].r2.w);
+        acc[mm][0] = acc[mm][0] + t0 * t0;  // the square of a binary32 value is exact in binary64
+        acc[mm][1] = acc[mm][1] + t1 * t1;
+        acc[mm][2] = acc[mm][2] + t2 * t2;
+        acc[mm][3] = acc[mm][3] + t3 * t3;
+      }
+    }
+  }
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) lanes[wave][4 * lane + i] = acc[mm][i];
+    wave_lds_fence();
+    if (lane == 0 && m0 + mm < M) {
+      double total = 0.0;
+#pragma unroll 16
+      for (int j = 0; j < kTreeLanes; ++j) total = total + lanes[wave][j];
+      chunk_sums[(uint64_t)(m0 + mm) * nchunks + chunk] = total;
+    }
+    wave_lds_fence();
+  }
+}
+
 // One workgroup per worker: group sums (thread q adds the chunks of groups q, q + 256, ... in order),
 // then thread 0 adds the groups in order.  MEAN: out[m] = float(total / d), and, when chunk_minmax is
 // given, scales[m] = max |g - out[m]| from the smallest and the largest element.  Otherwise
@@ -1110,6 +1171,30 @@ hipError_t tree_sum_launch(const CodecShape& c, const float* g, const float* gre
   float2* minmax = reinterpret_cast<float2*>(sums + nchunks * c.M);
   double* group_sums = sums + 2 * nchunks * c.M;
   const uint32_t gx = (uint32_t)((nchunks + kWavesPerBlock - 1) / kWavesPerBlock);
+  constexpr bool kSharedRef = NORM == kNormSub || NORM == kNormQuot || NORM == kNormComb;
+  if (SQUARE && kSharedRef && c.d % kTreeChunk == 0 && vec_ok(c.d, g, gref, gref2)) {
+    int mc = 4;  // workers per workgroup that share the reference tile in registers
+    while (mc > 1 && (uint64_t)gx * ((c.M + mc - 1) / mc) < 2048) mc >>= 1;
+    const float4* g4 = reinterpret_cast<const float4*>(g);
+    const float4* r4 = reinterpret_cast<const float4*>(gref);
+    const float4* r24 = reinterpret_cast<const float4*>(gref2);
+    dim3 grid(gx, (c.M + mc - 1) / mc);
+    if (mc == 4) {
+      hipLaunchKernelGGL((l2_chunk_kernel<kSharedRef ? NORM : kNormSub, 4>), grid, dim3(kBlock), 0, s, g4, r4, r24, sums,
+                         c.d / 4, nchunks, c.eps, c.M);
+    } else if (mc == 2) {
+      hipLaunchKernelGGL((l2_chunk_kernel<kSharedRef ? NORM : kNormSub, 2>), grid, dim3(kBlock), 0, s, g4, r4, r24, sums,
+                         c.d / 4, nchunks, c.eps, c.M);
+    } else {
+      hipLaunchKernelGGL((l2_chunk_kernel<kSharedRef ? NORM : kNormSub, 1>), grid, dim3(kBlock), 0, s, g4, r4, r24, sums,
+                         c.d / 4, nchunks, c.eps, c.M);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((tree_finish_kernel<false>), dim3(c.M), dim3(kBlock), 0, s, sums, group_sums, nullptr, nchunks,
+                       ngroups, c.d, out, scales);
+    return hipGetLastError();
+  }
   // workers per workgroup: as many as leave 2048 workgroups (only worth it when a reference is shared)
   uint32_t wpb = 1;
   if (SQUARE && gref != nullptr)
