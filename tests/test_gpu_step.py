@@ -91,6 +91,40 @@ def test_dense_logistic_skewed_features_at_the_experiments_shape():
         assert last < first - 0.02
 
 
+def test_free_running_trajectories_decrease_the_loss_alike():
+    # no teacher forcing: the library and the oracle each run 100 iterations on their own iterates; the
+    # trajectories may part after the first rounding decision that flips, the loss curves may not
+    M, n, d, batch, seed, T = 4, 2000, 1000, 64, 0, 100
+    say("free-running dense logistic d=1000 M=4 B=64 T=100")
+    X, y, _ = synth.logreg_dense(M, n, d, seed=seed, device=DEV)
+    ctx = make_ctx(d, M, 2, B.NORM_SUB, seed=seed, lr=0.1, batch=batch, problem=B.PROB_LOGREG_DENSE)
+    ctx.set_logreg_dense([X[m] for m in range(M)], [y[m] for m in range(M)])
+    cfg = oracle_cfg(ctx)
+    Xh, yh = X.cpu().numpy(), y.cpu().numpy()
+
+    def loss(wv):
+        z = Xh.reshape(-1, d).astype(np.float64) @ np.asarray(wv, dtype=np.float64)
+        return float(np.mean(np.logaddexp(0, z) - yh.reshape(-1) * z))
+
+    w = torch.zeros(d, device=DEV)
+    gref = torch.zeros(d, device=DEV)
+    buf = buffers(ctx)
+    wo, ro = np.zeros(d, np.float32), np.zeros(d, np.float32)
+    curve_gpu, curve_cpu = [], []
+    for it in range(T):
+        ctx.step(it, w, gref, buf["g"], buf["codes"], buf["scales"], buf["vbar"])
+        ids = [O.minibatch_indices(seed, it, m, batch, n) for m in range(M)]
+        go = np.stack([O.grad_logreg_dense(Xh[m], yh[m], wo, ids[m]) for m in range(M)]).astype(np.float32)
+        wo, ro, _, _, _ = O.step(cfg, it, wo, ro, go)
+        if it % 10 == 9:
+            torch.cuda.synchronize()
+            curve_gpu.append(loss(w.cpu().numpy()))
+            curve_cpu.append(loss(wo))
+    ctx.close()
+    assert curve_gpu[-1] < np.log(2) - 0.02 and curve_cpu[-1] < np.log(2) - 0.02
+    assert max(abs(a - b) for a, b in zip(curve_gpu, curve_cpu)) < 5e-3, (curve_gpu, curve_cpu)
+
+
 def test_dense_logistic_quotient_two_bit_scaled():
     # shape of the 16-worker quotient configuration, scaled to d=2^10, 2^12 rows per worker
     say("dense logistic quotient d=1024 M=16 n=4096 B=256 T=20")
