@@ -137,9 +137,10 @@ def test_dense_logistic_odd_dimension_four_bit_l2_period():
 
 
 def test_dense_logistic_wide_rows_first_iterations():
-    # d = 2^16 as in the large dense configuration (rows of 256 KiB), few rows: first 3 iterations
-    say("dense logistic d=65536 M=4 n=512 B=256 T=3")
-    _dense_case(M=4, n=512, d=65536, batch=256, bits=2, norm=B.NORM_QUOT, T=3, seed=7)
+    # d = 2^16, 16 workers, minibatch 256 as in the large dense configuration (rows of 256 KiB), shards of
+    # 512 rows (a step only touches minibatch rows): first 3 iterations
+    say("dense logistic d=65536 M=16 n=512 B=256 T=3")
+    _dense_case(M=16, n=512, d=65536, batch=256, bits=2, norm=B.NORM_QUOT, T=3, seed=7)
 
 
 def test_rosenbrock_chain_first_iterations_at_full_shape():
@@ -294,6 +295,39 @@ def test_csr_logistic_scaled(use_index):
                 cond[m] = logistic_condition(Xb, host[m][3][ids[m]], w0)
             return ref, cond
         _teacher_forced_step(ctx, cfg, it, w, gref, buf, grad_ref)
+    ctx.close()
+
+
+def test_csr_logistic_full_dimension_first_step():
+    # the sparse configuration's per-worker shape in full: d = 2^24, 16 777 entries per row, minibatch 512,
+    # 4-bit codes, subtraction -- with 4 workers and 512-row shards (a step only touches minibatch rows);
+    # gradient against the float64 oracle norm-wise, everything downstream bit for bit
+    M, n, d, batch, seed = 4, 512, 1 << 24, 512, 6
+    nnz_row = round(1e-3 * d)
+    say(f"csr logistic full dimension d={d} M={M} nnz/row={nnz_row} B={batch}")
+    shards, _ = synth.logreg_csr(M, n, d, nnz_row, seed, device=DEV)
+    ctx = make_ctx(d, M, 4, B.NORM_SUB, seed=seed, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR)
+    ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    ctx.build_csr_index()
+    cfg = oracle_cfg(ctx)
+    host = [tuple(t.cpu().numpy() for t in s) for s in shards]
+    w = 0.01 * torch.randn(d, device=DEV, generator=torch.Generator(device=DEV).manual_seed(1))
+    gref = torch.zeros(d, device=DEV)
+    buf = buffers(ctx)
+    w0, r0 = w.cpu().numpy(), gref.cpu().numpy()
+    ctx.step(0, w, gref, buf["g"], buf["codes"], buf["scales"], buf["vbar"])
+    torch.cuda.synchronize()
+    gh = buf["g"].cpu().numpy()
+    for m in range(M):
+        ids = O.minibatch_indices(seed, 0, m, batch, n)
+        ref = O.grad_logreg_csr(host[m][0], host[m][1], host[m][2], host[m][3], w0, ids, d)
+        err = gh[m].astype(np.float64) - ref
+        assert np.linalg.norm(err) <= 1e-5 * np.linalg.norm(ref), f"worker {m}: gradient (2-norm)"
+        assert np.abs(err).max() <= 1e-5 * np.abs(ref).max(), f"worker {m}: gradient (max-norm)"
+    w1, r1, c1, s1, v1 = O.step(cfg, 0, w0, r0, gh)
+    assert np.array_equal(buf["scales"].cpu().numpy(), s1) and np.array_equal(u32(buf["codes"]), c1)
+    assert np.array_equal(buf["vbar"].cpu().numpy(), v1) and np.array_equal(w.cpu().numpy(), w1)
+    assert np.array_equal(gref.cpu().numpy(), r1)
     ctx.close()
 
 
