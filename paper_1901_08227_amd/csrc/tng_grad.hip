@@ -211,6 +211,76 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
   }
 }
 
+// The same for problems with few columns (a handful of workgroups in all): 1024 threads, the minibatch
+// rows dealt round-robin to four row groups that run side by side, their partial sums added in the
+// fixed order ((p0 + p1) + p2) + p3.  Cuts the chain of dependent row fetches to a quarter.
+constexpr int kRowGroups = 4;
+template <bool FUSE>
+__global__ __launch_bounds__(kBlock* kRowGroups) void logreg_dense_grad_split_kernel(
+    const float* const* __restrict__ Xs, const uint32_t* __restrict__ idx, const float* __restrict__ resid,
+    const float* __restrict__ w, float* __restrict__ g, uint64_t d, uint32_t batch, float inv_b, float l2,
+    ScaleFusion fuse) {
+  __shared__ float sR[kBlock];
+  __shared__ uint32_t sRow[kBlock];
+  __shared__ float4 sAcc[kRowGroups - 1][kBlock];
+  __shared__ float red[16];
+  const uint32_t m = blockIdx.y;
+  const uint32_t tx = threadIdx.x % kBlock, rg = threadIdx.x / kBlock;
+  const GlobalPtr<float> X = as_global(Xs[m]);
+  const uint64_t col = (uint64_t)blockIdx.x * kBlock + tx;  // float4 index
+  const bool active = col < d / 4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (uint32_t base = 0; base < batch; base += kBlock) {
+    __syncthreads();
+    if (rg == 0 && base + tx < batch) {
+      sR[tx] = resid[(uint64_t)m * batch + base + tx];
+      sRow[tx] = idx[(uint64_t)m * batch + base + tx];
+    }
+    __syncthreads();
+    if (active) {
+      const uint32_t cnt = min((uint32_t)kBlock, batch - base);
+#pragma unroll 8
+      for (uint32_t i = rg; i < cnt; i += kRowGroups) {
+        const float4 xv = load4_stream(X + (uint64_t)sRow[i] * d, col);
+        const float r = sR[i];
+        acc.x = __builtin_fmaf(r, xv.x, acc.x);
+        acc.y = __builtin_fmaf(r, xv.y, acc.y);
+        acc.z = __builtin_fmaf(r, xv.z, acc.z);
+        acc.w = __builtin_fmaf(r, xv.w, acc.w);
+      }
+    }
+  }
+  if (rg > 0) sAcc[rg - 1][tx] = acc;
+  __syncthreads();
+  float amax = 0.f;
+  if (active && rg == 0) {
+#pragma unroll
+    for (int k = 0; k < kRowGroups - 1; ++k) {
+      const float4 p = sAcc[k][tx];
+      acc.x = acc.x + p.x;
+      acc.y = acc.y + p.y;
+      acc.z = acc.z + p.z;
+      acc.w = acc.w + p.w;
+    }
+    const float4 wv = reinterpret_cast<const float4*>(w)[col];
+    float4 o;
+    o.x = __builtin_fmaf(l2, wv.x, acc.x * inv_b);
+    o.y = __builtin_fmaf(l2, wv.y, acc.y * inv_b);
+    o.z = __builtin_fmaf(l2, wv.z, acc.z * inv_b);
+    o.w = __builtin_fmaf(l2, wv.w, acc.w * inv_b);
+    reinterpret_cast<float4*>(g + (uint64_t)m * d)[col] = o;
+    if (FUSE) {
+      float4 r1, r2;
+      load_refs4(fuse, col, r1, r2);
+      amax = absmax4(fuse, o, r1, r2);
+    }
+  }
+  if (FUSE) {
+    amax = block_max(amax, red);
+    if (threadIdx.x == 0) fuse.partials[(uint64_t)blockIdx.x * gridDim.y + m] = amax;
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // CSR logistic regression, column-tiled.
 //
@@ -736,6 +806,19 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
   }
   if (vec) {
     dim3 grid_g((uint32_t)((d / 4 + kBlock - 1) / kBlock), M);
+    const bool can_fuse = fuse != nullptr && fused_rows != nullptr && grid_g.x <= kAbsmaxMaxBlocks &&
+                          aligned16(fuse->gref) && aligned16(fuse->gref2);
+    if ((uint64_t)grid_g.x * M <= 128 && batch >= 4 * kRowGroups) {  // a handful of workgroups: split the rows
+      if (can_fuse) {
+        hipLaunchKernelGGL((logreg_dense_grad_split_kernel<true>), grid_g, dim3(kBlock * kRowGroups), 0, s, p.X, idx, resid,
+                           w, g, d, batch, inv_b, l2, *fuse);
+        *fused_rows = grid_g.x;
+      } else {
+        hipLaunchKernelGGL((logreg_dense_grad_split_kernel<false>), grid_g, dim3(kBlock * kRowGroups), 0, s, p.X, idx,
+                           resid, w, g, d, batch, inv_b, l2, ScaleFusion{});
+      }
+      return hipGetLastError();
+    }
     if (fuse != nullptr && fused_rows != nullptr && grid_g.x <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
         aligned16(fuse->gref2)) {
       hipLaunchKernelGGL((logreg_dense_grad_kernel<true, true>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,

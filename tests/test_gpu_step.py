@@ -136,6 +136,13 @@ def test_dense_logistic_odd_dimension_four_bit_l2_period():
     _dense_case(M=3, n=500, d=1003, batch=300, bits=4, norm=B.NORM_SUB, T=9, seed=5, l2=0.01, ref_period=4)
 
 
+def test_dense_logistic_few_columns_ragged_minibatch_over_one_staging_chunk():
+    # few columns (the gradient kernel deals the minibatch rows to row groups), minibatch 301: more than
+    # one staging chunk of 256 rows and not a multiple of the number of row groups
+    say("dense logistic d=1000 M=2 n=400 B=301 T=6")
+    _dense_case(M=2, n=400, d=1000, batch=301, bits=2, norm=B.NORM_SUB, T=6, seed=9, l2=0.001)
+
+
 def test_dense_logistic_wide_rows_first_iterations():
     # d = 2^16, 16 workers, minibatch 256 as in the large dense configuration (rows of 256 KiB), shards of
     # 512 rows (a step only touches minibatch rows): first 3 iterations
