@@ -164,17 +164,54 @@ def step_state(torch, ctx, w0):
             torch.empty(ctx.d, device=dev))
 
 
-def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup):
+def oracle_step_seconds(ctx, grads, w0):
+    """One whole iteration of the oracle on the host: `grads()` returns the M local gradients (timed),
+    then normalise/encode/decode/update/refresh.  Returns seconds."""
+    import numpy as np
+
+    from oracle import tng_oracle as O
+
+    c = ctx.cfg
+    cfg = O.Config(d=int(c.d), M=int(c.M), bits=int(c.bits), norm=int(c.norm), quot_eps=float(c.quot_eps),
+                   ref_policy=int(c.ref_policy), ref_period=int(c.ref_period), seed=int(c.seed), lr=float(c.lr),
+                   l2=float(c.l2), batch=int(c.batch))
+    t0 = time.perf_counter()
+    g = np.stack(grads(O)).astype(np.float32)
+    O.step(cfg, 0, w0, np.zeros(cfg.d, np.float32), g)
+    return time.perf_counter() - t0
+
+
+def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup, with_oracle=False):
     """tng_step (local gradient + encode + decode + update + reference refresh) on the four training
     workloads.  The two large logistic workloads keep their per-step shape (d, M, minibatch, density) but
     hold fewer rows per worker than described: a step touches only the minibatch rows, so its traffic
     does not depend on the shard size."""
     out = []
 
-    def record(name, ms, algo_bytes, note):
+    def record(name, ms, algo_bytes, note, oracle=None):
         out.append({"workload": name, "ms_per_step": round(ms, 4), "steps_per_s": round(1e3 / ms, 1),
                     "algorithmic_GBps": round(algo_bytes / (ms * 1e-3) / 1e9, 1),
                     "pct_hbm_peak": round(100 * algo_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2), "note": note})
+        if oracle is not None:      # (seconds, what was timed): the numpy oracle, one iteration, single thread
+            out[-1]["oracle_ms_per_step"] = round(oracle[0] * 1e3, 2)
+            out[-1]["oracle_sample"] = oracle[1]
+
+    def logistic_oracle(ctx, Xs, ys, n, d, dense=True, shards=None):
+        """Times the oracle on the rows the first minibatch touches (copied to the host beforehand)."""
+        import numpy as np
+
+        from oracle import tng_oracle as O
+
+        M, batch, seed = ctx.M, int(ctx.cfg.batch), int(ctx.cfg.seed)
+        ids = [O.minibatch_indices(seed, 0, m, batch, n) for m in range(M)]
+        w0 = np.zeros(d, np.float32)
+        if dense:
+            rows = [(Xs[m][torch.from_numpy(ids[m].astype(np.int64)).to(dev)].cpu().numpy(),
+                     ys[m].cpu().numpy()[ids[m]]) for m in range(M)]
+            return oracle_step_seconds(ctx, lambda O: [O.grad_logreg_dense(rows[m][0], rows[m][1], w0, np.arange(batch))
+                                                       for m in range(M)], w0)
+        host = [tuple(t.cpu().numpy() for t in sh) for sh in shards]
+        return oracle_step_seconds(ctx, lambda O: [O.grad_logreg_csr(*host[m], w0, ids[m], d) for m in range(M)], w0)
 
     # small dense logistic regression: latency bound
     M, n, d, batch = 4, 2000, 1000, 64
@@ -182,8 +219,9 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup):
     ctx = B.Context(d=d, M=M, bits=2, norm=B.NORM_SUB, seed=0, lr=0.1, batch=batch, problem=B.PROB_LOGREG_DENSE, device=dev)
     ctx.set_logreg_dense([X[m] for m in range(M)], [y[m] for m in range(M)])
     ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), steps * 4, warmup)
+    orc = (logistic_oracle(ctx, X, y, n, d), "same shape") if with_oracle else None
     record("dense logistic d=1000 M=4 B=64 ternary sub", ms, 2 * 4 * M * batch * d + 2 * (4 * M * d) + M * ctx.words * 8 + 24 * d,
-           "launch-latency bound")
+           "launch-latency bound", orc)
     ctx.close()
     del X, y
 
@@ -193,8 +231,12 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup):
     noises = [synth.gradient_noise(M, d, 1, it, variance=0.01, device=dev) for it in range(8)]
     ms = time_steps(torch, ctx, step_state(torch, ctx, synth.rosenbrock_start(d, 1, device=dev)), steps, warmup,
                     per_step=lambda it: ctx.set_noise(noises[it % 8]))
+    orc = None
+    if with_oracle:
+        x0, nz = synth.rosenbrock_start(d, 1, device=dev).cpu().numpy(), noises[0].cpu().numpy()
+        orc = (oracle_step_seconds(ctx, lambda O: [O.grad_rosenbrock(x0, nz[m]) for m in range(M)], x0), "same shape")
     record("Rosenbrock chain d=2^20 M=8 ternary sub", ms, 4 * M * d * 2 + 4 * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
-           "noise read + g write + two encode passes + decode/update")
+           "noise read + g write + two encode passes + decode/update", orc)
     del noises
     ctx.set_noise_variance(0.01)
     ms = time_steps(torch, ctx, step_state(torch, ctx, synth.rosenbrock_start(d, 1, device=dev)), steps, warmup)
@@ -210,8 +252,9 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup):
     ctx = B.Context(d=d, M=M, bits=2, norm=B.NORM_QUOT, seed=2, lr=0.1, batch=batch, problem=B.PROB_LOGREG_DENSE, device=dev)
     ctx.set_logreg_dense(X, y)
     ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), steps, warmup)
+    orc = (logistic_oracle(ctx, X, y, n, d), "same shape, minibatch rows already on the host") if with_oracle else None
     record("dense logistic d=2^16 M=16 B=256 2-bit quot", ms, 2 * 4 * M * batch * d + 3 * (4 * M * d) + M * ctx.words * 8 + 24 * d,
-           f"{n} rows per worker held (per-step traffic is that of the minibatch rows, read twice)")
+           f"{n} rows per worker held (per-step traffic is that of the minibatch rows, read twice)", orc)
     ctx.close()
     del X, y
 
@@ -224,11 +267,20 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup):
     ctx.build_csr_index()          # one-off, depends on the shards only
     ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), max(steps // 2, 5), max(warmup // 2, 2))
     nnz = M * batch * nnz_row
+    ctx.close()
+    orc = None
+    if with_oracle:     # the oracle on the scaled shape the parity tests use: d = 2^16, 8 workers, same density
+        del shards
+        Ms, ns, ds = 8, 2048, 1 << 16
+        small, _ = synth.logreg_csr(Ms, ns, ds, round(1e-3 * ds), seed=3, device=dev)
+        sctx = B.Context(d=ds, M=Ms, bits=4, norm=B.NORM_SUB, seed=3, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR, device=dev)
+        orc = (logistic_oracle(sctx, None, None, ns, ds, dense=False, shards=small),
+               "scaled to d=2^16, M=8, B=512, nnz/row=66 (1/2048 of the entries of the timed shape)")
+        sctx.close()
     record("sparse logistic d=2^24 M=64 B=512 nnz/row=16777 4-bit sub", ms,
            2 * 8 * nnz + 4 * M * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
            f"{n} rows per worker held, per-row tile index prebuilt; bytes: (col, val) twice (z pass, g pass), "
-           "g written once, two encode passes, decode/update")
-    ctx.close()
+           "g written once, two encode passes, decode/update", orc)
     return out
 
 
@@ -339,7 +391,7 @@ def main():
         del g, gref
         torch.cuda.empty_cache()
         log("timing whole iterations (tng_step) on the training workloads")
-        iteration_results = whole_iteration_benchmarks(torch, B, synth, dev, 20, 5)
+        iteration_results = whole_iteration_benchmarks(torch, B, synth, dev, 20, 5, with_oracle=not args.no_cpu)
         g = gref = None
 
     dom_name = max(head["kernels"], key=lambda k: head["kernels"][k]["ms"])
