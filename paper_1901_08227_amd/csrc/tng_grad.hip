@@ -619,10 +619,15 @@ __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __res
 // Where the time goes at d = 2^24, M = 64, B = 512 (2.47 ms): without the adds 2.32 ms, without the
 // write-out of g 1.96 ms -- the rest is reading the entries in 66-byte segments, at the rate such
 // segments are delivered at all (see the paired dot-product pass).
-// Variants that measured slower or no faster: prefetching the next tile's entries during the
-// write-out (software pipelining over a run of tiles); fetching the entries of two adjacent tiles
-// at once into registers and working through them in two phases (longer segments, fewer partial
-// memory lines: the gradient pass gained nothing, the dot-product pass lost to its second tile load).
+// Taken apart the same way, zeroing + write-out alone take 0.85 ms and staging + entry loads alone
+// 1.50 ms: per compute unit the phases simply add up.  Variants that measured slower or no faster:
+// prefetching the next tile's entries during the write-out (software pipelining over a run of
+// tiles); tiles of half the width with two workgroups per compute unit, so that one writes while
+// the other reads (2.79 ms: the segments of 33 bytes cost more than the overlap gains); fetching the
+// entries of two adjacent tiles at once into registers (one wavefront per row, segment descriptors
+// as wavefront-uniform values, no spills) and working through the tiles in two phases with the first
+// tile's stores left in flight (2.66 ms: its loads alone 1.26 ms, its write-out alone 1.06 ms, both
+// together more than their sum -- the random reads and the streaming writes compete in memory).
 __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* const* __restrict__ cols,
                                                                const float* const* __restrict__ vals,
                                                                const int64_t* __restrict__ rowbase,
