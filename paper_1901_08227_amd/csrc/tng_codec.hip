@@ -163,6 +163,23 @@ __global__ __launch_bounds__(kBlock) void absmax_finish_kernel(const float* __re
   }
 }
 
+// The M gradient rows as the vector kernels read them.  Row m starts m * pitch floats into the array;
+// the pitch (= d) need not be a multiple of 4, so a row may start at any 4-byte boundary.  16-byte
+// loads from such addresses are legal for global memory on this target (the type below only tells
+// the compiler not to assume more than 4-byte alignment; the instruction is the same).
+typedef float v4f_u_t __attribute__((ext_vector_type(4), aligned(4)));
+struct GradRows {
+  const float* base;
+  uint64_t pitch;
+  __device__ __forceinline__ const v4f_u_t* row(uint32_t m) const {
+    return reinterpret_cast<const v4f_u_t*>(base + (uint64_t)m * pitch);
+  }
+};
+__device__ __forceinline__ float4 load_row_stream(const v4f_u_t* p) {
+  const v4f_u_t v = __builtin_nontemporal_load(p);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // ------------------------------------------------------------------------------------------
 // Pass 1: R_m = max_e |v_{m,e}|   (section "Gradient Compression": R = max_d |v_d|)
 // ------------------------------------------------------------------------------------------
@@ -173,12 +190,12 @@ __global__ __launch_bounds__(kBlock) void absmax_finish_kernel(const float* __re
 constexpr int kAbsmaxLoads = 4;
 
 template <int NORM, bool FULL>
-__device__ __forceinline__ void absmax_load(const float4* __restrict__ row, const uint64_t (&iv)[kAbsmaxLoads],
+__device__ __forceinline__ void absmax_load(const v4f_u_t* __restrict__ row, const uint64_t (&iv)[kAbsmaxLoads],
                                             uint64_t nvec, float4 (&x)[kAbsmaxLoads]) {
 #pragma unroll
   for (int j = 0; j < kAbsmaxLoads; ++j) {
     if (FULL || iv[j] < nvec) {
-      x[j] = load_stream(row + iv[j]);
+      x[j] = load_row_stream(row + iv[j]);
     } else {
       x[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
@@ -203,13 +220,13 @@ __device__ __forceinline__ float absmax_reduce(const float4 (&x)[kAbsmaxLoads], 
 }
 
 template <int NORM, int MC, bool FULL>
-__device__ __forceinline__ void absmax_rows(const float4* __restrict__ g4, const RefTile<NORM> (&rt)[kAbsmaxLoads],
+__device__ __forceinline__ void absmax_rows(const GradRows& g, const RefTile<NORM> (&rt)[kAbsmaxLoads],
                                             const uint64_t (&iv)[kAbsmaxLoads], uint64_t nvec, uint32_t m0,
                                             uint32_t M, const float* __restrict__ means, float (&mx)[MC]) {
   constexpr int L = kAbsmaxLoads;
   float4 xa[L], xb[L];
   // rows past M (only when MC does not divide M) repeat the last row, which leaves its maximum unchanged
-  auto row = [&](int mm) { return g4 + (uint64_t)min(m0 + (uint32_t)mm, M - 1) * nvec; };
+  auto row = [&](int mm) { return g.row(min(m0 + (uint32_t)mm, M - 1)); };
   auto mean_of = [&](int mm) { return NORM == kNormMean ? means[min(m0 + (uint32_t)mm, M - 1)] : 0.f; };
   absmax_load<NORM, FULL>(row(0), iv, nvec, xa);
 #pragma unroll
@@ -224,8 +241,7 @@ __device__ __forceinline__ void absmax_rows(const float4* __restrict__ g4, const
 }
 
 template <int NORM, int MC>
-__global__ __launch_bounds__(kBlock) void absmax_vec_kernel(const float4* __restrict__ g4,
-                                                            const float4* __restrict__ ref4,
+__global__ __launch_bounds__(kBlock) void absmax_vec_kernel(GradRows g, const float4* __restrict__ ref4,
                                                             const float4* __restrict__ ref24,
                                                             float* partials, uint64_t nvec,
                                                             uint32_t M, float eps, const float* __restrict__ means) {
@@ -248,9 +264,9 @@ __global__ __launch_bounds__(kBlock) void absmax_vec_kernel(const float4* __rest
       if (full || iv[j] < nvec) rt[j].load(ref4, ref24, iv[j], eps);
     }
     if (full) {
-      absmax_rows<NORM, MC, true>(g4, rt, iv, nvec, m0, M, means, mx);
+      absmax_rows<NORM, MC, true>(g, rt, iv, nvec, m0, M, means, mx);
     } else {
-      absmax_rows<NORM, MC, false>(g4, rt, iv, nvec, m0, M, means, mx);
+      absmax_rows<NORM, MC, false>(g, rt, iv, nvec, m0, M, means, mx);
     }
   }
   block_max_to_partials<MC>(mx, m0, M, partials);
@@ -260,13 +276,14 @@ template <int NORM>
 __global__ __launch_bounds__(kBlock) void absmax_scalar_kernel(const float* __restrict__ g,
                                                                const float* __restrict__ ref,
                                                                const float* __restrict__ ref2,
-                                                               float* partials, uint64_t d, uint32_t M,
-                                                               float eps, const float* __restrict__ means) {
+                                                               float* partials, uint64_t first, uint64_t d,
+                                                               uint32_t M, float eps,
+                                                               const float* __restrict__ means) {
   const uint32_t m = blockIdx.y;
   const float mu = NORM == kNormMean ? means[m] : 0.f;
   float mx[1] = {0.f};
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-  for (uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x; e < d; e += stride) {
+  for (uint64_t e = first + (uint64_t)blockIdx.x * kBlock + threadIdx.x; e < d; e += stride) {
     float r1, r2;
     load_ref_scalar<NORM>(ref, ref2, e, eps, r1, r2);
     mx[0] = fmaxf(mx[0], fabsf(normalize_w<NORM>(g[(uint64_t)m * d + e], r1, r2, mu)));
@@ -294,12 +311,12 @@ struct QuantLane {
 };
 
 template <int NORM, bool FULL>
-__device__ __forceinline__ void load_worker_tile(const QuantLane<NORM>& q, const float4* __restrict__ g4,
-                                                 uint64_t nvec, uint32_t m, float4 (&x)[kLoadsPerLane]) {
+__device__ __forceinline__ void load_worker_tile(const QuantLane<NORM>& q, const GradRows& g, uint32_t m,
+                                                 float4 (&x)[kLoadsPerLane]) {
 #pragma unroll
   for (int j = 0; j < kLoadsPerLane; ++j) {
     if (FULL || q.ok[j]) {
-      x[j] = load_stream(g4 + (uint64_t)m * nvec + q.iv[j]);
+      x[j] = load_row_stream(g.row(m) + q.iv[j]);
     } else {
       x[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
@@ -426,7 +443,7 @@ __device__ __forceinline__ float fused_scale(const FusedScale& f, uint32_t m, ui
 
 template <int NORM, int BITS, int WPW, int SLOTS, bool FULL, bool FUSED, bool DEFER>
 __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, FragmentBuffer<WPW, SLOTS>& lds, int wave, int lane,
-                                              const float4* __restrict__ g4, const float* __restrict__ scales,
+                                              const GradRows& g, const float* __restrict__ scales,
                                               uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words,
                                               uint64_t word_base, uint32_t m0, uint32_t m_end, uint32_t iter,
                                               uint32_t k0, uint32_t k1, const float* __restrict__ means,
@@ -442,7 +459,7 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
     return FUSED ? fused_scale(fs, m, M, blockIdx.x == 0 && threadIdx.x == 0) : scales[m];
   };
   float ra = scale_of(m0), mua = mean_of(m0), rb = 0.f, mub = 0.f;
-  load_worker_tile<NORM, FULL>(q, g4, nvec, m0, xa);
+  load_worker_tile<NORM, FULL>(q, g, m0, xa);
   // Steady state: both prefetches of a trip are unconditional.  A load issued under a condition
   // makes the compiler wait for all outstanding loads where the paths join (it cannot count what
   // is in flight), which would drain the prefetch before the arithmetic it is meant to overlap.
@@ -450,13 +467,13 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
   for (; m + 2 < m_end; m += 2) {
     rb = scale_of(m + 1);
     mub = mean_of(m + 1);
-    load_worker_tile<NORM, FULL>(q, g4, nvec, m + 1, xb);
+    load_worker_tile<NORM, FULL>(q, g, m + 1, xb);
     quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
     store_packed<BITS, WPW, SLOTS, DEFER>(lds, DEFER ? (int)(m - m0) : 0, wave, lane, frag, codes + (uint64_t)m * words, word_base,
                                           words);
     ra = scale_of(m + 2);
     mua = mean_of(m + 2);
-    load_worker_tile<NORM, FULL>(q, g4, nvec, m + 2, xa);
+    load_worker_tile<NORM, FULL>(q, g, m + 2, xa);
     quantize_worker_tile<NORM, BITS, FULL>(q, xb, rb, mub, m + 1, iter, k0, k1, frag);
     store_packed<BITS, WPW, SLOTS, DEFER>(lds, DEFER ? (int)(m + 1 - m0) : 0, wave, lane, frag,
                                           codes + (uint64_t)(m + 1) * words, word_base, words);
@@ -465,7 +482,7 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
   if (m + 1 < m_end) {
     rb = scale_of(m + 1);
     mub = mean_of(m + 1);
-    load_worker_tile<NORM, FULL>(q, g4, nvec, m + 1, xb);
+    load_worker_tile<NORM, FULL>(q, g, m + 1, xb);
     quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
     store_packed<BITS, WPW, SLOTS, DEFER>(lds, DEFER ? (int)(m - m0) : 0, wave, lane, frag, codes + (uint64_t)m * words, word_base,
                                           words);
@@ -482,7 +499,7 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
 
 template <int NORM, int BITS, int MC, bool FUSED>
 __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
-    const float4* __restrict__ g4, const float4* __restrict__ ref4, const float4* __restrict__ ref24,
+    GradRows g, const float4* __restrict__ ref4, const float4* __restrict__ ref24,
     const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words,
     uint32_t M, float eps, uint32_t k0, uint32_t k1, uint32_t iter, const float* __restrict__ means,
     FusedScale fs) {
@@ -505,14 +522,14 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
   const uint32_t m_end = min(m0 + MC, M);
   if ((wave_tile + 1) * (kWave * L) <= nvec) {  // wave-uniform
     if (MC > 1 && words % 4 == 0 && (reinterpret_cast<uintptr_t>(codes) & 15u) == 0) {  // 16-byte aligned rows
-      quantize_rows<NORM, BITS, WPW, MC, true, FUSED, true>(q, lds, wave, lane, g4, scales, codes, nvec, words,
+      quantize_rows<NORM, BITS, WPW, MC, true, FUSED, true>(q, lds, wave, lane, g, scales, codes, nvec, words,
                                                             word_base, m0, m_end, iter, k0, k1, means, fs, M);
     } else {
-      quantize_rows<NORM, BITS, WPW, MC, true, FUSED, false>(q, lds, wave, lane, g4, scales, codes, nvec, words,
+      quantize_rows<NORM, BITS, WPW, MC, true, FUSED, false>(q, lds, wave, lane, g, scales, codes, nvec, words,
                                                              word_base, m0, m_end, iter, k0, k1, means, fs, M);
     }
   } else {
-    quantize_rows<NORM, BITS, WPW, MC, false, FUSED, false>(q, lds, wave, lane, g4, scales, codes, nvec, words,
+    quantize_rows<NORM, BITS, WPW, MC, false, FUSED, false>(q, lds, wave, lane, g, scales, codes, nvec, words,
                                                             word_base, m0, m_end, iter, k0, k1, means, fs, M);
   }
 }
@@ -521,15 +538,16 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
 template <int NORM, int BITS>
 __global__ __launch_bounds__(kBlock) void quantize_pack_scalar_kernel(
     const float* __restrict__ g, const float* __restrict__ ref, const float* __restrict__ ref2,
-    const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t d, uint64_t words, uint32_t M,
-    float eps, uint32_t k0, uint32_t k1, uint32_t iter, const float* __restrict__ means, FusedScale fs) {
+    const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t first_word, uint64_t d,
+    uint64_t words, uint32_t M, float eps, uint32_t k0, uint32_t k1, uint32_t iter,
+    const float* __restrict__ means, FusedScale fs) {
   constexpr int PER = 32 / BITS;
   const uint32_t m = blockIdx.y;
   const float mu = NORM == kNormMean ? means[m] : 0.f;
   const float R = fs.rows != 0 ? fused_scale(fs, m, M, blockIdx.x == 0 && threadIdx.x == 0) : scales[m];
   const float inv_r = R != 0.f ? 1.0f / R : 0.f;
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-  for (uint64_t wi = (uint64_t)blockIdx.x * kBlock + threadIdx.x; wi < words; wi += stride) {
+  for (uint64_t wi = first_word + (uint64_t)blockIdx.x * kBlock + threadIdx.x; wi < words; wi += stride) {
     uint32_t word = 0u;
     if (R != 0.f) {
 #pragma unroll 1
@@ -678,12 +696,12 @@ __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
 template <int NORM, int BITS>
 __global__ __launch_bounds__(kBlock) void decode_scalar_kernel(
     const uint32_t* __restrict__ codes, const float* __restrict__ scales, const float* ref,
-    const float* __restrict__ ref2, float* __restrict__ vbar, float* __restrict__ w, float* refout, uint64_t d,
-    uint64_t words, uint32_t M, float eps, float inv_m, float lr, const float* __restrict__ means) {
+    const float* __restrict__ ref2, float* __restrict__ vbar, float* __restrict__ w, float* refout, uint64_t first,
+    uint64_t d, uint64_t words, uint32_t M, float eps, float inv_m, float lr, const float* __restrict__ means) {
   __shared__ float sR[kScaleChunk], sStep[kScaleChunk];
   constexpr int PER = 32 / BITS;
   constexpr uint32_t MASK = (1u << BITS) - 1u;
-  const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  const uint64_t e = first + (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   const bool active = e < d;
   const uint64_t wi = e / PER;
   const uint32_t sh = (uint32_t)(e % PER) * BITS;
@@ -960,12 +978,34 @@ inline uint32_t div_up_u32(uint64_t a, uint64_t b) {
   return (uint32_t)(q > kMaxGridX ? kMaxGridX : q);
 }
 
-// Workers handled inside one workgroup: the largest of 8, 4, 2, 1 that divides M and still
-// leaves enough workgroups to fill 256 compute units.
+// Workers handled inside one workgroup (8, 4, 2 or 1; the last group of a row of workgroups may be
+// short).  A group reads the shared reference once, so fewer groups mean less traffic; a short group
+// costs the scale pass repeated loads of its last row (cache hits, weighted 0.3 of a row here).  At
+// least 2048 workgroups are kept to fill 256 compute units.
 inline int pick_workers_per_block(uint32_t M, uint64_t tiles) {
-  int mc = 8;
-  while (mc > 1 && (M % mc != 0 || tiles * (M / mc) < 2048)) mc >>= 1;
-  return mc;
+  int best = 1;
+  double best_cost = (double)M;
+  for (int mc = 2; mc <= 8; mc *= 2) {
+    const uint32_t groups = (M + mc - 1) / mc;
+    if (tiles * groups < 2048) break;
+    const double cost = groups + 0.3 * (groups * mc - M);
+    if (cost <= best_cost) {
+      best = mc;
+      best_cost = cost;
+    }
+  }
+  return best;
+}
+
+// How many leading coordinates of every row the vector kernels take: all of them when d is a
+// multiple of 4, else the largest multiple of 16 (whole packed words for either code width); the
+// scalar kernels finish the rest of each row.  0: scalar kernels only (the shared operands are not
+// 16-byte aligned).
+inline uint64_t vector_part(uint64_t d, const void* a, const void* b, const void* c = nullptr,
+                            const void* e = nullptr) {
+  auto al = [](const void* p) { return p == nullptr || (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+  if (!(al(a) && al(b) && al(c) && al(e))) return 0;
+  return d % 4 == 0 ? d : d - d % 16;
 }
 
 inline bool vec_ok(uint64_t d, const void* a, const void* b, const void* c) {
@@ -974,16 +1014,17 @@ inline bool vec_ok(uint64_t d, const void* a, const void* b, const void* c) {
 }
 
 template <int NORM, int MC>
-hipError_t absmax_vec_launch(const CodecShape& c, const float* g, const float* gref, const float* gref2,
+hipError_t absmax_vec_launch(const CodecShape& c, uint64_t dv, const float* g, const float* gref, const float* gref2,
                              float* partials, uint32_t* nblocks, hipStream_t s) {
-  const uint64_t nvec = c.d / 4;
+  const uint64_t nvec = dv / 4;
   const uint32_t per_y = div_up_u32(nvec, (uint64_t)kBlock * kAbsmaxLoads);
-  const uint32_t gx = per_y < kAbsmaxMaxBlocks ? per_y : kAbsmaxMaxBlocks;
+  const uint32_t cap = kAbsmaxMaxBlocks - 1;  // one row of partials is kept for the rows' scalar remainder
+  const uint32_t gx = per_y < cap ? per_y : cap;
   *nblocks = gx;
   dim3 grid(gx, (c.M + MC - 1) / MC);
-  hipLaunchKernelGGL((absmax_vec_kernel<NORM, MC>), grid, dim3(kBlock), 0, s,
-                     reinterpret_cast<const float4*>(g), reinterpret_cast<const float4*>(gref),
-                     reinterpret_cast<const float4*>(gref2), partials, nvec, c.M, c.eps, c.means);
+  hipLaunchKernelGGL((absmax_vec_kernel<NORM, MC>), grid, dim3(kBlock), 0, s, GradRows{g, c.d},
+                     reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), partials, nvec,
+                     c.M, c.eps, c.means);
   return hipGetLastError();
 }
 
@@ -992,19 +1033,26 @@ hipError_t absmax_dispatch(const CodecShape& c, const float* g, const float* gre
                            float* partials, float* scales, hipStream_t s) {
   uint32_t nblocks = 0;
   hipError_t e;
-  if (vec_ok(c.d, g, gref, gref2)) {
-    const int mc = pick_workers_per_block(c.M, (c.d / 4 + kBlock * kAbsmaxLoads - 1) / (kBlock * kAbsmaxLoads));
+  const uint64_t dv = vector_part(c.d, gref, gref2);
+  if (dv != 0) {
+    const int mc = pick_workers_per_block(c.M, (dv / 4 + kBlock * kAbsmaxLoads - 1) / (kBlock * kAbsmaxLoads));
     switch (mc) {
-      case 8: e = absmax_vec_launch<NORM, 8>(c, g, gref, gref2, partials, &nblocks, s); break;
-      case 4: e = absmax_vec_launch<NORM, 4>(c, g, gref, gref2, partials, &nblocks, s); break;
-      case 2: e = absmax_vec_launch<NORM, 2>(c, g, gref, gref2, partials, &nblocks, s); break;
-      default: e = absmax_vec_launch<NORM, 1>(c, g, gref, gref2, partials, &nblocks, s); break;
+      case 8: e = absmax_vec_launch<NORM, 8>(c, dv, g, gref, gref2, partials, &nblocks, s); break;
+      case 4: e = absmax_vec_launch<NORM, 4>(c, dv, g, gref, gref2, partials, &nblocks, s); break;
+      case 2: e = absmax_vec_launch<NORM, 2>(c, dv, g, gref, gref2, partials, &nblocks, s); break;
+      default: e = absmax_vec_launch<NORM, 1>(c, dv, g, gref, gref2, partials, &nblocks, s); break;
+    }
+    if (e == hipSuccess && dv < c.d) {  // the last d - dv < 16 coordinates of every row: one more row of partials
+      hipLaunchKernelGGL((absmax_scalar_kernel<NORM>), dim3(1, c.M), dim3(kBlock), 0, s, g, gref, gref2,
+                         partials + (uint64_t)nblocks * c.M, dv, c.d, c.M, c.eps, c.means);
+      nblocks += 1;
+      e = hipGetLastError();
     }
   } else {
     const uint32_t per_y = div_up_u32(c.d, kBlock);
     nblocks = per_y < kAbsmaxMaxBlocks ? per_y : kAbsmaxMaxBlocks;
     hipLaunchKernelGGL((absmax_scalar_kernel<NORM>), dim3(nblocks, c.M), dim3(kBlock), 0, s, g, gref, gref2,
-                       partials, c.d, c.M, c.eps, c.means);
+                       partials, (uint64_t)0, c.d, c.M, c.eps, c.means);
     e = hipGetLastError();
   }
   if (e != hipSuccess) return e;
@@ -1013,16 +1061,15 @@ hipError_t absmax_dispatch(const CodecShape& c, const float* g, const float* gre
 }
 
 template <int NORM, int BITS, int MC, bool FUSED>
-hipError_t quantize_vec_launch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+hipError_t quantize_vec_launch(const CodecShape& c, uint64_t dv, uint32_t iter, const float* g, const float* gref,
                                const float* gref2, const float* scales, uint32_t* codes, const FusedScale& fs,
                                hipStream_t s) {
-  const uint64_t nvec = c.d / 4;
+  const uint64_t nvec = dv / 4;
   const uint64_t tiles = (nvec + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
   dim3 grid((uint32_t)tiles, (c.M + MC - 1) / MC);
-  hipLaunchKernelGGL((quantize_pack_vec_kernel<NORM, BITS, MC, FUSED>), grid, dim3(kBlock), 0, s,
-                     reinterpret_cast<const float4*>(g), reinterpret_cast<const float4*>(gref),
-                     reinterpret_cast<const float4*>(gref2), scales, codes, nvec, c.words, c.M, c.eps, c.k0,
-                     c.k1, iter, c.means, fs);
+  hipLaunchKernelGGL((quantize_pack_vec_kernel<NORM, BITS, MC, FUSED>), grid, dim3(kBlock), 0, s, GradRows{g, c.d},
+                     reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), scales, codes, nvec,
+                     c.words, c.M, c.eps, c.k0, c.k1, iter, c.means, fs);
   return hipGetLastError();
 }
 
@@ -1033,29 +1080,39 @@ template <int NORM, int BITS>
 hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
                              const float* gref2, float* scales, uint32_t* codes, const float* partials,
                              uint32_t fused_rows, hipStream_t s) {
-  const bool vec = vec_ok(c.d, g, gref, gref2);
-  const uint64_t tiles = (c.d / 4 + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
+  const uint64_t dv = vector_part(c.d, gref, gref2);
+  const bool vec = dv != 0;
+  const uint64_t tiles = (dv / 4 + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
   const int mc = vec ? pick_workers_per_block(c.M, tiles) : 1;
   FusedScale fs{partials, fused_rows, scales};
-  if (fused_rows > kFusedScaleRows || (fused_rows > 0 && mc != 1)) {
+  if (fused_rows > kFusedScaleRows || (fused_rows > 0 && (mc != 1 || dv != c.d))) {
     hipLaunchKernelGGL(absmax_finish_kernel, dim3(c.M), dim3(kBlock), 0, s, partials, fused_rows, c.M, scales);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     fs.rows = 0;
   }
   if (vec) {
-    if (fs.rows > 0) return quantize_vec_launch<NORM, BITS, 1, true>(c, iter, g, gref, gref2, scales, codes, fs, s);
-    switch (mc) {
-      case 8: return quantize_vec_launch<NORM, BITS, 8, false>(c, iter, g, gref, gref2, scales, codes, fs, s);
-      case 4: return quantize_vec_launch<NORM, BITS, 4, false>(c, iter, g, gref, gref2, scales, codes, fs, s);
-      case 2: return quantize_vec_launch<NORM, BITS, 2, false>(c, iter, g, gref, gref2, scales, codes, fs, s);
-      default: return quantize_vec_launch<NORM, BITS, 1, false>(c, iter, g, gref, gref2, scales, codes, fs, s);
+    hipError_t e;
+    if (fs.rows > 0) {
+      e = quantize_vec_launch<NORM, BITS, 1, true>(c, dv, iter, g, gref, gref2, scales, codes, fs, s);
+    } else {
+      switch (mc) {
+        case 8: e = quantize_vec_launch<NORM, BITS, 8, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
+        case 4: e = quantize_vec_launch<NORM, BITS, 4, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
+        case 2: e = quantize_vec_launch<NORM, BITS, 2, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
+        default: e = quantize_vec_launch<NORM, BITS, 1, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
+      }
     }
+    if (e != hipSuccess || dv == c.d) return e;
+    // the last d - dv < 16 coordinates of every row: their one or two packed words, after the vector pass
+    hipLaunchKernelGGL((quantize_pack_scalar_kernel<NORM, BITS>), dim3(1, c.M), dim3(kBlock), 0, s, g, gref, gref2,
+                       scales, codes, dv * BITS / 32, c.d, c.words, c.M, c.eps, c.k0, c.k1, iter, c.means, fs);
+    return hipGetLastError();
   }
   const uint32_t per_y = div_up_u32(c.words, kBlock);
   dim3 grid(per_y < 65536u ? per_y : 65536u, c.M);
   hipLaunchKernelGGL((quantize_pack_scalar_kernel<NORM, BITS>), grid, dim3(kBlock), 0, s, g, gref, gref2,
-                     scales, codes, c.d, c.words, c.M, c.eps, c.k0, c.k1, iter, c.means, fs);
+                     scales, codes, (uint64_t)0, c.d, c.words, c.M, c.eps, c.k0, c.k1, iter, c.means, fs);
   return hipGetLastError();
 }
 
@@ -1064,8 +1121,9 @@ hipError_t decode_dispatch(const CodecShape& c, const uint32_t* codes, const flo
                            const float* gref2, float* vbar, float* w, float lr, float* ref_out,
                            hipStream_t s) {
   const float inv_m = 1.0f / (float)c.M;
-  if (vec_ok(c.d, gref, gref2, vbar) && vec_ok(c.d, w, ref_out, nullptr)) {
-    const uint64_t nvec = c.d / 4;
+  const uint64_t dv = vector_part(c.d, gref, gref2, vbar, w) != 0 ? vector_part(c.d, ref_out, nullptr) : 0;
+  if (dv != 0) {
+    const uint64_t nvec = dv / 4;
     const uint64_t big_tiles = (nvec + kBlock * kDecodeLoads - 1) / (kBlock * kDecodeLoads);
     // Codes that fit the 256 MiB last-level cache were just written by the quantiser and are rewritten
     // by the next iteration: ordinary loads keep the lines resident (measured 4 % faster, and the
@@ -1086,11 +1144,15 @@ hipError_t decode_dispatch(const CodecShape& c, const uint32_t* codes, const flo
       TNG_DECODE_LAUNCH(1, false, (nvec + kBlock - 1) / kBlock);
     }
 #undef TNG_DECODE_LAUNCH
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || dv == c.d) return e;
+    hipLaunchKernelGGL((decode_scalar_kernel<NORM, BITS>), dim3(1), dim3(kBlock), 0, s, codes, scales, gref, gref2, vbar,
+                       w, ref_out, dv, c.d, c.words, c.M, c.eps, inv_m, lr, c.means);  // the last d - dv < 16
     return hipGetLastError();
   }
   const uint64_t blocks = (c.d + kBlock - 1) / kBlock;
   hipLaunchKernelGGL((decode_scalar_kernel<NORM, BITS>), dim3((uint32_t)blocks), dim3(kBlock), 0, s, codes,
-                     scales, gref, gref2, vbar, w, ref_out, c.d, c.words, c.M, c.eps, inv_m, lr, c.means);
+                     scales, gref, gref2, vbar, w, ref_out, (uint64_t)0, c.d, c.words, c.M, c.eps, inv_m, lr, c.means);
   return hipGetLastError();
 }
 
