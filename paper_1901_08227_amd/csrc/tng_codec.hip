@@ -751,11 +751,11 @@ __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restr
                                                             const float* __restrict__ means,
                                                             double* __restrict__ chunk_sums,
                                                             float2* __restrict__ chunk_minmax, uint64_t d,
-                                                            uint64_t nchunks, float eps, uint32_t M,
-                                                            uint32_t workers_per_block) {
+                                                            uint64_t first_chunk, uint64_t nchunks, float eps,
+                                                            uint32_t M, uint32_t workers_per_block) {
   __shared__ double lanes[kWavesPerBlock][kTreeLanes];
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-  const uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+  const uint64_t chunk = first_chunk + (uint64_t)blockIdx.x * kWavesPerBlock + wave;
   if (chunk >= nchunks) return;  // whole wavefront; no workgroup barrier below
   const uint64_t base = chunk * kTreeChunk + 4u * (uint32_t)lane;
   constexpr int K = kTreeChunk / kTreeLanes;
@@ -768,11 +768,13 @@ __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restr
   const float mu = (SQUARE && NORM == kNormMean) ? means[m] : 0.f;
   double acc[4] = {0.0, 0.0, 0.0, 0.0};
   float lo = INFINITY, hi = -INFINITY;
-  if (VEC) {
+  const bool full = (chunk + 1) * kTreeChunk <= d;
+  // 16-byte loads (the row may start at any 4-byte boundary); the last chunk of a row whose length is
+  // not a multiple of 4 goes element by element
+  if (VEC && (full || d % 4 == 0)) {
     // loads in batches: all 16 rows of the chunk at once, or 8 rows plus their reference tiles
     constexpr bool kHasRef = SQUARE && (NORM == kNormSub || NORM == kNormQuot || NORM == kNormComb);
     constexpr int KB = kHasRef ? 8 : K;
-    const bool full = (chunk + 1) * kTreeChunk <= d;
 #pragma unroll
     for (int k0 = 0; k0 < K; k0 += KB) {
       float4 x[KB];
@@ -781,7 +783,7 @@ __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restr
       for (int k = 0; k < KB; ++k) {
         const uint64_t e = base + (uint64_t)(k0 + k) * kTreeLanes;
         const bool in = full || e < d;
-        x[k] = in ? load_stream(reinterpret_cast<const float4*>(row + e)) : make_float4(0.f, 0.f, 0.f, 0.f);
+        x[k] = in ? load_row_stream(reinterpret_cast<const v4f_u_t*>(row + e)) : make_float4(0.f, 0.f, 0.f, 0.f);
         if (SQUARE && in)
           rt[k].template load<false>(reinterpret_cast<const float4*>(ref), reinterpret_cast<const float4*>(ref2), e / 4,
                                      eps);
@@ -853,15 +855,14 @@ __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restr
 // pass), so the reference is read from memory once per MC workers.  Lane sums still add their
 // elements in the order k = 0..15: the quarters and the rows inside a quarter are walked in order.
 template <int NORM, int MC>
-__global__ __launch_bounds__(kBlock) void l2_chunk_kernel(const float4* __restrict__ g4,
-                                                          const float4* __restrict__ ref4,
+__global__ __launch_bounds__(kBlock) void l2_chunk_kernel(GradRows g, const float4* __restrict__ ref4,
                                                           const float4* __restrict__ ref24,
-                                                          double* __restrict__ chunk_sums, uint64_t nvec,
+                                                          double* __restrict__ chunk_sums, uint64_t whole_chunks,
                                                           uint64_t nchunks, float eps, uint32_t M) {
   __shared__ double lanes[kWavesPerBlock][kTreeLanes];
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
-  if (chunk >= nchunks) return;  // whole wavefront; no workgroup barrier below
+  if (chunk >= whole_chunks) return;  // whole wavefront; no workgroup barrier below
   const uint32_t m0 = blockIdx.y * MC;
   constexpr int Q = 4;                                  // rows (k) per quarter chunk
   constexpr int K = kTreeChunk / kTreeLanes;            // 16 rows of 64 float4 per chunk
@@ -877,10 +878,10 @@ __global__ __launch_bounds__(kBlock) void l2_chunk_kernel(const float4* __restri
 #pragma unroll
     for (int mm = 0; mm < MC; ++mm) {
       // rows past M (MC not dividing M) repeat the last row; their sums are not stored
-      const float4* __restrict__ row = g4 + (uint64_t)min(m0 + (uint32_t)mm, M - 1) * nvec;
+      const v4f_u_t* __restrict__ row = g.row(min(m0 + (uint32_t)mm, M - 1));
       float4 x[Q];
 #pragma unroll
-      for (int k = 0; k < Q; ++k) x[k] = load_stream(row + v0 + (uint64_t)(k0 + k) * kWave);
+      for (int k = 0; k < Q; ++k) x[k] = load_row_stream(row + v0 + (uint64_t)(k0 + k) * kWave);
 #pragma unroll
       for (int k = 0; k < Q; ++k) {
         const double t0 = (double)normalize<NORM>(x[k].x, rt[k].r1.x, rt[k].r2.x);
@@ -1001,10 +1002,13 @@ inline int pick_workers_per_block(uint32_t M, uint64_t tiles) {
 // multiple of 4, else the largest multiple of 16 (whole packed words for either code width); the
 // scalar kernels finish the rest of each row.  0: scalar kernels only (the shared operands are not
 // 16-byte aligned).
+inline bool aligned16_or_null(const void* a, const void* b, const void* c = nullptr, const void* e = nullptr) {
+  auto al = [](const void* p) { return p == nullptr || (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+  return al(a) && al(b) && al(c) && al(e);
+}
 inline uint64_t vector_part(uint64_t d, const void* a, const void* b, const void* c = nullptr,
                             const void* e = nullptr) {
-  auto al = [](const void* p) { return p == nullptr || (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
-  if (!(al(a) && al(b) && al(c) && al(e))) return 0;
+  if (!aligned16_or_null(a, b, c, e)) return 0;
   return d % 4 == 0 ? d : d - d % 16;
 }
 
@@ -1234,25 +1238,33 @@ hipError_t tree_sum_launch(const CodecShape& c, const float* g, const float* gre
   double* group_sums = sums + 2 * nchunks * c.M;
   const uint32_t gx = (uint32_t)((nchunks + kWavesPerBlock - 1) / kWavesPerBlock);
   constexpr bool kSharedRef = NORM == kNormSub || NORM == kNormQuot || NORM == kNormComb;
-  if (SQUARE && kSharedRef && c.d % kTreeChunk == 0 && vec_ok(c.d, g, gref, gref2)) {
+  const uint64_t whole = c.d / kTreeChunk;  // chunks that lie inside the rows entirely
+  if (SQUARE && kSharedRef && whole != 0 && aligned16_or_null(gref, gref2)) {
+    const uint32_t gw = (uint32_t)((whole + kWavesPerBlock - 1) / kWavesPerBlock);
     int mc = 4;  // workers per workgroup that share the reference tile in registers
-    while (mc > 1 && (uint64_t)gx * ((c.M + mc - 1) / mc) < 2048) mc >>= 1;
-    const float4* g4 = reinterpret_cast<const float4*>(g);
+    while (mc > 1 && (uint64_t)gw * ((c.M + mc - 1) / mc) < 2048) mc >>= 1;
+    const GradRows rows{g, c.d};
     const float4* r4 = reinterpret_cast<const float4*>(gref);
     const float4* r24 = reinterpret_cast<const float4*>(gref2);
-    dim3 grid(gx, (c.M + mc - 1) / mc);
+    dim3 grid(gw, (c.M + mc - 1) / mc);
     if (mc == 4) {
-      hipLaunchKernelGGL((l2_chunk_kernel<kSharedRef ? NORM : kNormSub, 4>), grid, dim3(kBlock), 0, s, g4, r4, r24, sums,
-                         c.d / 4, nchunks, c.eps, c.M);
+      hipLaunchKernelGGL((l2_chunk_kernel<kSharedRef ? NORM : kNormSub, 4>), grid, dim3(kBlock), 0, s, rows, r4, r24, sums,
+                         whole, nchunks, c.eps, c.M);
     } else if (mc == 2) {
-      hipLaunchKernelGGL((l2_chunk_kernel<kSharedRef ? NORM : kNormSub, 2>), grid, dim3(kBlock), 0, s, g4, r4, r24, sums,
-                         c.d / 4, nchunks, c.eps, c.M);
+      hipLaunchKernelGGL((l2_chunk_kernel<kSharedRef ? NORM : kNormSub, 2>), grid, dim3(kBlock), 0, s, rows, r4, r24, sums,
+                         whole, nchunks, c.eps, c.M);
     } else {
-      hipLaunchKernelGGL((l2_chunk_kernel<kSharedRef ? NORM : kNormSub, 1>), grid, dim3(kBlock), 0, s, g4, r4, r24, sums,
-                         c.d / 4, nchunks, c.eps, c.M);
+      hipLaunchKernelGGL((l2_chunk_kernel<kSharedRef ? NORM : kNormSub, 1>), grid, dim3(kBlock), 0, s, rows, r4, r24, sums,
+                         whole, nchunks, c.eps, c.M);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (whole < nchunks) {  // the ragged last chunk of every row
+      hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, true, false>), dim3(1, c.M), dim3(kBlock), 0, s, g, gref, gref2,
+                         c.means, sums, minmax, c.d, whole, nchunks, c.eps, c.M, 1u);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL((tree_finish_kernel<false>), dim3(c.M), dim3(kBlock), 0, s, sums, group_sums, nullptr, nchunks,
                        ngroups, c.d, out, scales);
     return hipGetLastError();
@@ -1262,12 +1274,12 @@ hipError_t tree_sum_launch(const CodecShape& c, const float* g, const float* gre
   if (SQUARE && gref != nullptr)
     while (wpb < 8 && wpb < c.M && (uint64_t)gx * ((c.M + 2 * wpb - 1) / (2 * wpb)) >= 2048) wpb *= 2;
   dim3 grid(gx, (c.M + wpb - 1) / wpb);
-  if (vec_ok(c.d, g, gref, gref2)) {
+  if (aligned16_or_null(gref, gref2)) {
     hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, true, MINMAX>), grid, dim3(kBlock), 0, s, g, gref, gref2,
-                       c.means, sums, minmax, c.d, nchunks, c.eps, c.M, wpb);
+                       c.means, sums, minmax, c.d, (uint64_t)0, nchunks, c.eps, c.M, wpb);
   } else {
     hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, false, MINMAX>), grid, dim3(kBlock), 0, s, g, gref, gref2,
-                       c.means, sums, minmax, c.d, nchunks, c.eps, c.M, wpb);
+                       c.means, sums, minmax, c.d, (uint64_t)0, nchunks, c.eps, c.M, wpb);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
