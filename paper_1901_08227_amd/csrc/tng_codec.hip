@@ -981,15 +981,16 @@ inline uint32_t div_up_u32(uint64_t a, uint64_t b) {
 
 // Workers handled inside one workgroup (8, 4, 2 or 1; the last group of a row of workgroups may be
 // short).  A group reads the shared reference once, so fewer groups mean less traffic; a short group
-// costs the scale pass repeated loads of its last row (cache hits, weighted 0.3 of a row here).  At
-// least 2048 workgroups are kept to fill 256 compute units.
-inline int pick_workers_per_block(uint32_t M, uint64_t tiles) {
+// costs the scale pass repeated loads of its last row (cache hits: repeat_cost 0.3 of a row there,
+// nothing in the quantiser, which stops at the last worker).  At least 2048 workgroups are kept to
+// fill 256 compute units.
+inline int pick_workers_per_block(uint32_t M, uint64_t tiles, double repeat_cost) {
   int best = 1;
   double best_cost = (double)M;
   for (int mc = 2; mc <= 8; mc *= 2) {
     const uint32_t groups = (M + mc - 1) / mc;
     if (tiles * groups < 2048) break;
-    const double cost = groups + 0.3 * (groups * mc - M);
+    const double cost = groups + repeat_cost * (groups * mc - M);
     if (cost <= best_cost) {
       best = mc;
       best_cost = cost;
@@ -1039,7 +1040,7 @@ hipError_t absmax_dispatch(const CodecShape& c, const float* g, const float* gre
   hipError_t e;
   const uint64_t dv = vector_part(c.d, gref, gref2);
   if (dv != 0) {
-    const int mc = pick_workers_per_block(c.M, (dv / 4 + kBlock * kAbsmaxLoads - 1) / (kBlock * kAbsmaxLoads));
+    const int mc = pick_workers_per_block(c.M, (dv / 4 + kBlock * kAbsmaxLoads - 1) / (kBlock * kAbsmaxLoads), 0.3);
     switch (mc) {
       case 8: e = absmax_vec_launch<NORM, 8>(c, dv, g, gref, gref2, partials, &nblocks, s); break;
       case 4: e = absmax_vec_launch<NORM, 4>(c, dv, g, gref, gref2, partials, &nblocks, s); break;
@@ -1087,7 +1088,7 @@ hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g,
   const uint64_t dv = vector_part(c.d, gref, gref2);
   const bool vec = dv != 0;
   const uint64_t tiles = (dv / 4 + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
-  const int mc = vec ? pick_workers_per_block(c.M, tiles) : 1;
+  const int mc = vec ? pick_workers_per_block(c.M, tiles, 0.0) : 1;
   FusedScale fs{partials, fused_rows, scales};
   if (fused_rows > kFusedScaleRows || (fused_rows > 0 && (mc != 1 || dv != c.d))) {
     hipLaunchKernelGGL(absmax_finish_kernel, dim3(c.M), dim3(kBlock), 0, s, partials, fused_rows, c.M, scales);
