@@ -751,12 +751,13 @@ __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restr
                                                             const float* __restrict__ means,
                                                             double* __restrict__ chunk_sums,
                                                             float2* __restrict__ chunk_minmax, uint64_t d,
-                                                            uint64_t first_chunk, uint64_t nchunks, float eps,
-                                                            uint32_t M, uint32_t workers_per_block) {
+                                                            uint64_t first_chunk, uint64_t end_chunk,
+                                                            uint64_t nchunks, float eps, uint32_t M,
+                                                            uint32_t workers_per_block) {
   __shared__ double lanes[kWavesPerBlock][kTreeLanes];
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const uint64_t chunk = first_chunk + (uint64_t)blockIdx.x * kWavesPerBlock + wave;
-  if (chunk >= nchunks) return;  // whole wavefront; no workgroup barrier below
+  if (chunk >= end_chunk) return;  // whole wavefront; no workgroup barrier below
   const uint64_t base = chunk * kTreeChunk + 4u * (uint32_t)lane;
   constexpr int K = kTreeChunk / kTreeLanes;
   // A wavefront takes its chunk of several workers in turn: the reference tile of the chunk is then
@@ -768,10 +769,10 @@ __global__ __launch_bounds__(kBlock) void tree_chunk_kernel(const float* __restr
   const float mu = (SQUARE && NORM == kNormMean) ? means[m] : 0.f;
   double acc[4] = {0.0, 0.0, 0.0, 0.0};
   float lo = INFINITY, hi = -INFINITY;
-  const bool full = (chunk + 1) * kTreeChunk <= d;
-  // 16-byte loads (the row may start at any 4-byte boundary); the last chunk of a row whose length is
-  // not a multiple of 4 goes element by element
-  if (VEC && (full || d % 4 == 0)) {
+  // VEC: 16-byte loads (the row may start at any 4-byte boundary).  The caller keeps the last chunk of
+  // rows whose length is not a multiple of 4 away from this variant.
+  if (VEC) {
+    const bool full = (chunk + 1) * kTreeChunk <= d;
     // loads in batches: all 16 rows of the chunk at once, or 8 rows plus their reference tiles
     constexpr bool kHasRef = SQUARE && (NORM == kNormSub || NORM == kNormQuot || NORM == kNormComb);
     constexpr int KB = kHasRef ? 8 : K;
@@ -1261,8 +1262,13 @@ hipError_t tree_sum_launch(const CodecShape& c, const float* g, const float* gre
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (whole < nchunks) {  // the ragged last chunk of every row
-      hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, true, false>), dim3(1, c.M), dim3(kBlock), 0, s, g, gref, gref2,
-                         c.means, sums, minmax, c.d, whole, nchunks, c.eps, c.M, 1u);
+      if (c.d % 4 == 0) {
+        hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, true, false>), dim3(1, c.M), dim3(kBlock), 0, s, g, gref,
+                           gref2, c.means, sums, minmax, c.d, whole, nchunks, nchunks, c.eps, c.M, 1u);
+      } else {
+        hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, false, false>), dim3(1, c.M), dim3(kBlock), 0, s, g, gref,
+                           gref2, c.means, sums, minmax, c.d, whole, nchunks, nchunks, c.eps, c.M, 1u);
+      }
       e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
@@ -1276,11 +1282,17 @@ hipError_t tree_sum_launch(const CodecShape& c, const float* g, const float* gre
     while (wpb < 8 && wpb < c.M && (uint64_t)gx * ((c.M + 2 * wpb - 1) / (2 * wpb)) >= 2048) wpb *= 2;
   dim3 grid(gx, (c.M + wpb - 1) / wpb);
   if (aligned16_or_null(gref, gref2)) {
-    hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, true, MINMAX>), grid, dim3(kBlock), 0, s, g, gref, gref2,
-                       c.means, sums, minmax, c.d, (uint64_t)0, nchunks, c.eps, c.M, wpb);
+    // the last chunk of rows whose length is not a multiple of 4 goes element by element
+    const uint64_t vec_end = c.d % 4 == 0 ? nchunks : whole;
+    if (vec_end != 0)
+      hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, true, MINMAX>), grid, dim3(kBlock), 0, s, g, gref, gref2,
+                         c.means, sums, minmax, c.d, (uint64_t)0, vec_end, nchunks, c.eps, c.M, wpb);
+    if (vec_end != nchunks)
+      hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, false, MINMAX>), dim3(1, c.M), dim3(kBlock), 0, s, g, gref,
+                         gref2, c.means, sums, minmax, c.d, vec_end, nchunks, nchunks, c.eps, c.M, 1u);
   } else {
     hipLaunchKernelGGL((tree_chunk_kernel<NORM, SQUARE, false, MINMAX>), grid, dim3(kBlock), 0, s, g, gref, gref2,
-                       c.means, sums, minmax, c.d, (uint64_t)0, nchunks, c.eps, c.M, wpb);
+                       c.means, sums, minmax, c.d, (uint64_t)0, nchunks, nchunks, c.eps, c.M, wpb);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
