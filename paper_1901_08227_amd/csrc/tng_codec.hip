@@ -164,10 +164,8 @@ __global__ __launch_bounds__(kBlock) void absmax_finish_kernel(const float* __re
 }
 
 // The M gradient rows as the vector kernels read them.  Row m starts m * pitch floats into the array;
-// the pitch (= d) need not be a multiple of 4, so a row may start at any 4-byte boundary.  16-byte
-// loads from such addresses are legal for global memory on this target (the type below only tells
-// the compiler not to assume more than 4-byte alignment; the instruction is the same).
-typedef float v4f_u_t __attribute__((ext_vector_type(4), aligned(4)));
+// the pitch (= d) need not be a multiple of 4, so a row may start at any 4-byte boundary (hence the
+// 16-byte loads that assume 4-byte alignment only).
 struct GradRows {
   const float* base;
   uint64_t pitch;

@@ -54,6 +54,25 @@ __device__ __forceinline__ float4 load4(GlobalPtr<float> p, uint64_t i) {
   return make_float4(v.x, v.y, v.z, v.w);
 }
 
+// 16 bytes at a 4-byte aligned address: rows of d floats start anywhere when d is not a multiple of
+// 4.  Such loads and stores are legal for global memory on this target; the type only tells the
+// compiler not to assume more alignment than there is (the instruction is the same).
+typedef float v4f_u_t __attribute__((ext_vector_type(4), aligned(4)));
+
+__device__ __forceinline__ float4 load4_stream_any(GlobalPtr<float> p, uint64_t i) {
+  const v4f_u_t v = __builtin_nontemporal_load(reinterpret_cast<GlobalPtr<v4f_u_t>>(p) + i);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ void store4_any(float* p, uint64_t i, const float4& x) {
+  v4f_u_t v;
+  v.x = x.x;
+  v.y = x.y;
+  v.z = x.z;
+  v.w = x.w;
+  reinterpret_cast<v4f_u_t*>(p)[i] = v;
+}
+
 // The same as a streaming (non-temporal) load: shard rows are touched once per pass.
 __device__ __forceinline__ float4 load4_stream(GlobalPtr<float> p, uint64_t i) {
   const v4f_t v = __builtin_nontemporal_load(reinterpret_cast<GlobalPtr<v4f_t>>(p) + i);

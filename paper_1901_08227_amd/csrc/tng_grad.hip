@@ -116,12 +116,18 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_resid_kernel(const float*
       const float4 wv = w4[k];
 #pragma unroll
       for (int r = 0; r < ROWS; ++r) {
-        const float4 xv = load4_stream(x[r], k);
+        const float4 xv = load4_stream_any(x[r], k);
         a0[r] = __builtin_fmaf(xv.x, wv.x, a0[r]);
         a1[r] = __builtin_fmaf(xv.y, wv.y, a1[r]);
         a2[r] = __builtin_fmaf(xv.z, wv.z, a2[r]);
         a3[r] = __builtin_fmaf(xv.w, wv.w, a3[r]);
       }
+    }
+    if (4 * nvec + threadIdx.x < d) {  // the last d mod 4 columns
+      const uint64_t k = 4 * nvec + threadIdx.x;
+      const float wk = w[k];
+#pragma unroll
+      for (int r = 0; r < ROWS; ++r) a0[r] = __builtin_fmaf(x[r][k], wk, a0[r]);
     }
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) acc[r] = (a0[r] + a1[r]) + (a2[r] + a3[r]);
@@ -150,14 +156,14 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
                                                                    const float* __restrict__ resid,
                                                                    const float* __restrict__ w,
                                                                    float* __restrict__ g, uint64_t d,
-                                                                   uint32_t batch, float inv_b, float l2,
-                                                                   ScaleFusion fuse) {
+                                                                   uint64_t first_col, uint32_t batch, float inv_b,
+                                                                   float l2, ScaleFusion fuse) {
   __shared__ float sR[kBlock];
   __shared__ uint32_t sRow[kBlock];
   __shared__ float red[16];
   const uint32_t m = blockIdx.y;
   const GlobalPtr<float> X = as_global(Xs[m]);
-  const uint64_t col = (uint64_t)blockIdx.x * kBlock + threadIdx.x;  // float4 (VEC) or float index
+  const uint64_t col = first_col + (uint64_t)blockIdx.x * kBlock + threadIdx.x;  // float4 (VEC) or float index
   const uint64_t ncol = VEC ? d / 4 : d;
   const bool active = col < ncol;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -173,7 +179,7 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
       if (VEC) {
 #pragma unroll 8
         for (uint32_t i = 0; i < cnt; ++i) {
-          const float4 xv = load4_stream(X + (uint64_t)sRow[i] * d, col);
+          const float4 xv = load4_stream_any(X + (uint64_t)sRow[i] * d, col);
           const float r = sR[i];
           acc.x = __builtin_fmaf(r, xv.x, acc.x);
           acc.y = __builtin_fmaf(r, xv.y, acc.y);
@@ -195,7 +201,7 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
       o.y = __builtin_fmaf(l2, wv.y, acc.y * inv_b);
       o.z = __builtin_fmaf(l2, wv.z, acc.z * inv_b);
       o.w = __builtin_fmaf(l2, wv.w, acc.w * inv_b);
-      reinterpret_cast<float4*>(g + (uint64_t)m * d)[col] = o;
+      store4_any(g + (uint64_t)m * d, col, o);
       if (FUSE) {
         float4 r1, r2;
         load_refs4(fuse, col, r1, r2);
@@ -722,9 +728,10 @@ __device__ __forceinline__ float4 gaussian4(const NoiseGen& gen, uint64_t block,
 
 __global__ __launch_bounds__(kBlock) void rosenbrock_kernel(const float* __restrict__ x,
                                                             const float* __restrict__ noise, NoiseGen gen,
-                                                            float* __restrict__ g, uint64_t d, uint32_t M) {
+                                                            float* __restrict__ g, uint64_t first, uint64_t d,
+                                                            uint32_t M) {
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < d; i += stride) {
+  for (uint64_t i = first + (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < d; i += stride) {
     const float base = rosenbrock_component(i > 0 ? x[i - 1] : 0.f, x[i], i + 1 < d ? x[i + 1] : 0.f, i > 0, i + 1 < d);
     for (uint32_t m = 0; m < M; ++m) {
       const uint64_t o = (uint64_t)m * d + i;
@@ -739,20 +746,22 @@ __global__ __launch_bounds__(kBlock) void rosenbrock_kernel(const float* __restr
   }
 }
 
-// d a multiple of 4, 16-byte aligned operands: a thread owns 4 consecutive coordinates; the gradient
-// is computed once and reused for all workers, the noise is streamed with 16-byte loads.
+// The first 4 * (d / 4) coordinates: a thread owns 4 consecutive ones; the gradient is computed once
+// and reused for all workers, the noise is streamed with 16-byte loads (rows of noise and g start at
+// any 4-byte boundary when d is not a multiple of 4).
 template <bool FUSE>
 __global__ __launch_bounds__(kBlock) void rosenbrock_vec_kernel(const float* __restrict__ x,
-                                                                const float4* __restrict__ noise4, NoiseGen gen,
-                                                                float4* __restrict__ g4, uint64_t nvec, uint32_t M,
+                                                                const float* __restrict__ noise, NoiseGen gen,
+                                                                float* __restrict__ g, uint64_t d, uint32_t M,
                                                                 ScaleFusion fuse) {
   __shared__ float red[16];
+  const uint64_t nvec = d / 4;
   const uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   const bool active = q < nvec;
   float4 base = make_float4(0.f, 0.f, 0.f, 0.f), r1 = base, r2 = base;
   if (active) {
     const float4 xv = reinterpret_cast<const float4*>(x)[q];
-    const bool first = q == 0, last = q + 1 == nvec;
+    const bool first = q == 0, last = 4 * q + 4 >= d;
     const float xl = first ? 0.f : x[4 * q - 1];
     const float xr = last ? 0.f : x[4 * q + 4];
     base.x = rosenbrock_component(xl, xv.x, xv.y, !first, true);
@@ -765,14 +774,14 @@ __global__ __launch_bounds__(kBlock) void rosenbrock_vec_kernel(const float* __r
     float amax = 0.f;
     if (active) {
       float4 o = base;
-      if (gen.sigma > 0.f || noise4 != nullptr) {
-        const float4 n = gen.sigma > 0.f ? gaussian4(gen, q, m) : load_stream(noise4 + (uint64_t)m * nvec + q);
+      if (gen.sigma > 0.f || noise != nullptr) {
+        const float4 n = gen.sigma > 0.f ? gaussian4(gen, q, m) : load4_stream_any(as_global(noise) + (uint64_t)m * d, q);
         o.x = base.x + n.x;
         o.y = base.y + n.y;
         o.z = base.z + n.z;
         o.w = base.w + n.w;
       }
-      g4[(uint64_t)m * nvec + q] = o;
+      store4_any(g + (uint64_t)m * d, q, o);
       if (FUSE) amax = absmax4(fuse, o, r1, r2);
     }
     if (FUSE) {
@@ -798,8 +807,10 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
                                     const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
                                     hipStream_t s) {
   if (fused_rows != nullptr) *fused_rows = 0;
-  // Shards are required to be 16-byte aligned; rows stay aligned only when d is a multiple of 4.
-  const bool vec = d % 4 == 0 && aligned16(w) && aligned16(g);
+  // Rows of X and of g start at any 4-byte boundary when d is not a multiple of 4: the vector kernels
+  // read and write them with 16-byte accesses that assume no more, over the first 4 * (d / 4) columns.
+  const bool vec = d >= 4 && aligned16(w);
+  const bool whole = d % 4 == 0;
   const float inv_b = 1.0f / (float)batch;
   dim3 grid_r(batch, M);
   if (vec && (uint64_t)M * (batch / 4) >= 1024) {  // enough rows to keep the chip busy four at a time
@@ -811,9 +822,11 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
   }
   if (vec) {
     dim3 grid_g((uint32_t)((d / 4 + kBlock - 1) / kBlock), M);
-    const bool can_fuse = fuse != nullptr && fused_rows != nullptr && grid_g.x <= kAbsmaxMaxBlocks &&
+    // the fused scale pass sees the vector part only, so it needs all of d there
+    const bool can_fuse = whole && fuse != nullptr && fused_rows != nullptr && grid_g.x <= kAbsmaxMaxBlocks &&
                           aligned16(fuse->gref) && aligned16(fuse->gref2);
-    if ((uint64_t)grid_g.x * M <= 128 && batch >= 4 * kRowGroups) {  // a handful of workgroups: split the rows
+    if (whole && aligned16(g) && (uint64_t)grid_g.x * M <= 128 && batch >= 4 * kRowGroups) {
+      // a handful of workgroups: split the rows
       if (can_fuse) {
         hipLaunchKernelGGL((logreg_dense_grad_split_kernel<true>), grid_g, dim3(kBlock * kRowGroups), 0, s, p.X, idx, resid,
                            w, g, d, batch, inv_b, l2, *fuse);
@@ -824,21 +837,23 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
       }
       return hipGetLastError();
     }
-    if (fuse != nullptr && fused_rows != nullptr && grid_g.x <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
-        aligned16(fuse->gref2)) {
+    if (can_fuse) {
       hipLaunchKernelGGL((logreg_dense_grad_kernel<true, true>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
-                         batch, inv_b, l2, *fuse);
+                         (uint64_t)0, batch, inv_b, l2, *fuse);
       *fused_rows = grid_g.x;
     } else {
       hipLaunchKernelGGL((logreg_dense_grad_kernel<true, false>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
-                         batch, inv_b, l2, ScaleFusion{});
+                         (uint64_t)0, batch, inv_b, l2, ScaleFusion{});
     }
+    if (!whole)  // the last d mod 4 columns
+      hipLaunchKernelGGL((logreg_dense_grad_kernel<false, false>), dim3(1, M), dim3(kBlock), 0, s, p.X, idx, resid, w, g,
+                         d, 4 * (d / 4), batch, inv_b, l2, ScaleFusion{});
   } else {
     hipLaunchKernelGGL((logreg_dense_resid_kernel<false, 1>), grid_r, dim3(kBlock), 0, s, p.X, p.y, p.n_rows, idx, w,
                        resid, d, batch, k0, k1, iter);
     dim3 grid_g((uint32_t)((d + kBlock - 1) / kBlock), M);
     hipLaunchKernelGGL((logreg_dense_grad_kernel<false, false>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
-                       batch, inv_b, l2, ScaleFusion{});
+                       (uint64_t)0, batch, inv_b, l2, ScaleFusion{});
   }
   return hipGetLastError();
 }
@@ -915,24 +930,25 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
 hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, NoiseGen gen, float* g,
                                   const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s) {
   if (fused_rows != nullptr) *fused_rows = 0;
-  if (d % 4 == 0 && aligned16(x) && aligned16(noise) && aligned16(g)) {
+  if (d >= 4 && aligned16(x)) {
     const uint64_t nvec = d / 4;
     const uint32_t blocks = (uint32_t)((nvec + kBlock - 1) / kBlock);
-    if (fuse != nullptr && fused_rows != nullptr && blocks <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
+    // the fused scale pass sees the vector part only, so it needs all of d there
+    if (d % 4 == 0 && fuse != nullptr && fused_rows != nullptr && blocks <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
         aligned16(fuse->gref2)) {
-      hipLaunchKernelGGL(rosenbrock_vec_kernel<true>, dim3(blocks), dim3(kBlock), 0, s, x,
-                         reinterpret_cast<const float4*>(noise), gen, reinterpret_cast<float4*>(g), nvec, M, *fuse);
+      hipLaunchKernelGGL(rosenbrock_vec_kernel<true>, dim3(blocks), dim3(kBlock), 0, s, x, noise, gen, g, d, M, *fuse);
       *fused_rows = blocks;
     } else {
-      hipLaunchKernelGGL(rosenbrock_vec_kernel<false>, dim3(blocks), dim3(kBlock), 0, s, x,
-                         reinterpret_cast<const float4*>(noise), gen, reinterpret_cast<float4*>(g), nvec, M,
+      hipLaunchKernelGGL(rosenbrock_vec_kernel<false>, dim3(blocks), dim3(kBlock), 0, s, x, noise, gen, g, d, M,
                          ScaleFusion{});
     }
+    if (d % 4 != 0)  // the last d mod 4 coordinates
+      hipLaunchKernelGGL(rosenbrock_kernel, dim3(1), dim3(kBlock), 0, s, x, noise, gen, g, 4 * nvec, d, M);
     return hipGetLastError();
   }
   const uint64_t bx = (d + kBlock - 1) / kBlock;
   hipLaunchKernelGGL(rosenbrock_kernel, dim3((uint32_t)(bx < 16384 ? bx : 16384)), dim3(kBlock), 0, s, x, noise, gen,
-                     g, d, M);
+                     g, (uint64_t)0, d, M);
   return hipGetLastError();
 }
 
