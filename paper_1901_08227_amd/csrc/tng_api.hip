@@ -140,10 +140,20 @@ inline void mark(tng_ctx* ctx, uint64_t call, int which) {
   if (ctx->prof_slots != 0) (void)hipEventRecord(ctx->prof[5 * (call % ctx->prof_slots) + which], ctx->stream);
 }
 
+// The single-workgroup path for tiny problems (see launch_single_pass).  Not taken while timing events
+// are recorded: they mark the separate passes.
+bool single_pass_ok(const tng_ctx* ctx, const float* g, const float* gref, const float* vbar, const float* w,
+                    const float* ref_out) {
+  return ctx->prof_slots == 0 && tng::single_pass_applies(ctx->shape, g, gref, ctx->gref2, vbar, w, ref_out);
+}
+
 // fused_rows > 0: a gradient kernel has already left that many rows of partial maxima in the
 // workspace, only their reduction remains of the scale pass.
 tng_status encode_impl(tng_ctx* ctx, uint32_t iter, const float* g, const float* gref, uint32_t* codes,
                        float* scales, uint32_t fused_rows = 0) {
+  if (fused_rows == 0 && single_pass_ok(ctx, g, gref, nullptr, nullptr, nullptr))  // tiny problems: one launch
+    return hip_status(tng::launch_single_pass(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, false, nullptr,
+                                              nullptr, 0.f, nullptr, ctx->stream));
   const uint64_t call = ctx->enc_calls++;
   mark(ctx, call, 0);
   hipError_t e = hipSuccess;
@@ -494,29 +504,37 @@ tng_status tng_step(tng_ctx* ctx, uint32_t iter, float* w, float* gref, float* g
   if (ctx->cfg.ref_policy == TNG_REF_WINDOW_AVG && ctx->history == nullptr) return TNG_ERR_BAD_STATE;
   if (ctx->cfg.problem == TNG_PROB_LOGREG_DENSE && !ctx->have_dense) return TNG_ERR_BAD_STATE;
   if (ctx->cfg.problem == TNG_PROB_LOGREG_CSR && !ctx->have_csr) return TNG_ERR_BAD_STATE;
+  const tng_config& c = ctx->cfg;
+  const bool window = c.ref_policy == TNG_REF_WINDOW_AVG;
+  const uint32_t slot = window ? iter % c.ref_window : 0u;
+  // where the decode pass leaves a second copy of the decoded average: its slot of the history ring
+  // (window average), or the reference itself when it is refreshed now (last average)
+  float* ref_out = window ? ctx->history + (uint64_t)slot * c.d : (refresh_now(c, iter) ? gref : nullptr);
+  // tiny problems: everything after the gradient in one launch
+  const bool single = single_pass_ok(ctx, g, gref, vbar, w, ref_out);
   uint32_t fused_rows = 0;
-  if (ctx->cfg.problem != TNG_PROB_EXTERNAL) {
-    const tng::ScaleFusion fuse{ctx->cfg.norm, ctx->cfg.quot_eps, gref, ctx->gref2, ctx->partials};
+  if (c.problem != TNG_PROB_EXTERNAL) {
+    const tng::ScaleFusion fuse{c.norm, c.quot_eps, gref, ctx->gref2, ctx->partials};
     // the maximum can ride along with the gradient kernel; a scale that needs the row mean or an
     // ordered sum cannot
-    const bool can_fuse = ctx->cfg.norm != TNG_NORM_MEAN && ctx->cfg.scale == TNG_SCALE_MAX;
+    const bool can_fuse = !single && c.norm != TNG_NORM_MEAN && c.scale == TNG_SCALE_MAX;
     s = local_grad_impl(ctx, iter, w, g, can_fuse ? &fuse : nullptr, can_fuse ? &fused_rows : nullptr);
     if (s != TNG_OK) return s;
   }
-  s = encode_impl(ctx, iter, g, gref, codes, scales, fused_rows);
-  if (s != TNG_OK) return s;
-  if (ctx->cfg.ref_policy == TNG_REF_WINDOW_AVG) {
-    // the decode pass also leaves the decoded average in its slot of the history ring
-    const tng_config& c = ctx->cfg;
-    const uint32_t slot = iter % c.ref_window;
-    s = decode_impl(ctx, codes, scales, gref, vbar, w, ctx->history + (uint64_t)slot * c.d);
+  if (single) {
+    s = hip_status(tng::launch_single_pass(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, true, vbar, w, c.lr,
+                                           ref_out, ctx->stream));
     if (s != TNG_OK) return s;
-    if (!refresh_now(c, iter)) return TNG_OK;
+  } else {
+    s = encode_impl(ctx, iter, g, gref, codes, scales, fused_rows);
+    if (s != TNG_OK) return s;
+    s = decode_impl(ctx, codes, scales, gref, vbar, w, ref_out);
+    if (s != TNG_OK) return s;
+  }
+  if (window && refresh_now(c, iter))
     return hip_status(tng::launch_window_mean(ctx->history, c.ref_window, (slot + 1) % c.ref_window, c.d, gref,
                                               ctx->stream));
-  }
-  float* ref_out = refresh_now(ctx->cfg, iter) ? gref : nullptr;  // last-average policy: fused into the decode pass
-  return decode_impl(ctx, codes, scales, gref, vbar, w, ref_out);
+  return TNG_OK;
 }
 
 }  // extern "C"

@@ -691,6 +691,137 @@ __global__ __launch_bounds__(kBlock) void decode_vec_kernel(
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// One workgroup for tiny problems (d <= 4 * kBlock): scale, quantise and pack, and (DECODE) the
+// server side as well, in one launch.
+//
+// A thread owns one float4 of coordinates of every worker (M <= MC rows in registers), so once the
+// M scales are known -- a workgroup reduction -- it can code its values, and since it then holds all
+// M codes of its coordinates it can decode, average, de-normalise and update them without reading
+// anything back.  Such problems are bound by the latency of their launches (about 4 us each), not
+// by bytes.
+// The same kernel over several workgroups, with the maxima exchanged through device-scope atomics
+// and a meeting point (bounded wait, grid checked against the occupancy), was measured too: it wins
+// up to 16 workgroups (16.6 -> 15.5 us per iteration at d = 2^14, M = 8) and loses beyond (d = 2^20,
+// M = 8: 32 -> 56 us): with eight compute dies, each with its own L2, every arrival and every flag
+// is an access to memory-side atomics, about 25 us for a full meeting of 128 or more workgroups.
+// ------------------------------------------------------------------------------------------
+constexpr int kSinglePassMaxWorkers = 16;
+
+template <int NORM, int BITS, int MC, bool DECODE>
+__global__ __launch_bounds__(kBlock) void single_pass_kernel(
+    GradRows g, const float4* ref4, const float4* __restrict__ ref24, float* __restrict__ scales,
+    uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words, uint32_t M, float eps, uint32_t k0, uint32_t k1,
+    uint32_t iter, float4* __restrict__ vbar4, float4* w4, float4* refout4, float inv_m, float lr) {
+  constexpr int WPB = kBlock * 4 * BITS / 32;  // packed words per workgroup and worker
+  constexpr uint32_t MASK = (1u << BITS) - 1u;
+  constexpr float S = (float)((1 << (BITS - 1)) - 1);
+  __shared__ float red[MC][kWavesPerBlock];
+  __shared__ float sScale[MC];
+  __shared__ union {
+    lds_u8 b8[MC][WPB * 4];
+    lds_u16 b16[MC][WPB * 2];
+    lds_u32 b32[MC][WPB];
+  } buf;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const uint64_t q = threadIdx.x;  // one workgroup
+  const bool active = q < nvec;
+
+  RefTile<NORM> rt;
+  rt.r1 = rt.r2 = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 x[MC];
+  float amax[MC];
+  if (active) {
+    rt.template load<false>(ref4, ref24, q, eps);
+#pragma unroll
+    for (int mm = 0; mm < MC; ++mm)  // rows past M repeat the last one: all loads in flight, none under a condition
+      x[mm] = load_row_stream(g.row(min((uint32_t)mm, M - 1)) + q);
+  }
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) {
+    amax[mm] = 0.f;
+    if (active) {
+      const float a0 = fabsf(normalize<NORM>(x[mm].x, rt.r1.x, rt.r2.x));
+      const float a1 = fabsf(normalize<NORM>(x[mm].y, rt.r1.y, rt.r2.y));
+      const float a2 = fabsf(normalize<NORM>(x[mm].z, rt.r1.z, rt.r2.z));
+      const float a3 = fabsf(normalize<NORM>(x[mm].w, rt.r1.w, rt.r2.w));
+      amax[mm] = fmaxf(fmaxf(a0, a1), fmaxf(a2, a3));
+    }
+    const float v = wave_max(amax[mm]);
+    if (lane == 0) red[mm][wave] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < M) {
+    float v = red[threadIdx.x][0];
+#pragma unroll
+    for (int k = 1; k < kWavesPerBlock; ++k) v = fmaxf(v, red[threadIdx.x][k]);
+    v = v < FLT_MIN ? 0.f : v;
+    sScale[threadIdx.x] = v;
+    scales[threadIdx.x] = v;
+  }
+  __syncthreads();
+
+  uint32_t frag[MC];
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) {
+    frag[mm] = 0u;
+    if ((uint32_t)mm < M) {
+      const float R = sScale[mm];
+      if (active && R != 0.f) {
+        const float inv_r = 1.0f / R;
+        const U32x4 rnd = philox4x32_10((uint32_t)q, (uint32_t)mm, iter, 0u, k0, k1);
+        const uint32_t c0 = quantize_code<BITS>(normalize<NORM>(x[mm].x, rt.r1.x, rt.r2.x), inv_r, rnd.x);
+        const uint32_t c1 = quantize_code<BITS>(normalize<NORM>(x[mm].y, rt.r1.y, rt.r2.y), inv_r, rnd.y);
+        const uint32_t c2 = quantize_code<BITS>(normalize<NORM>(x[mm].z, rt.r1.z, rt.r2.z), inv_r, rnd.z);
+        const uint32_t c3 = quantize_code<BITS>(normalize<NORM>(x[mm].w, rt.r1.w, rt.r2.w), inv_r, rnd.w);
+        frag[mm] = c0 | (c1 << BITS) | (c2 << (2 * BITS)) | (c3 << (3 * BITS));
+      }
+      if (BITS == 2) {
+        buf.b8[mm][threadIdx.x] = (uint8_t)frag[mm];
+      } else {
+        buf.b16[mm][threadIdx.x] = (uint16_t)frag[mm];
+      }
+    }
+  }
+  __syncthreads();
+  for (uint32_t t = threadIdx.x; t < M * (uint32_t)WPB; t += kBlock) {
+    const uint32_t mm = t / WPB, j = t % WPB;
+    const uint64_t wi = j;
+    if (wi < words) store_word_through(codes + (uint64_t)mm * words + wi, buf.b32[mm][j]);
+  }
+
+  if (DECODE && active) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int mm = 0; mm < MC; ++mm) {
+      if ((uint32_t)mm < M) {
+        const float R = sScale[mm], step = R / S;
+        const uint32_t f = frag[mm];
+        acc.x = acc.x + decode_code<BITS>(f & MASK, R, step);
+        acc.y = acc.y + decode_code<BITS>((f >> BITS) & MASK, R, step);
+        acc.z = acc.z + decode_code<BITS>((f >> (2 * BITS)) & MASK, R, step);
+        acc.w = acc.w + decode_code<BITS>((f >> (3 * BITS)) & MASK, R, step);
+      }
+    }
+    float4 o;
+    o.x = denormalize<NORM>(acc.x * inv_m, rt.r1.x, rt.r2.x);
+    o.y = denormalize<NORM>(acc.y * inv_m, rt.r1.y, rt.r2.y);
+    o.z = denormalize<NORM>(acc.z * inv_m, rt.r1.z, rt.r2.z);
+    o.w = denormalize<NORM>(acc.w * inv_m, rt.r1.w, rt.r2.w);
+    store_stream(vbar4 + q, o);
+    if (w4 != nullptr) {
+      float4 w = load_stream(w4 + q);
+      const float px = lr * o.x, py = lr * o.y, pz = lr * o.z, pw = lr * o.w;
+      w.x = w.x - px;
+      w.y = w.y - py;
+      w.z = w.z - pz;
+      w.w = w.w - pw;
+      w4[q] = w;
+    }
+    if (refout4 != nullptr) refout4[q] = o;
+  }
+}
+
 template <int NORM, int BITS>
 __global__ __launch_bounds__(kBlock) void decode_scalar_kernel(
     const uint32_t* __restrict__ codes, const float* __restrict__ scales, const float* ref,
@@ -1331,6 +1462,55 @@ hipError_t launch_quantize_pack(const CodecShape& c, uint32_t iter, const float*
     default: TNG_Q(kNormComb, gref, gref2);
   }
 #undef TNG_Q
+}
+
+namespace {
+template <int NORM, int BITS>
+hipError_t single_pass_dispatch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                                const float* gref2, float* scales, uint32_t* codes, bool decode, float* vbar,
+                                float* w, float lr, float* ref_out, hipStream_t s) {
+#define TNG_SP(MC, DEC)                                                                                             \
+  hipLaunchKernelGGL((single_pass_kernel<NORM, BITS, MC, DEC>), dim3(1), dim3(kBlock), 0, s, GradRows{g, c.d},       \
+                     reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), scales, codes,   \
+                     c.d / 4, c.words, c.M, c.eps, c.k0, c.k1, iter, reinterpret_cast<float4*>(vbar),                \
+                     reinterpret_cast<float4*>(w), reinterpret_cast<float4*>(ref_out), 1.0f / (float)c.M, lr)
+  if (c.M <= 8) {
+    if (decode) {
+      TNG_SP(8, true);
+    } else {
+      TNG_SP(8, false);
+    }
+  } else if (decode) {
+    TNG_SP(16, true);
+  } else {
+    TNG_SP(16, false);
+  }
+#undef TNG_SP
+  return hipGetLastError();
+}
+}  // namespace
+
+bool single_pass_applies(const CodecShape& c, const float* g, const float* gref, const float* gref2, const float* vbar,
+                         const float* w, const float* ref_out) {
+  return c.scale_l2 == 0 && c.norm != kNormMean && c.d % 4 == 0 && c.d <= 4 * (uint64_t)kBlock &&
+         c.M <= (uint32_t)kSinglePassMaxWorkers && aligned16_or_null(g, gref, gref2) &&
+         aligned16_or_null(vbar, w, ref_out);
+}
+
+hipError_t launch_single_pass(const CodecShape& c, uint32_t iter, const float* g, const float* gref, const float* gref2,
+                              float* scales, uint32_t* codes, bool decode, float* vbar, float* w, float lr,
+                              float* ref_out, hipStream_t s) {
+  if (!single_pass_applies(c, g, gref, gref2, vbar, w, ref_out)) return hipErrorInvalidValue;
+#define TNG_SPD(NORM, R1, R2)                                                                                        \
+  return c.bits == 2 ? single_pass_dispatch<NORM, 2>(c, iter, g, R1, R2, scales, codes, decode, vbar, w, lr, ref_out, s) \
+                     : single_pass_dispatch<NORM, 4>(c, iter, g, R1, R2, scales, codes, decode, vbar, w, lr, ref_out, s)
+  switch (c.norm) {
+    case kNormNone: TNG_SPD(kNormNone, nullptr, nullptr);
+    case kNormSub: TNG_SPD(kNormSub, gref, nullptr);
+    case kNormQuot: TNG_SPD(kNormQuot, gref, nullptr);
+    default: TNG_SPD(kNormComb, gref, gref2);
+  }
+#undef TNG_SPD
 }
 
 hipError_t launch_decode(const CodecShape& c, const uint32_t* codes, const float* scales, const float* gref,

@@ -72,6 +72,16 @@ hipError_t launch_decode(const CodecShape& c, const uint32_t* codes, const float
                          const float* gref, const float* gref2, float* vbar, float* w, float lr,
                          float* ref_out, hipStream_t s);
 
+// Tiny problems (d <= 1024 and a multiple of 4, M <= 16, largest-magnitude scale, no per-worker mean,
+// 16-byte aligned operands): scale, quantise and pack in ONE single-workgroup launch, and with
+// decode = true the decode / average / de-normalise / update pass as well (vbar, w, ref_out as for
+// launch_decode).  single_pass_applies tells whether launch_single_pass may be called.
+bool single_pass_applies(const CodecShape& c, const float* g, const float* gref, const float* gref2, const float* vbar,
+                         const float* w, const float* ref_out);
+hipError_t launch_single_pass(const CodecShape& c, uint32_t iter, const float* g, const float* gref, const float* gref2,
+                              float* scales, uint32_t* codes, bool decode, float* vbar, float* w, float lr,
+                              float* ref_out, hipStream_t s);
+
 struct LogregData {
   const float* const* X;        // device table [M] of dense shards (dense problem)
   const int64_t* const* rowptr; // device tables [M] (CSR problem)

@@ -506,3 +506,46 @@ def test_resume_from_saved_state_reproduces_the_run():
         ctx.close()
     for a, b in zip(runs[0], runs[1]):
         assert torch.equal(a, b)
+
+
+def test_tiny_problem_one_workgroup_equals_separate_passes():
+    # d <= 1024 (a multiple of 4), M <= 16: everything after the gradient is one single-workgroup launch,
+    # unless timing events are being recorded -- they mark the separate passes, which then run instead.
+    # Both ways give the same bits (each is also compared with the oracle by the other tests).
+    import bench
+    cases = [(1000, 4, 2, B.NORM_SUB), (1024, 16, 4, B.NORM_QUOT), (36, 3, 2, B.NORM_COMB), (512, 9, 4, B.NORM_NONE),
+             (4, 1, 2, B.NORM_SUB)]
+    for d, M, bits, norm in cases:
+        say(f"one workgroup against separate passes d={d} M={M} bits={bits} norm={norm}")
+        outs = []
+        for separate in (False, True):
+            ctx = make_ctx(d, M, bits, norm, seed=13, lr=1e-5, ref_period=2, problem=B.PROB_ROSENBROCK)
+            ev = None
+            if separate:
+                ev = bench.HipEvents(5)
+                ctx.set_profile_events(ev.ev, 1)
+            if norm == B.NORM_COMB:
+                gref2 = torch.rand(d, generator=torch.Generator(device=DEV).manual_seed(3), device=DEV) + 0.5
+                ctx.set_second_reference(gref2)
+            x = synth.rosenbrock_start(d, 6, device=DEV)
+            gref = 0.1 * synth.rosenbrock_start(d, 7, device=DEV)
+            buf = buffers(ctx)
+            trace = []
+            for it in range(3):
+                ctx.set_noise(synth.gradient_noise(M, d, 5, it, device=DEV))
+                ctx.step(it, x, gref, buf["g"], buf["codes"], buf["scales"], buf["vbar"])
+                torch.cuda.synchronize()
+                trace.append([t.clone() for t in (buf["g"], buf["codes"], buf["scales"], buf["vbar"], x, gref)])
+            # the encoder on its own takes the same route
+            codes2, scales2 = torch.empty_like(buf["codes"]), torch.empty_like(buf["scales"])
+            ctx.normalize_encode(7, buf["g"], gref, codes2, scales2)
+            torch.cuda.synchronize()
+            trace.append([codes2, scales2])
+            if ev is not None:
+                ctx.set_profile_events(None, 0)
+                ev.destroy()
+            ctx.close()
+            outs.append(trace)
+        for a, b in zip(outs[0], outs[1]):
+            for ta, tb in zip(a, b):
+                assert torch.equal(ta, tb)
