@@ -72,3 +72,54 @@ def test_full_size_windows(full_inputs, bits, norm, scale):
         assert np.array_equal(vbar_dev[s:s + win].cpu().numpy(), vb), f"decoded average in window at {s}"
     # properties that hold at any size: |decoded - mean(g)| is bounded by the mean grid step
     ctx.close()
+
+
+@pytest.mark.parametrize("bits,norm,scale", [(2, B.NORM_SUB, B.SCALE_MAX), (4, B.NORM_QUOT, B.SCALE_MAX),
+                                             (2, B.NORM_MEAN, B.SCALE_L2)])
+def test_large_rows_of_odd_length_and_odd_worker_count(bits, norm, scale):
+    # d = 2^26 + 3: every row but the first starts off the 16-byte grid (vector kernels over the first
+    # d - d % 16 coordinates, element-wise kernels for the rest); M = 5: one short group of workers
+    d, M, it = (1 << 26) + 3, 5, 9
+    say(f"large ragged rows d=2^26+3 M=5 bits={bits} norm={norm} scale={scale}")
+    g, gref = synth.codec_inputs(M, d, seed=4, device=DEV)
+    ctx = make_ctx(d, M, bits, norm, seed=8, scale=scale)
+    cfg = oracle_cfg(ctx)
+    buf = buffers(ctx)
+    means_dev = None
+    if norm == B.NORM_MEAN:
+        means_dev = torch.zeros(M, device=DEV)
+        ctx.set_worker_means(means_dev)
+    ctx.normalize_encode(it, g, gref, buf["codes"], buf["scales"])
+    ctx.decode_aggregate(buf["codes"], buf["scales"], gref, buf["vbar"])
+    torch.cuda.synchronize()
+    scales = buf["scales"].cpu().numpy()
+    rh = gref.cpu().numpy()
+    means = None
+    if means_dev is not None:
+        means = np.array([O.worker_mean(g[m].cpu().numpy()) for m in range(M)], dtype=np.float32)
+        assert np.array_equal(means_dev.cpu().numpy(), means), "worker means"
+    for m in range(M):
+        v = O.normalize(g[m].cpu().numpy(), rh, norm, cfg.quot_eps, None, None if means is None else means[m])
+        assert O.scale_of(v, scale) == scales[m], f"scale of worker {m}"
+        del v
+    rng = np.random.default_rng(bits + norm)
+    win, per = 4096, 32 // bits
+    last = (d // 16) * 16 - (win - 16)                       # reaches past the end of the rows
+    starts = [0, last] + [int(s) * 16 for s in rng.integers(0, (d - win) // 16, 12)]
+    for s in starts:
+        n = min(win, d - s)
+        gw = g[:, s:s + n].cpu().numpy()
+        rw = rh[s:s + n]
+        nwords = O.words_per_row(n, bits)
+        words = np.zeros((M, nwords), dtype=np.uint32)
+        for m in range(M):
+            v = O.normalize(gw[m], rw, norm, cfg.quot_eps, None, None if means is None else means[m])
+            u = O.uniform_from_word(O.quant_draw_words(cfg.seed, it, m, n, first=s))
+            level, neg = O.quantize(v, scales[m], bits, u)
+            words[m] = O.pack(level, neg, bits)
+        got = u32(buf["codes"][:, s // per:s // per + nwords])
+        assert np.array_equal(got, words), f"codes in window at {s}"
+        vb = O.decode_aggregate(cfg, words, scales, rw, n, None, means)
+        assert np.array_equal(buf["vbar"][s:s + n].cpu().numpy(), vb), f"decoded average in window at {s}"
+    assert s // per + nwords <= ctx.words
+    ctx.close()
