@@ -450,7 +450,7 @@ def test_external_gradients_and_separate_calls_equal_the_fused_step():
 
 def test_window_average_reference():
     # reference = mean of the last 3 decoded averages, refreshed every 2 iterations
-    for d, M, W, K in [(5000, 3, 3, 2), (4099, 2, 4, 1), (1 << 16, 4, 2, 3)]:
+    for d, M, W, K in [(5000, 3, 3, 2), (4099, 2, 4, 1), (1 << 16, 4, 2, 3), (1000, 4, 3, 2)]:   # the last: single-workgroup path
         say(f"window-average reference d={d} M={M} window={W} period={K}")
         ctx = make_ctx(d, M, 2, B.NORM_SUB, seed=5, lr=1e-5, ref_policy=B.REF_WINDOW_AVG, ref_period=K, ref_window=W,
                        problem=B.PROB_ROSENBROCK)
