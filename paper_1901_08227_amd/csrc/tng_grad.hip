@@ -621,7 +621,9 @@ __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __res
 }
 
 // Gradient pass: one workgroup per (worker, tile); every minibatch row adds (r_i / B) val into the
-// fp64 tile in LDS, and the finished tile is written once (+ l2 w).
+// fp64 tile in LDS, and the finished tile is written once (+ l2 w).  FUSE: the write-out also leaves
+// the tile's largest |normalize(g)| for the scale pass (partials[tile][worker]), which then need not
+// read g again: +0.5 ms here against a 0.7 ms pass saved at d = 2^24, M = 64.
 // Where the time goes at d = 2^24, M = 64, B = 512 (2.47 ms): without the adds 2.32 ms, without the
 // write-out of g 1.96 ms -- the rest is reading the entries in 66-byte segments, at the rate such
 // segments are delivered at all (see the paired dot-product pass).
@@ -634,6 +636,7 @@ __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __res
 // as wavefront-uniform values, no spills) and working through the tiles in two phases with the first
 // tile's stores left in flight (2.66 ms: its loads alone 1.26 ms, its write-out alone 1.06 ms, both
 // together more than their sum -- the random reads and the streaming writes compete in memory).
+template <bool FUSE>
 __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* const* __restrict__ cols,
                                                                const float* const* __restrict__ vals,
                                                                const int64_t* __restrict__ rowbase,
@@ -641,11 +644,12 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
                                                                const float* __restrict__ resid,
                                                                const float* __restrict__ w, float* __restrict__ g,
                                                                uint64_t d, uint32_t batch, uint32_t ntiles,
-                                                               uint32_t tile_shift, float l2) {
+                                                               uint32_t tile_shift, float l2, ScaleFusion fuse) {
   extern __shared__ double gtile[];  // g over the tile's columns, accumulated in fp64
   __shared__ int64_t sLo[kCsrRows];
   __shared__ uint32_t sLen[kCsrRows];
   __shared__ float sR[kCsrRows];
+  __shared__ float red[kCsrThreads / kWave];
   const uint32_t m = blockIdx.x, t = blockIdx.y;
   const uint32_t T = 1u << tile_shift;
   const uint64_t c0 = (uint64_t)t << tile_shift;
@@ -679,8 +683,37 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
       }
     }
   }
-  __syncthreads();
   float* __restrict__ out = g + (uint64_t)m * d;
+  if (FUSE) {
+    // Fused scale pass (the launcher has checked: full tiles of 2^kCsrTileShift columns, no l2 term,
+    // aligned rows).  The reference of the thread's columns is fetched before the barrier, so the wait
+    // for it runs while the slower wavefronts finish their adds.
+    constexpr int kPer = (1 << kCsrTileShift) / (4 * kCsrThreads);
+    float4 r1[kPer], r2[kPer];
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) load_refs4(fuse, c0 / 4 + (uint32_t)k * kCsrThreads + threadIdx.x, r1[k], r2[k]);
+    __syncthreads();
+    float4* __restrict__ out4 = reinterpret_cast<float4*>(out + c0);
+    float amax = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      const uint32_t q = (uint32_t)k * kCsrThreads + threadIdx.x;
+      const float4 o = make_float4((float)gtile[4 * q], (float)gtile[4 * q + 1], (float)gtile[4 * q + 2],
+                                   (float)gtile[4 * q + 3]);
+      store_stream(out4 + q, o);
+      amax = fmaxf(amax, absmax4(fuse, o, r1[k], r2[k]));
+    }
+    amax = wave_max(amax);
+    if (threadIdx.x % kWave == 0) red[threadIdx.x / kWave] = amax;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+      for (int k = 1; k < kCsrThreads / kWave; ++k) amax = fmaxf(amax, red[k]);
+      fuse.partials[(uint64_t)t * gridDim.x + m] = amax;
+    }
+    return;
+  }
+  __syncthreads();
   if (c0 + T <= d && T % 4 == 0 && l2 == 0.f && ((reinterpret_cast<uintptr_t>(out) | (d * 4)) & 15u) == 0) {
     float4* __restrict__ out4 = reinterpret_cast<float4*>(out + c0);
     for (uint32_t q = threadIdx.x; q < T / 4; q += kCsrThreads)
@@ -887,10 +920,14 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
   const size_t lds_w = sizeof(float) << shift, lds_g = sizeof(double) << shift;
   static bool attr_set = false;  // the g tile exceeds the 64 KiB default limit of dynamic LDS
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_grad_kernel),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_grad_kernel<false>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize,
                                              (int)(sizeof(double) << kCsrTileShift));
     if (e != hipSuccess) return e;
+    const hipError_t e4 = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_grad_kernel<true>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                                              (int)(sizeof(double) << kCsrTileShift));
+    if (e4 != hipSuccess) return e4;
     const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_z_wide_kernel),
                                               hipFuncAttributeMaxDynamicSharedMemorySize,
                                               (int)(2 * sizeof(float) << kCsrTileShift));
@@ -918,12 +955,16 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
   }
   hipLaunchKernelGGL(csr_z_reduce_kernel, dim3((batch + kBlock - 1) / kBlock, M), dim3(kBlock), 0, s, zpart, p.y, idx,
                      z, batch, nparts, inv_b);
-  // The scale pass is not fused here: this kernel runs one workgroup per compute unit with its phases
-  // back to back, and the extra reference loads and reduction in its epilogue cost more (+0.8 ms at
-  // d = 2^24, M = 64) than the separate scale pass they would replace (0.7 ms).
-  (void)fuse;
-  hipLaunchKernelGGL(csr_grad_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, rowbase, bounds, z, w,
-                     g, d, batch, ntiles, shift, l2);
+  // The scale pass rides along when every tile is a full one and the write-out is the plain one.
+  if (fuse != nullptr && fused_rows != nullptr && shift == kCsrTileShift && d % (1ull << kCsrTileShift) == 0 &&
+      l2 == 0.f && ntiles <= kAbsmaxMaxBlocks && aligned16(g) && aligned16(fuse->gref) && aligned16(fuse->gref2)) {
+    hipLaunchKernelGGL(csr_grad_kernel<true>, dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, rowbase, bounds,
+                       z, w, g, d, batch, ntiles, shift, l2, *fuse);
+    *fused_rows = ntiles;
+  } else {
+    hipLaunchKernelGGL(csr_grad_kernel<false>, dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, rowbase,
+                       bounds, z, w, g, d, batch, ntiles, shift, l2, ScaleFusion{});
+  }
   return hipGetLastError();
 }
 

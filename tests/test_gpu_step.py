@@ -271,15 +271,17 @@ def test_every_normalisation_through_the_fused_step():
             ctx.close()
 
 
-@pytest.mark.parametrize("use_index", [False, True])
-def test_csr_logistic_scaled(use_index):
-    # shape of the sparse configuration scaled to d=2^16, M=8, 0.1% density, 4-bit, subtraction;
-    # with and without the prebuilt per-row tile index
+@pytest.mark.parametrize("use_index,bits,norm", [(False, 4, B.NORM_SUB), (True, 4, B.NORM_SUB),
+                                                 (True, 2, B.NORM_QUOT), (True, 4, B.NORM_NONE)])
+def test_csr_logistic_scaled(use_index, bits, norm):
+    # shape of the sparse configuration scaled to d=2^16, M=8, 0.1% density, 4-bit, subtraction, with and
+    # without the prebuilt per-row tile index; the other normalisations through the scale pass that rides
+    # along with the gradient kernel's write-out
     M, n, d, batch, seed = 8, 1024, 1 << 16, 128, 4
     nnz_row = round(1e-3 * d)
-    say(f"csr logistic d={d} M={M} nnz/row={nnz_row} index={use_index}")
+    say(f"csr logistic d={d} M={M} nnz/row={nnz_row} index={use_index} bits={bits} norm={norm}")
     shards, _ = synth.logreg_csr(M, n, d, nnz_row, seed, device=DEV)
-    ctx = make_ctx(d, M, 4, B.NORM_SUB, seed=seed, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR)
+    ctx = make_ctx(d, M, bits, norm, seed=seed, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR)
     ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
     if use_index:
         ctx.build_csr_index()
@@ -287,6 +289,9 @@ def test_csr_logistic_scaled(use_index):
     host = [tuple(t.cpu().numpy() for t in s) for s in shards]
     w = torch.zeros(d, device=DEV)
     gref = torch.zeros(d, device=DEV)
+    if norm == B.NORM_QUOT:      # a reference that is not zero everywhere, so that most quotients are finite
+        gref = 1e-3 * torch.randn(d, device=DEV, generator=torch.Generator(device=DEV).manual_seed(9))
+        gref[::7] = 0.0
     buf = buffers(ctx)
     for it in range(6):
         def grad_ref(w0, it=it):
