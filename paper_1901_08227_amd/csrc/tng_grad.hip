@@ -623,7 +623,7 @@ __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __res
 // Gradient pass: one workgroup per (worker, tile); every minibatch row adds (r_i / B) val into the
 // fp64 tile in LDS, and the finished tile is written once (+ l2 w).  FUSE: the write-out also leaves
 // the tile's largest |normalize(g)| for the scale pass (partials[tile][worker]), which then need not
-// read g again: +0.5 ms here against a 0.7 ms pass saved at d = 2^24, M = 64.
+// read g again: +0.35 ms here against a 0.7 ms pass saved at d = 2^24, M = 64.
 // Where the time goes at d = 2^24, M = 64, B = 512 (2.47 ms): without the adds 2.32 ms, without the
 // write-out of g 1.96 ms -- the rest is reading the entries in 66-byte segments, at the rate such
 // segments are delivered at all (see the paired dot-product pass).
@@ -654,6 +654,13 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
   const uint32_t T = 1u << tile_shift;
   const uint64_t c0 = (uint64_t)t << tile_shift;
   for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) gtile[j] = 0.0;
+  // fused scale pass: the reference of the thread's columns, fetched first so that nothing waits for it
+  constexpr int kPer = (1 << kCsrTileShift) / (4 * kCsrThreads);
+  float4 r1[kPer], r2[kPer];
+  if (FUSE) {
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) load_refs4(fuse, c0 / 4 + (uint32_t)k * kCsrThreads + threadIdx.x, r1[k], r2[k]);
+  }
   const GlobalPtr<int32_t> c = as_global(cols[m]);
   const GlobalPtr<float> v = as_global(vals[m]);
   const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
@@ -688,10 +695,6 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
     // Fused scale pass (the launcher has checked: full tiles of 2^kCsrTileShift columns, no l2 term,
     // aligned rows).  The reference of the thread's columns is fetched before the barrier, so the wait
     // for it runs while the slower wavefronts finish their adds.
-    constexpr int kPer = (1 << kCsrTileShift) / (4 * kCsrThreads);
-    float4 r1[kPer], r2[kPer];
-#pragma unroll
-    for (int k = 0; k < kPer; ++k) load_refs4(fuse, c0 / 4 + (uint32_t)k * kCsrThreads + threadIdx.x, r1[k], r2[k]);
     __syncthreads();
     float4* __restrict__ out4 = reinterpret_cast<float4*>(out + c0);
     float amax = 0.f;
