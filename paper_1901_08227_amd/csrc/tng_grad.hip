@@ -506,8 +506,8 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
                                                                  uint32_t batch, uint32_t ntiles, uint32_t npairs,
                                                                  uint32_t M, uint32_t workers_per_block) {
   extern __shared__ float wtile[];  // w over the columns of both tiles
-  __shared__ int64_t sLo[kCsrRows];
-  __shared__ uint32_t sLen[kCsrRows];
+  __shared__ int64_t sLoBuf[2][kCsrRows];  // segment starts and lengths, this step's and the next one's
+  __shared__ uint32_t sLenBuf[2][kCsrRows];
   const uint32_t pair = blockIdx.y;
   const uint32_t t_lo = 2 * pair, t_hi = min(2 * pair + 2, ntiles);
   constexpr uint32_t T = 2u << kCsrTileShift;
@@ -529,25 +529,39 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
   }
   const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
   const uint32_t j0 = group * kCsrUnroll;
-  // the tiles of w serve several workers in turn
+  // The tiles of w serve several workers in turn.  A step is one trip of kCsrRows minibatch rows of one
+  // worker; the segment bounds of the next step are fetched while this step's entries are on their
+  // way (every thread fetches, the row index clamped, so that no load sits under a condition).
+  static_assert(kCsrThreads >= kCsrRows, "one thread per staged row");
   const uint32_t m_first = blockIdx.x * workers_per_block, m_last = min(m_first + workers_per_block, M);
-  for (uint32_t m = m_first; m < m_last; ++m) {
-  float* __restrict__ zpart = zparts + ((uint64_t)m * npairs + pair) * batch;
-  const GlobalPtr<int32_t> c = as_global(cols[m]);
-  const GlobalPtr<float> v = as_global(vals[m]);
-  for (uint32_t first = 0; first < batch; first += kCsrRows) {
+  const uint32_t trips = (batch + kCsrRows - 1) / kCsrRows;
+  const uint32_t steps = (m_last - m_first) * trips;
+  auto fetch_bounds = [&](uint32_t step, int64_t& start, uint32_t& length) {
+    const uint32_t m = m_first + step / trips, first = (step % trips) * kCsrRows;
+    const uint32_t j = first + min(threadIdx.x, min((uint32_t)kCsrRows, batch - first) - 1u);
+    const uint32_t* __restrict__ b = bounds + (uint64_t)m * (ntiles + 1) * batch;
+    const uint32_t lo = b[(uint64_t)t_lo * batch + j], hi = b[(uint64_t)t_hi * batch + j];
+    start = rowbase[(uint64_t)m * batch + j] + lo;
+    length = hi - lo;
+  };
+  int64_t next_start;
+  uint32_t next_len;
+  fetch_bounds(0, next_start, next_len);
+  if (threadIdx.x < (uint32_t)kCsrRows) {
+    sLoBuf[0][threadIdx.x] = next_start;
+    sLenBuf[0][threadIdx.x] = next_len;
+  }
+  for (uint32_t step = 0; step < steps; ++step) {
+  {
+    const uint32_t m = m_first + step / trips, first = (step % trips) * kCsrRows;
+    float* __restrict__ zpart = zparts + ((uint64_t)m * npairs + pair) * batch;
+    const GlobalPtr<int32_t> c = as_global(cols[m]);
+    const GlobalPtr<float> v = as_global(vals[m]);
     const uint32_t count = min((uint32_t)kCsrRows, batch - first);
-    __syncthreads();
-    {
-      const uint32_t* __restrict__ b = bounds + (uint64_t)m * (ntiles + 1) * batch + first;
-      const int64_t* __restrict__ base = rowbase + (uint64_t)m * batch + first;
-      for (uint32_t j = threadIdx.x; j < count; j += kCsrThreads) {
-        const uint32_t lo = b[(uint64_t)t_lo * batch + j], hi = b[(uint64_t)t_hi * batch + j];
-        sLo[j] = base[j] + lo;
-        sLen[j] = hi - lo;
-      }
-    }
-    __syncthreads();
+    const int64_t* sLo = sLoBuf[step & 1];
+    const uint32_t* sLen = sLenBuf[step & 1];
+    __syncthreads();  // this step's bounds are in place, the other buffer is free
+    fetch_bounds(min(step + 1, steps - 1), next_start, next_len);
     uint32_t len[kCsrUnroll];
     int32_t col[kCsrUnroll][2];
     float val[kCsrUnroll][2];
@@ -592,6 +606,10 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
     r1 += __shfl_xor(r1, 1, kWave);
     const uint32_t u = (b4 ? 8u : 0u) + (b3 ? 4u : 0u) + (b2 ? 2u : 0u) + (b1 ? 1u : 0u);
     if ((gl & 1u) == 0u && j0 + u < count) zpart[first + j0 + u] = r1;
+    if (threadIdx.x < (uint32_t)kCsrRows) {
+      sLoBuf[(step + 1) & 1][threadIdx.x] = next_start;
+      sLenBuf[(step + 1) & 1][threadIdx.x] = next_len;
+    }
   }
   }
 }
