@@ -653,7 +653,12 @@ __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __res
 // entries of two adjacent tiles at once into registers (one wavefront per row, segment descriptors
 // as wavefront-uniform values, no spills) and working through the tiles in two phases with the first
 // tile's stores left in flight (2.66 ms: its loads alone 1.26 ms, its write-out alone 1.06 ms, both
-// together more than their sum -- the random reads and the streaming writes compete in memory).
+// together more than their sum -- the random reads and the streaming writes compete in memory);
+// a run of four tiles per workgroup with the next tile's segment bounds prefetched, the tile cleared
+// by its own write-out and barriers that wait for LDS traffic only (+0.3 ms).  What the variants that
+// keep a workgroup alive across tiles have in common: loads and stores share one in-order counter,
+// so the wait for the next tile's entries is also a wait for the previous tile's stores to be
+// acknowledged, while a workgroup that ends after its write-out leaves them to drain behind it.
 template <bool FUSE>
 __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* const* __restrict__ cols,
                                                                const float* const* __restrict__ vals,
