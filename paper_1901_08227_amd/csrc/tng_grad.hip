@@ -217,36 +217,39 @@ __global__ __launch_bounds__(kBlock) void logreg_dense_grad_kernel(const float* 
   }
 }
 
-// The same for problems with few columns (a handful of workgroups in all): 1024 threads, the minibatch
-// rows dealt round-robin to four row groups that run side by side, their partial sums added in the
-// fixed order ((p0 + p1) + p2) + p3.  Cuts the chain of dependent row fetches to a quarter.
-constexpr int kRowGroups = 4;
-template <bool FUSE>
-__global__ __launch_bounds__(kBlock* kRowGroups) void logreg_dense_grad_split_kernel(
+// The same for problems with few columns (a handful of workgroups in all): 1024 threads, COLS float4
+// columns times RG row groups; the minibatch rows are dealt round-robin to the row groups, which run
+// side by side, and their partial sums are added in the fixed order ((p0 + p1) + p2) + ...  Cuts the
+// chain of dependent row fetches to 1/RG; narrow column blocks (32 x 32) also spread a tiny problem
+// over eight times as many compute units, each of which can only pull so many bytes per microsecond.
+constexpr int kSplitThreads = 1024;
+template <int COLS, bool FUSE>
+__global__ __launch_bounds__(kSplitThreads) void logreg_dense_grad_split_kernel(
     const float* const* __restrict__ Xs, const uint32_t* __restrict__ idx, const float* __restrict__ resid,
     const float* __restrict__ w, float* __restrict__ g, uint64_t d, uint32_t batch, float inv_b, float l2,
     ScaleFusion fuse) {
+  constexpr int RG = kSplitThreads / COLS;
   __shared__ float sR[kBlock];
   __shared__ uint32_t sRow[kBlock];
-  __shared__ float4 sAcc[kRowGroups - 1][kBlock];
+  __shared__ float4 sAcc[RG - 1][COLS];
   __shared__ float red[16];
   const uint32_t m = blockIdx.y;
-  const uint32_t tx = threadIdx.x % kBlock, rg = threadIdx.x / kBlock;
+  const uint32_t tx = threadIdx.x % COLS, rg = threadIdx.x / COLS;
   const GlobalPtr<float> X = as_global(Xs[m]);
-  const uint64_t col = (uint64_t)blockIdx.x * kBlock + tx;  // float4 index
+  const uint64_t col = (uint64_t)blockIdx.x * COLS + tx;  // float4 index
   const bool active = col < d / 4;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (uint32_t base = 0; base < batch; base += kBlock) {
     __syncthreads();
-    if (rg == 0 && base + tx < batch) {
-      sR[tx] = resid[(uint64_t)m * batch + base + tx];
-      sRow[tx] = idx[(uint64_t)m * batch + base + tx];
+    if (threadIdx.x < (uint32_t)kBlock && base + threadIdx.x < batch) {
+      sR[threadIdx.x] = resid[(uint64_t)m * batch + base + threadIdx.x];
+      sRow[threadIdx.x] = idx[(uint64_t)m * batch + base + threadIdx.x];
     }
     __syncthreads();
     if (active) {
       const uint32_t cnt = min((uint32_t)kBlock, batch - base);
 #pragma unroll 8
-      for (uint32_t i = rg; i < cnt; i += kRowGroups) {
+      for (uint32_t i = rg; i < cnt; i += RG) {
         const float4 xv = load4_stream(X + (uint64_t)sRow[i] * d, col);
         const float r = sR[i];
         acc.x = __builtin_fmaf(r, xv.x, acc.x);
@@ -261,7 +264,7 @@ __global__ __launch_bounds__(kBlock* kRowGroups) void logreg_dense_grad_split_ke
   float amax = 0.f;
   if (active && rg == 0) {
 #pragma unroll
-    for (int k = 0; k < kRowGroups - 1; ++k) {
+    for (int k = 0; k < RG - 1; ++k) {
       const float4 p = sAcc[k][tx];
       acc.x = acc.x + p.x;
       acc.y = acc.y + p.y;
@@ -884,17 +887,30 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
     // the fused scale pass sees the vector part only, so it needs all of d there
     const bool can_fuse = whole && fuse != nullptr && fused_rows != nullptr && grid_g.x <= kAbsmaxMaxBlocks &&
                           aligned16(fuse->gref) && aligned16(fuse->gref2);
-    if (whole && aligned16(g) && (uint64_t)grid_g.x * M <= 128 && batch >= 4 * kRowGroups) {
-      // a handful of workgroups: split the rows
-      if (can_fuse) {
-        hipLaunchKernelGGL((logreg_dense_grad_split_kernel<true>), grid_g, dim3(kBlock * kRowGroups), 0, s, p.X, idx, resid,
-                           w, g, d, batch, inv_b, l2, *fuse);
-        *fused_rows = grid_g.x;
-      } else {
-        hipLaunchKernelGGL((logreg_dense_grad_split_kernel<false>), grid_g, dim3(kBlock * kRowGroups), 0, s, p.X, idx,
-                           resid, w, g, d, batch, inv_b, l2, ScaleFusion{});
+    if (whole && aligned16(g)) {  // a handful of workgroups: split the rows
+      const uint32_t narrow = (uint32_t)((d / 4 + 31) / 32);
+#define TNG_SPLIT(COLS, GX, F)                                                                                        \
+  hipLaunchKernelGGL((logreg_dense_grad_split_kernel<COLS, F>), dim3(GX, M), dim3(kSplitThreads), 0, s, p.X, idx, resid, \
+                     w, g, d, batch, inv_b, l2, F ? *fuse : ScaleFusion{})
+      if (narrow <= 8 && batch >= 64) {  // d <= 1024; up to 8 rows of fused maxima are reduced by the quantiser itself
+        if (can_fuse) {
+          TNG_SPLIT(32, narrow, true);
+          *fused_rows = narrow;
+        } else {
+          TNG_SPLIT(32, narrow, false);
+        }
+        return hipGetLastError();
       }
-      return hipGetLastError();
+      if ((uint64_t)grid_g.x * M <= 128 && batch >= 16) {
+        if (can_fuse) {
+          TNG_SPLIT(256, grid_g.x, true);
+          *fused_rows = grid_g.x;
+        } else {
+          TNG_SPLIT(256, grid_g.x, false);
+        }
+        return hipGetLastError();
+      }
+#undef TNG_SPLIT
     }
     if (can_fuse) {
       hipLaunchKernelGGL((logreg_dense_grad_kernel<true, true>), grid_g, dim3(kBlock), 0, s, p.X, idx, resid, w, g, d,
