@@ -8,8 +8,7 @@ from paper_1901_08227_amd import binding as B
 DEV = "cuda:0"
 
 
-def say(msg):
-    print(msg, flush=True)
+from progress import say  # noqa: E402,F401  (one progress line, visible through pytest's capture)
 
 
 def make_ctx(d, M, bits, norm, seed=0, **kw):
@@ -62,3 +61,54 @@ def grad_close(a, b, cond, rel=1e-5):
     diff = np.abs(a - b)
     return bool(np.linalg.norm(a - b) <= rel * np.linalg.norm(b) and diff.max() <= rel * np.abs(b).max()
                 and np.all(diff <= rel * np.abs(b) + 4 * EPS32 * cond))
+
+
+def logistic_condition_csr(rowptr, col, val, y, w, ids, d, l2=0.0):
+    """logistic_condition for minibatch rows stored as CSR, without densifying them.  Float64, host."""
+    w64 = np.asarray(w, dtype=np.float64)
+    cond = np.zeros(d, dtype=np.float64)
+    for i in np.asarray(ids):
+        a, b = int(rowptr[i]), int(rowptr[i + 1])
+        c = np.asarray(col[a:b], dtype=np.int64)
+        x = np.asarray(val[a:b], dtype=np.float64)
+        r = O.sigmoid64(np.array([x @ w64[c]]))[0] - float(y[i])
+        Z = np.abs(x) @ np.abs(w64[c])
+        np.add.at(cond, c, (abs(r) + 0.25 * Z) * np.abs(x))
+    return cond / float(len(ids)) + abs(l2) * np.abs(w64)
+
+
+def oracle_step_threaded(cfg, it, w, gref, g, threads=8, block=1 << 22):
+    """The oracle's iteration (what O.step computes for the shared-reference normalisations and the
+    largest-magnitude or l2 scale) put together from the oracle's own per-worker and per-coordinate
+    functions, so that host threads can share the work at large M * d: the workers' side one worker per
+    task, the server's side one block of coordinates per task (block: a multiple of 16 coordinates, whole
+    packed words for either width).  numpy releases the interpreter lock inside its loops.  Nothing is
+    computed here: every value comes out of an oracle function.  tests/test_oracle_step.py holds it
+    against O.step."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    assert cfg.norm in (O.NORM_NONE, O.NORM_SUB, O.NORM_QUOT) and block % 16 == 0
+    g = np.asarray(g, dtype=np.float32)
+    M, d = g.shape
+    per = 32 // cfg.bits
+
+    def worker(m):
+        v = O.normalize(g[m], gref, cfg.norm, cfg.quot_eps)
+        R = O.scale_of(v, cfg.scale_kind)
+        u = O.uniform_from_word(O.quant_draw_words(cfg.seed, it, m, d))
+        level, neg = O.quantize(v, R, cfg.bits, u)
+        return O.pack(level, neg, cfg.bits), R
+
+    def server(a):
+        b = min(a + block, d)
+        return O.decode_aggregate(cfg, codes[:, a // per:(b + per - 1) // per], scales, gref[a:b], b - a)
+
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        enc = list(pool.map(worker, range(M)))
+        codes = np.stack([e[0] for e in enc])
+        scales = np.array([e[1] for e in enc], dtype=np.float32)
+        vbar = np.concatenate(list(pool.map(server, range(0, d, block))))
+    w_next = O.update_iterate(w, vbar, cfg.lr)
+    assert cfg.ref_policy in (O.REF_ZERO, O.REF_LAST_AVG)
+    gref_next = O.update_reference(cfg, it, vbar, gref)
+    return w_next, gref_next, codes, scales, vbar

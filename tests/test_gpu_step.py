@@ -10,7 +10,8 @@ import pytest
 import torch
 
 from oracle import tng_oracle as O
-from gpu_util import DEV, buffers, grad_close, logistic_condition, make_ctx, oracle_cfg, say, u32
+from gpu_util import (DEV, buffers, grad_close, logistic_condition, logistic_condition_csr, make_ctx, oracle_cfg,
+                      say, u32)
 from paper_1901_08227_amd import binding as B
 from paper_1901_08227_amd import synth
 
@@ -65,6 +66,8 @@ def _dense_case(M, n, d, batch, bits, norm, T, seed, lr=0.1, l2=0.0, ref_period=
             cond = np.stack([logistic_condition(Xh[m][ids[m]], yh[m][ids[m]], w0, l2) for m in range(M)])
             return ref, cond
         _teacher_forced_step(ctx, cfg, it, w, gref, buf, grad_ref)
+        if it % 50 == 49:
+            say(f"  it={it} done")
     last = loss(w.cpu().numpy())
     ctx.close()
     return first, last
@@ -127,8 +130,9 @@ def test_free_running_trajectories_decrease_the_loss_alike():
 
 def test_dense_logistic_quotient_two_bit_scaled():
     # shape of the 16-worker quotient configuration, scaled to d=2^10, 2^12 rows per worker
-    say("dense logistic quotient d=1024 M=16 n=4096 B=256 T=20")
-    _dense_case(M=16, n=4096, d=1024, batch=256, bits=2, norm=B.NORM_QUOT, T=20, seed=3)
+    # all 200 iterations
+    say("dense logistic quotient d=1024 M=16 n=4096 B=256 T=200")
+    _dense_case(M=16, n=4096, d=1024, batch=256, bits=2, norm=B.NORM_QUOT, T=200, seed=3)
 
 
 def test_dense_logistic_odd_dimension_four_bit_l2_period():
@@ -152,19 +156,28 @@ def test_dense_logistic_wide_rows_first_iterations():
 
 def test_rosenbrock_chain_first_iterations_at_full_shape():
     # d = 2^20, M = 8, noise N(0, 0.01), ternary, subtraction; reference refreshed every 16 iterations
+    # ("Nonconvex Problems"): the first 48 of the 500 iterations, three refreshes
     d, M, seed = 1 << 20, 8, 1
-    say(f"rosenbrock d={d} M={M}")
-    ctx = make_ctx(d, M, 2, B.NORM_SUB, seed=seed, lr=1e-5, ref_period=2, problem=B.PROB_ROSENBROCK)
+    say(f"rosenbrock d={d} M={M} K=16, 48 iterations")
+    ctx = make_ctx(d, M, 2, B.NORM_SUB, seed=seed, lr=1e-5, ref_period=16, problem=B.PROB_ROSENBROCK)
     cfg = oracle_cfg(ctx)
     x = synth.rosenbrock_start(d, seed, device=DEV)
     gref = torch.zeros(d, device=DEV)
     buf = buffers(ctx)
-    for it in range(4):
+    refreshes = 0
+    for it in range(48):
         noise = synth.gradient_noise(M, d, seed, it, variance=0.01, device=DEV)
         ctx.set_noise(noise)
         nh = noise.cpu().numpy()
+        before = gref.clone()
         _teacher_forced_step(ctx, cfg, it, x, gref, buf,
                              lambda w0: np.stack([O.grad_rosenbrock(w0, nh[m]) for m in range(M)]), grad_exact=True)
+        changed = not torch.equal(before, gref)
+        assert changed == ((it + 1) % 16 == 0), f"it={it}: the reference changes on refresh iterations only"
+        refreshes += changed
+        if it % 8 == 7:
+            say(f"  it={it} done")
+    assert refreshes == 3
     ctx.close()
 
 
@@ -271,12 +284,12 @@ def test_every_normalisation_through_the_fused_step():
             ctx.close()
 
 
-@pytest.mark.parametrize("use_index,bits,norm", [(False, 4, B.NORM_SUB), (True, 4, B.NORM_SUB),
-                                                 (True, 2, B.NORM_QUOT), (True, 4, B.NORM_NONE)])
-def test_csr_logistic_scaled(use_index, bits, norm):
-    # shape of the sparse configuration scaled to d=2^16, M=8, 0.1% density, 4-bit, subtraction, with and
-    # without the prebuilt per-row tile index; the other normalisations through the scale pass that rides
-    # along with the gradient kernel's write-out
+@pytest.mark.parametrize("use_index,bits,norm,T", [(False, 4, B.NORM_SUB, 6), (True, 4, B.NORM_SUB, 100),
+                                                   (True, 2, B.NORM_QUOT, 6), (True, 4, B.NORM_NONE, 6)])
+def test_csr_logistic_scaled(use_index, bits, norm, T):
+    # shape of the sparse configuration scaled to d=2^16, M=8, 0.1% density, 4-bit, subtraction, with the
+    # prebuilt per-row tile index: all 100 iterations; without the index, and the other normalisations
+    # through the scale pass that rides along with the gradient kernel's write-out: the first 6
     M, n, d, batch, seed = 8, 1024, 1 << 16, 128, 4
     nnz_row = round(1e-3 * d)
     say(f"csr logistic d={d} M={M} nnz/row={nnz_row} index={use_index} bits={bits} norm={norm}")
@@ -293,20 +306,16 @@ def test_csr_logistic_scaled(use_index, bits, norm):
         gref = 1e-3 * torch.randn(d, device=DEV, generator=torch.Generator(device=DEV).manual_seed(9))
         gref[::7] = 0.0
     buf = buffers(ctx)
-    for it in range(6):
+    for it in range(T):
         def grad_ref(w0, it=it):
             ids = [O.minibatch_indices(seed, it, m, batch, n) for m in range(M)]
             ref = np.stack([O.grad_logreg_csr(host[m][0], host[m][1], host[m][2], host[m][3], w0, ids[m], d)
                             for m in range(M)])
-            cond = np.zeros((M, d))
-            for m in range(M):                       # densify the minibatch rows for the condition term
-                Xb = np.zeros((batch, d), dtype=np.float32)
-                for j, i in enumerate(ids[m]):
-                    a, b = host[m][0][i], host[m][0][i + 1]
-                    Xb[j, host[m][1][a:b]] = host[m][2][a:b]
-                cond[m] = logistic_condition(Xb, host[m][3][ids[m]], w0)
+            cond = np.stack([logistic_condition_csr(*host[m], w0, ids[m], d) for m in range(M)])
             return ref, cond
         _teacher_forced_step(ctx, cfg, it, w, gref, buf, grad_ref)
+        if it % 20 == 19:
+            say(f"  it={it} done")
     ctx.close()
 
 

@@ -131,3 +131,24 @@ def test_csr_gradient_equals_dense_gradient_of_the_same_matrix():
         a = O.grad_logreg_csr(rowptr, col, val, y, w, idx, d, l2)
         b = O.grad_logreg_dense(dense, y, w, idx, l2)
         assert np.allclose(a, b, rtol=1e-12, atol=1e-15)
+
+
+def test_condition_term_of_the_gradient_tolerance_sparse_equals_dense():
+    # the GPU tests bound fp32 cancellation by cond_k = (1/B) sum_i (|r_i| + Z_i/4) |x_ik| + |l2 w_k|; the
+    # CSR form of that helper must equal the dense one on the densified rows
+    from gpu_util import logistic_condition, logistic_condition_csr
+
+    rng = np.random.default_rng(3)
+    n, d, nnz = 20, 64, 7
+    cols = np.stack([np.sort(rng.choice(d, nnz, replace=False)) for _ in range(n)]).astype(np.int32)
+    vals = rng.standard_normal((n, nnz)).astype(np.float32)
+    rowptr = np.arange(n + 1, dtype=np.int64) * nnz
+    y = (rng.random(n) < 0.5).astype(np.float32)
+    w = rng.standard_normal(d).astype(np.float32)
+    ids = rng.integers(0, n, 13)
+    Xb = np.zeros((len(ids), d), dtype=np.float32)
+    for j, i in enumerate(ids):
+        Xb[j, cols[i]] = vals[i]
+    a = logistic_condition(Xb, y[ids], w, 0.01)
+    b = logistic_condition_csr(rowptr, cols.reshape(-1), vals.reshape(-1), y, w, ids, d, 0.01)
+    assert np.allclose(a, b, rtol=1e-12, atol=0)

@@ -102,6 +102,26 @@ def test_whole_iteration_composes_the_parts():
         assert np.array_equal(gref2, vbar if it == 1 else gref)
 
 
+def test_threaded_composition_used_by_the_large_gpu_tests_equals_the_whole_iteration():
+    # tests/gpu_util.oracle_step_threaded shares the oracle's work between host threads (workers, then
+    # blocks of coordinates); it must give what O.step gives, bit for bit, ragged blocks included
+    from gpu_util import oracle_step_threaded
+
+    rng = np.random.default_rng(4)
+    for d, M, bits, norm, block in [(1000, 5, 2, O.NORM_SUB, 64), (4099, 3, 4, O.NORM_QUOT, 1024),
+                                    (333, 2, 4, O.NORM_NONE, 16), (70, 9, 2, O.NORM_SUB, 1 << 22)]:
+        cfg = O.Config(d=d, M=M, bits=bits, norm=norm, seed=21, lr=0.05, ref_period=2)
+        w = rng.standard_normal(d).astype(F32)
+        gref = rng.standard_normal(d).astype(F32)
+        gref[::5] = 0
+        g = rng.standard_normal((M, d)).astype(F32)
+        for it in (0, 1):
+            want = O.step(cfg, it, w, gref, g)
+            got = oracle_step_threaded(cfg, it, w, gref, g, threads=3, block=block)
+            for a, b in zip(want, got):
+                assert np.array_equal(a, b)
+
+
 def _run_logistic(norm_cfg, T=60):
     """Small copy of the dense logistic workload: returns (losses, C_nz estimates, coder MSE)."""
     rng = np.random.default_rng(5)
