@@ -32,7 +32,8 @@
  *   - Errors: a NULL pointer, misalignment or an out-of-range field gives
  *     TNG_ERR_INVALID_ARG and enqueues nothing; a call that needs problem data that was
  *     not set gives TNG_ERR_BAD_STATE; a workspace smaller than tng_workspace_bytes gives
- *     TNG_ERR_WORKSPACE; a failed launch gives TNG_ERR_HIP.
+ *     TNG_ERR_WORKSPACE; a failed launch gives TNG_ERR_HIP; tng_create gives TNG_ERR_HOST_MEMORY when
+ *     the host cannot hold the context.
  */
 #ifndef TNG_H
 #define TNG_H
@@ -52,7 +53,9 @@ typedef enum {
   TNG_ERR_BAD_STATE = 2,
   TNG_ERR_WORKSPACE = 3,
   TNG_ERR_UNSUPPORTED = 4,
-  TNG_ERR_HIP = 5
+  TNG_ERR_HIP = 5,
+  TNG_ERR_TOO_LARGE = 6,
+  TNG_ERR_HOST_MEMORY = 7
 } tng_status;
 
 /* How the gradient is normalised before coding (section "Normalized Gradients"). */
@@ -193,6 +196,24 @@ tng_status tng_local_grad(tng_ctx* ctx, uint32_t iter, const float* w, float* g)
  * taken as 0 below FLT_MIN. */
 tng_status tng_normalize_encode(tng_ctx* ctx, uint32_t iter, const float* g, const float* gref,
                                 uint32_t* codes, float* scales);
+
+/* tng_normalize_encode for callers that cannot allocate device memory or hold a context: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same kernels, same
+ * outputs, bit for bit, as tng_normalize_encode of a context created from *cfg; what that call keeps in
+ * the caller's workspace (the per-workgroup partial maxima of the scale pass) lives in a fixed 1 MiB
+ * array in device memory inside the library, which every GPU the library has run on holds until the
+ * process ends.  No hipMalloc / hipFree, no context, no workspace; the first call on a device looks up
+ * the array's address there.
+ *   cfg: host; only d, M, bits, norm, quot_eps, seed are used (the rest must still be valid).
+ *   hip_stream: a hipStream_t of the current device (NULL = the default stream); the call is asynchronous.
+ *   g, gref, codes, scales: device, as for tng_normalize_encode.
+ * Limits: M <= 64 (TNG_ERR_TOO_LARGE beyond); scale = TNG_SCALE_MAX and norm in {NONE, SUB, QUOT}
+ * (TNG_ERR_UNSUPPORTED otherwise: the other modes need a second reference, per-worker means or the
+ * ordered-sum scratch).  All calls on one GPU share the one array: calls that overlap in time on the
+ * same GPU (different streams, different threads) race; calls on one stream are safe.  Nothing in the
+ * array has to be cleared between calls. */
+tng_status tng_normalize_encode_static(const tng_config* cfg, void* hip_stream, uint32_t iter, const float* g,
+                                       const float* gref, uint32_t* codes, float* scales);
 
 /* Server's side: vbar[e] = denorm( (sum_m decode(codes[m][e]) in worker order) * (1/M) ).
  * codes, scales, gref as above; vbar: device [d] (out). */

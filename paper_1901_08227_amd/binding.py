@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libtng.so")
 
 TNG_OK = 0
 TNG_ERR_INVALID_ARG, TNG_ERR_BAD_STATE, TNG_ERR_WORKSPACE, TNG_ERR_UNSUPPORTED, TNG_ERR_HIP = 1, 2, 3, 4, 5
+TNG_ERR_TOO_LARGE, TNG_ERR_HOST_MEMORY = 6, 7
 NORM_NONE, NORM_SUB, NORM_QUOT, NORM_COMB, NORM_MEAN = 0, 1, 2, 3, 4
 SCALE_MAX, SCALE_L2 = 0, 1
 REF_ZERO, REF_LAST_AVG, REF_WINDOW_AVG = 0, 1, 2
@@ -73,6 +74,7 @@ def lib() -> ctypes.CDLL:
             "tng_minibatch_indices": [vp, u32, vp],
             "tng_local_grad": [vp, u32, vp, vp],
             "tng_normalize_encode": [vp, u32, vp, vp, vp, vp],
+            "tng_normalize_encode_static": [cfgp, vp, u32, vp, vp, vp, vp],
             "tng_decode_aggregate": [vp, vp, vp, vp, vp],
             "tng_update_reference": [vp, u32, vp, vp],
             "tng_step": [vp, u32, vp, vp, vp, vp, vp, vp],
@@ -279,3 +281,14 @@ def tng_update_reference(ctx: Context, it, vbar, gref):
 
 def tng_step(ctx: Context, it, w, gref, g, codes, scales, vbar):
     ctx.step(it, w, gref, g, codes, scales, vbar)
+
+
+def tng_normalize_encode_static(cfg: TngConfig, stream, it, g, gref, codes, scales):
+    """The encoder without a context or a workspace (fixed scratch inside the library; M <= 64)."""
+    words = tng_words_per_row(int(cfg.d), int(cfg.bits))
+    M, d = int(cfg.M), int(cfg.d)
+    _check(lib().tng_normalize_encode_static(
+        ctypes.byref(cfg), ctypes.c_void_p(stream.cuda_stream if stream is not None else 0), it,
+        _ptr(g, torch.float32, M * d, "g"), _ptr(gref, torch.float32, d, "gref"),
+        _ptr(codes, torch.int32, M * words, "codes"), _ptr(scales, torch.float32, M, "scales")),
+        "tng_normalize_encode_static")

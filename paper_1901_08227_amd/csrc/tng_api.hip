@@ -6,6 +6,7 @@
 #include "tng_kernels.hpp"
 
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -33,6 +34,13 @@ struct tng_ctx {
   uint32_t prof_slots;
   uint64_t enc_calls, dec_calls;
 };
+
+// Scratch of tng_normalize_encode_static: the partial maxima of the scale pass for up to
+// kStaticMaxWorkers workers, resident on every GPU the library runs on until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+constexpr uint32_t kStaticMaxWorkers = 64;
+constexpr size_t kStaticScratchBytes = (size_t)tng::kAbsmaxMaxBlocks * kStaticMaxWorkers * sizeof(float);  // 1 MiB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -119,6 +127,25 @@ tng_status update_reference_impl(tng_ctx* ctx, uint32_t iter, const float* vbar,
 }
 
 inline tng_status hip_status(hipError_t e) { return e == hipSuccess ? TNG_OK : TNG_ERR_HIP; }
+
+// Device address of the static scratch array on the current device: every GPU holds its own copy at its
+// own address, looked up once per device (the first call on it) and kept.
+constexpr int kMaxDevices = 64;
+std::mutex static_scratch_mutex;
+float* static_scratch_ptr[kMaxDevices] = {};
+
+tng_status static_scratch(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TNG_ERR_HIP;
+  std::lock_guard<std::mutex> lock(static_scratch_mutex);
+  if (static_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return TNG_ERR_HIP;
+    static_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = static_scratch_ptr[dev];
+  return TNG_OK;
+}
 
 tng::LogregData logreg_tables(const tng_ctx* ctx) {
   const uint32_t M = ctx->cfg.M;
@@ -236,6 +263,20 @@ tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g
   }
 }
 
+void set_shape(tng_ctx* ctx, const tng_config* cfg) {
+  const uint64_t per = 32 / cfg->bits;
+  ctx->shape.d = cfg->d;
+  ctx->shape.words = (cfg->d + per - 1) / per;
+  ctx->shape.M = cfg->M;
+  ctx->shape.bits = (int)cfg->bits;
+  ctx->shape.norm = cfg->norm;
+  ctx->shape.eps = cfg->quot_eps;
+  ctx->shape.k0 = (uint32_t)(cfg->seed & 0xFFFFFFFFull);
+  ctx->shape.k1 = (uint32_t)(cfg->seed >> 32);
+  ctx->shape.scale_l2 = cfg->scale == TNG_SCALE_L2 ? 1 : 0;
+  ctx->shape.means = nullptr;
+}
+
 tng_status upload_tables(tng_ctx* ctx, const void* const* t0, const void* const* t1, const void* const* t2,
                          const void* const* t3, const uint64_t* n_rows) {
   const uint32_t M = ctx->cfg.M;
@@ -283,6 +324,8 @@ const char* tng_status_string(tng_status s) {
     case TNG_ERR_WORKSPACE: return "workspace too small or misaligned";
     case TNG_ERR_UNSUPPORTED: return "unsupported";
     case TNG_ERR_HIP: return "HIP runtime error";
+    case TNG_ERR_HOST_MEMORY: return "host memory exhausted";
+    case TNG_ERR_TOO_LARGE: return "more workers than the fixed scratch of the no-allocation entry point holds";
   }
   return "unknown status";
 }
@@ -295,19 +338,10 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   const Partition p = partition(cfg);
   if (workspace == nullptr || !aligned(workspace, kAlign) || workspace_bytes < p.total) return TNG_ERR_WORKSPACE;
   tng_ctx* ctx = new (std::nothrow) tng_ctx();
-  if (ctx == nullptr) return TNG_ERR_HIP;
+  if (ctx == nullptr) return TNG_ERR_HOST_MEMORY;
   ctx->cfg = *cfg;
   ctx->stream = static_cast<hipStream_t>(hip_stream);
-  ctx->shape.d = cfg->d;
-  ctx->shape.words = tng_words_per_row(cfg->d, cfg->bits);
-  ctx->shape.M = cfg->M;
-  ctx->shape.bits = (int)cfg->bits;
-  ctx->shape.norm = cfg->norm;
-  ctx->shape.eps = cfg->quot_eps;
-  ctx->shape.k0 = (uint32_t)(cfg->seed & 0xFFFFFFFFull);
-  ctx->shape.k1 = (uint32_t)(cfg->seed >> 32);
-  ctx->shape.scale_l2 = cfg->scale == TNG_SCALE_L2 ? 1 : 0;
-  ctx->shape.means = nullptr;
+  set_shape(ctx, cfg);
   char* base = static_cast<char*>(workspace);
   ctx->idx = reinterpret_cast<uint32_t*>(base + p.idx_off);
   ctx->resid = reinterpret_cast<float*>(base + p.resid_off);
@@ -481,6 +515,26 @@ tng_status tng_normalize_encode(tng_ctx* ctx, uint32_t iter, const float* g, con
   const tng_status s = check_codec_args(ctx, g, gref, codes, scales, nullptr, true, false);
   if (s != TNG_OK) return s;
   return encode_impl(ctx, iter, g, gref, codes, scales);
+}
+
+tng_status tng_normalize_encode_static(const tng_config* cfg, void* hip_stream, uint32_t iter, const float* g,
+                                       const float* gref, uint32_t* codes, float* scales) {
+  if (!config_valid(cfg)) return TNG_ERR_INVALID_ARG;
+  if (cfg->scale != TNG_SCALE_MAX ||
+      (cfg->norm != TNG_NORM_NONE && cfg->norm != TNG_NORM_SUB && cfg->norm != TNG_NORM_QUOT))
+    return TNG_ERR_UNSUPPORTED;
+  if (cfg->M > kStaticMaxWorkers) return TNG_ERR_TOO_LARGE;
+  tng_ctx local{};  // a host object on the stack; its vectors stay empty
+  local.cfg = *cfg;
+  local.stream = static_cast<hipStream_t>(hip_stream);
+  set_shape(&local, cfg);
+  const tng_status s = check_codec_args(&local, g, gref, codes, scales, nullptr, true, false);
+  if (s != TNG_OK) return s;
+  const tng_status sp = static_scratch(&local.partials);
+  if (sp != TNG_OK) return sp;
+  // nothing in the scratch has to start at zero: the scale pass writes every partial maximum that its
+  // reduction reads
+  return encode_impl(&local, iter, g, gref, codes, scales);
 }
 
 tng_status tng_decode_aggregate(tng_ctx* ctx, const uint32_t* codes, const float* scales, const float* gref,
