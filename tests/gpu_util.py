@@ -112,3 +112,23 @@ def oracle_step_threaded(cfg, it, w, gref, g, threads=8, block=1 << 22):
     assert cfg.ref_policy in (O.REF_ZERO, O.REF_LAST_AVG)
     gref_next = O.update_reference(cfg, it, vbar, gref)
     return w_next, gref_next, codes, scales, vbar
+
+
+def assert_row_sums_are_the_exact_ones(cfg, g, gref, gref2, means, scales, rows=None):
+    """Holds the library's (= the oracle's pinned-order) per-worker means and l2 scales against the
+    values mathematics fixes: float32(exact sum / d) and float32(sqrt(exact sum of squares)), computed
+    with integer arithmetic (tests/exact_sums.py).  No-op for configurations with neither."""
+    from exact_sums import exact_sum, round_to_f32, sqrt_to_f32
+
+    g = np.asarray(g, dtype=np.float32)
+    M, d = g.shape
+    for m in (range(M) if rows is None else rows):
+        mu = None
+        if cfg.norm == O.NORM_MEAN:
+            mu = means[m]
+            assert mu == round_to_f32(exact_sum(g[m]) / d), f"mean of worker {m} is not the exactly rounded mean"
+        if cfg.scale_kind == O.SCALE_L2:
+            v = O.normalize(g[m], gref, cfg.norm, cfg.quot_eps, gref2, mu)
+            want = sqrt_to_f32(exact_sum(v.astype(np.float64) ** 2))
+            want = want if want >= O.FLT_MIN else np.float32(0.0)
+            assert scales[m] == want, f"l2 scale of worker {m} is not the exactly rounded norm"

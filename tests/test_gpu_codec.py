@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from oracle import tng_oracle as O
-from gpu_util import DEV, buffers, make_ctx, oracle_cfg, say, u32
+from gpu_util import DEV, assert_row_sums_are_the_exact_ones, buffers, make_ctx, oracle_cfg, say, u32
 from paper_1901_08227_amd import binding as B
 from paper_1901_08227_amd import synth
 
@@ -40,6 +40,7 @@ def _check_encode_decode(ctx, it, g, gref, gref2, tag):
         assert np.array_equal(means_dev.cpu().numpy(), means), f"{tag}: worker means"
     codes, scales = O.normalize_encode(cfg, it, gh, rh, r2h, means)
     assert np.array_equal(buf["scales"].cpu().numpy(), scales), f"{tag}: scales"
+    assert_row_sums_are_the_exact_ones(cfg, gh, rh, r2h, means, scales)
     got = u32(buf["codes"])
     if not np.array_equal(got, codes):
         bad = np.argwhere(got != codes)

@@ -12,7 +12,7 @@ import pytest
 import torch
 
 from oracle import tng_oracle as O
-from gpu_util import DEV, buffers, make_ctx, oracle_cfg, say, u32
+from gpu_util import DEV, assert_row_sums_are_the_exact_ones, buffers, make_ctx, oracle_cfg, say, u32
 from paper_1901_08227_amd import binding as B
 from paper_1901_08227_amd import synth
 
@@ -103,6 +103,10 @@ def test_full_size_windows(full_inputs, bits, norm, scale):
         v = O.normalize(g[m].cpu().numpy(), rh, norm, cfg.quot_eps, None, None if means is None else means[m])
         assert O.scale_of(v, scale) == scales[m], f"scale of worker {m}"
         del v
+    say("the same sums in exact integer arithmetic (first and last worker)")
+    for m in (0, M - 1):
+        row = g[m].cpu().numpy()[None, :]
+        assert_row_sums_are_the_exact_ones(cfg, row, rh, None, None if means is None else means[m:m + 1], scales[m:m + 1])
     rng = np.random.default_rng(bits * 10 + norm)
     win = 4096
     starts = [0, d - win] + [int(s) * 16 for s in rng.integers(0, (d - win) // 16, 30)]
@@ -153,6 +157,8 @@ def test_large_rows_of_odd_length_and_odd_worker_count(bits, norm, scale):
         v = O.normalize(g[m].cpu().numpy(), rh, norm, cfg.quot_eps, None, None if means is None else means[m])
         assert O.scale_of(v, scale) == scales[m], f"scale of worker {m}"
         del v
+    row = g[M - 1].cpu().numpy()[None, :]
+    assert_row_sums_are_the_exact_ones(cfg, row, rh, None, None if means is None else means[M - 1:], scales[M - 1:])
     rng = np.random.default_rng(bits + norm)
     win, per = 4096, 32 // bits
     last = (d // 16) * 16 - (win - 16)                       # reaches past the end of the rows

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from oracle import tng_oracle as O
-from gpu_util import DEV, buffers, make_ctx, oracle_cfg, say, u32
+from gpu_util import DEV, assert_row_sums_are_the_exact_ones, buffers, make_ctx, oracle_cfg, say, u32
 from paper_1901_08227_amd import binding as B
 
 pytestmark = pytest.mark.gpu
@@ -63,6 +63,7 @@ def test_random_configurations(block):
             assert np.array_equal(means_dev.cpu().numpy(), means)
         codes, scales = O.normalize_encode(cfg, it, gh, rh, r2h, means)
         assert np.array_equal(buf["scales"].cpu().numpy(), scales)
+        assert_row_sums_are_the_exact_ones(cfg, gh, rh, r2h, means, scales)
         assert np.array_equal(u32(buf["codes"]), codes)
         vbar = O.decode_aggregate(cfg, codes, scales, rh, d, r2h, means)
         assert np.array_equal(buf["vbar"].cpu().numpy(), vbar)

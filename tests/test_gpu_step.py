@@ -10,7 +10,7 @@ import pytest
 import torch
 
 from oracle import tng_oracle as O
-from gpu_util import (DEV, buffers, grad_close, logistic_condition, logistic_condition_csr, make_ctx, oracle_cfg,
+from gpu_util import (DEV, assert_row_sums_are_the_exact_ones, buffers, grad_close, logistic_condition, logistic_condition_csr, make_ctx, oracle_cfg,
                       say, u32)
 from paper_1901_08227_amd import binding as B
 from paper_1901_08227_amd import synth
@@ -279,6 +279,8 @@ def test_every_normalisation_through_the_fused_step():
                 assert np.array_equal(buf["scales"].cpu().numpy(), s1), "scales from the fused partial maxima"
                 if norm == B.NORM_MEAN:
                     assert np.array_equal(means.cpu().numpy(), O.worker_means(gh))
+                assert_row_sums_are_the_exact_ones(cfg, gh, r0, gref2.cpu().numpy(),
+                                                   means.cpu().numpy() if norm == B.NORM_MEAN else None, s1)
                 assert np.array_equal(u32(buf["codes"]), c1) and np.array_equal(buf["vbar"].cpu().numpy(), v1)
                 assert np.array_equal(x.cpu().numpy(), w1) and np.array_equal(gref.cpu().numpy(), r1)
             ctx.close()

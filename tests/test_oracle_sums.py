@@ -115,3 +115,75 @@ def test_l2_scale(bits):
         err += ((q - v) ** 2).sum()
     assert np.all(np.abs(acc / T - v) < 5 * float(R) / (2 * s) / math.sqrt(T) + 1e-6)
     assert err / T <= min(d / s ** 2, math.sqrt(d) / s) * exact ** 2 * 1.05
+
+
+def test_exact_sum_helpers_against_the_exactly_rounded_library_sum():
+    # tests/exact_sums.py is what the pinned-order sums are held against; pin it first: exact_sum equals
+    # math.fsum (exactly rounded to binary64) wherever binary64 can show it, round_to_f32 agrees with the
+    # IEEE conversion on binary64 inputs and resolves ties to even, sqrt_to_f32 on exact squares and on 2
+    from fractions import Fraction
+
+    from exact_sums import exact_sum, round_to_f32, sqrt_to_f32
+
+    rng = np.random.default_rng(11)
+    for n in (1, 2, 17, 1000, 50000):
+        x = (rng.standard_normal(n) * 10.0 ** rng.integers(-12, 12, n)).astype(F32)
+        assert float(exact_sum(x)) == math.fsum(x.astype(np.float64).tolist())
+        sq = x.astype(np.float64) ** 2
+        assert float(exact_sum(sq)) == math.fsum(sq.tolist())
+    assert exact_sum(np.array([2.0 ** 60, 1.0, -(2.0 ** 60)])) == 1                 # no order, no loss
+    assert exact_sum(np.array([0.1, 0.2], dtype=F32)) == Fraction(float(F32(0.1))) + Fraction(float(F32(0.2)))
+    for v in rng.standard_normal(300) * 10.0 ** rng.integers(-20, 20, 300):
+        assert round_to_f32(Fraction(float(v))) == F32(v)
+    assert round_to_f32(Fraction(2 ** 24 + 1)) == F32(2 ** 24) and round_to_f32(Fraction(2 ** 24 + 3)) == F32(2 ** 24 + 4)
+    assert round_to_f32(Fraction(1, 3)) == F32(1.0 / 3.0) and round_to_f32(Fraction(-7, 5)) == F32(-1.4)
+    assert sqrt_to_f32(Fraction(9, 4)) == F32(1.5) and sqrt_to_f32(Fraction(2)) == F32(math.sqrt(2.0))
+    for v in rng.uniform(1e-6, 1e6, 200):
+        assert sqrt_to_f32(Fraction(float(v))) == F32(math.sqrt(float(v)))            # 53 >= 2*24+2: no double rounding
+
+
+def test_pinned_order_sums_round_to_what_the_exact_sums_round_to():
+    # The mean reference and the l2 scale are DEFINED as float32(exact sum / D) and float32(sqrt(exact sum of
+    # squares)); the oracle (and the library) add in binary64 in one pinned order, which could differ from that
+    # only if the exact value sat within ~1e-13 relative of a binary32 rounding boundary.  Held against the
+    # exact values on the inputs the parity tests use (the generator of the encode/decode benchmark, and
+    # shifted / scaled rows), sizes up to 2^22.
+    import torch
+
+    from exact_sums import exact_sum, round_to_f32, sqrt_to_f32
+    from paper_1901_08227_amd import synth
+
+    checked = 0
+    for d, M, seed in [(1, 2, 2), (5, 2, 7), (257, 3, 260), (4096, 2, 4098), (4099, 3, 1), (65536, 4, 3),
+                       (4096 * 20 + 148, 3, 231), ((1 << 20) + 8200, 2, 5), (1 << 22, 2, 1)]:
+        g, gref = (t.numpy() for t in synth.codec_inputs(M, d, seed))
+        for m in range(M):
+            for row in (g[m], g[m] * F32(1e-3) + F32(7.0)):
+                assert O.worker_mean(row) == round_to_f32(exact_sum(row) / d), (d, m)
+                for v in (row, row - gref, row - O.worker_mean(row)):
+                    v = v.astype(F32)
+                    want = sqrt_to_f32(exact_sum(v.astype(np.float64) ** 2))
+                    assert O.scale_of(v, O.SCALE_L2) == (want if want >= O.FLT_MIN else 0), (d, m)
+                    checked += 1
+    assert checked > 100
+
+
+def test_reciprocal_multiply_stays_within_two_roundings_of_the_quotient():
+    # "Gradient Compression": P(z = 1) = |v_d| / R.  The coder evaluates |v| * fl(1/R), one reciprocal per
+    # worker, instead of a division per element: two roundings instead of one.  The probability it realises
+    # then differs from |v|/R by at most 2^-23 |v|/R (below two steps of the 24-bit uniform grid), it never
+    # exceeds 1 after the clamp, and the arg-max element itself maps to 1 - 2^-24 or 1, i.e. is coded at
+    # the top level with probability >= 1 - 2^-24.
+    rng = np.random.default_rng(12)
+    worst = 0.0
+    for _ in range(200):
+        R = F32(abs(rng.standard_normal()) * 10.0 ** rng.integers(-20, 20) + 1e-30)
+        a = (rng.random(2000).astype(F32) * R).astype(F32)
+        a[0] = R
+        t = np.minimum(a * (F32(1.0) / R), F32(1.0))
+        exact = a.astype(np.float64) / np.float64(R)
+        worst = max(worst, float(np.max(np.abs(t.astype(np.float64) - exact) / np.maximum(exact, 1e-300))))
+        assert t.max() <= 1.0 and t[0] >= F32(1.0) - F32(2.0 ** -24)
+        one_ulp = np.abs(t - (a / R).astype(F32)) <= np.spacing(np.maximum(t, F32(2.0 ** -126)))
+        assert one_ulp.all()                                   # at most one unit in the last place from fl(|v|/R)
+    assert worst <= 2.0 ** -23
