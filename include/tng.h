@@ -135,6 +135,14 @@ tng_status tng_set_logreg_dense(tng_ctx* ctx, const float* const* X, const float
 tng_status tng_set_logreg_csr(tng_ctx* ctx, const int64_t* const* rowptr,
                               const int32_t* const* col, const float* const* val,
                               const float* const* y, const uint64_t* n_rows);
+/* Optional, CSR problem: checks the shards given to the last tng_set_logreg_csr against what the
+ * gradient kernels assume and cannot check on the hot path: row pointers non-negative and
+ * non-decreasing, ending within the nnz[m] entries stored for worker m (nnz: host array of M counts =
+ * the lengths of the col / val arrays), fewer than 2^32 entries per row; column ids in [0, d) and
+ * strictly ascending within each row.  One pass over the row pointers and, only if they are sound, one
+ * over the column ids; blocks until done.  TNG_OK, or TNG_ERR_INVALID_ARG if any check fails (the
+ * kernels index on-chip tiles with col - tile start: shards that fail must not be used). */
+tng_status tng_validate_csr(tng_ctx* ctx, const uint64_t* nnz);
 /* Optional, CSR problem: a per-row index of where each stored row enters each column tile of the
  * gradient kernels (the columns are processed in tiles of 2^14 coordinates held in on-chip memory).
  * Without it every tng_local_grad / tng_step re-derives these offsets with a pass over the column ids

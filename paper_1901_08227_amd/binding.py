@@ -63,6 +63,7 @@ def lib() -> ctypes.CDLL:
             "tng_set_logreg_dense": [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(u64)],
             "tng_set_logreg_csr": [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                    ctypes.POINTER(vp), ctypes.POINTER(u64)],
+            "tng_validate_csr": [vp, ctypes.POINTER(u64)],
             "tng_set_noise": [vp, vp],
             "tng_set_noise_variance": [vp, ctypes.c_float],
             "tng_set_csr_index": [vp, vp, ctypes.c_size_t],
@@ -179,6 +180,12 @@ class Context:
         self._keep["data"] = (list(rowptr), list(col), list(val), list(y))
         self.n_rows = n
         _check(lib().tng_set_logreg_csr(self.handle, tr, tc, tv, ty, rows), "tng_set_logreg_csr")
+
+    def validate_csr(self):
+        """Device pass over the CSR shards set last: raises TngError(TNG_ERR_INVALID_ARG) if row pointers or
+        column ids break what the gradient kernels assume."""
+        nnz = (ctypes.c_uint64 * self.M)(*[int(c.numel()) for c in self._keep["data"][1]])
+        _check(lib().tng_validate_csr(self.handle, nnz), "tng_validate_csr")
 
     def build_csr_index(self):
         """Allocates and builds the per-row tile index for the CSR shards set last (optional speed-up)."""

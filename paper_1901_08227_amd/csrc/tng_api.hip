@@ -29,6 +29,7 @@ struct tng_ctx {
   float noise_sigma;      // > 0: Gaussian noise is generated on the device instead
   const float* gref2;     // second reference of the combined normalisation
   float* history;         // [ref_window][d] ring of decoded averages (window-average reference)
+  uint32_t* check;        // CSR problem: flag word of tng_validate_csr, then uint64[M] entry counts at +256 bytes
   double* sums;           // chunk and group sums of the order-pinned row sums (mean reference, l2 scale)
   std::vector<hipEvent_t> prof;  // optional timing events, 5 per slot
   uint32_t prof_slots;
@@ -69,7 +70,7 @@ bool config_valid(const tng_config* c) {
 }
 
 struct Partition {
-  size_t idx_off, resid_off, tables_off, partials_off, rowbase_off, bounds_off, zpart_off, sums_off, total;
+  size_t idx_off, resid_off, tables_off, partials_off, rowbase_off, bounds_off, zpart_off, sums_off, check_off, total;
 };
 
 Partition partition(const tng_config* c) {
@@ -96,6 +97,8 @@ Partition partition(const tng_config* c) {
   p.sums_off = off;
   if (c->norm == TNG_NORM_MEAN || c->scale == TNG_SCALE_L2)
     off += round_up(tng::tree_sum_scratch(c->d, c->M) * sizeof(double));
+  p.check_off = off;  // tng_validate_csr: a flag word and the per-worker entry counts
+  if (c->problem == TNG_PROB_LOGREG_CSR) off += round_up(256 + (size_t)c->M * sizeof(uint64_t));
   p.total = off;
   return p;
 }
@@ -351,6 +354,7 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->bounds = reinterpret_cast<uint32_t*>(base + p.bounds_off);
   ctx->zpart = reinterpret_cast<float*>(base + p.zpart_off);
   ctx->sums = reinterpret_cast<double*>(base + p.sums_off);
+  ctx->check = reinterpret_cast<uint32_t*>(base + p.check_off);
   ctx->have_dense = ctx->have_csr = false;
   ctx->have_index = false;
   ctx->noise = nullptr;
@@ -433,6 +437,32 @@ tng_status tng_set_csr_index(tng_ctx* ctx, void* index, size_t bytes) {
     return TNG_ERR_HIP;
   }
   return TNG_OK;
+}
+
+tng_status tng_validate_csr(tng_ctx* ctx, const uint64_t* nnz) {
+  if (ctx == nullptr || nnz == nullptr) return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.problem != TNG_PROB_LOGREG_CSR || !ctx->have_csr) return TNG_ERR_BAD_STATE;
+  const uint32_t M = ctx->cfg.M;
+  uint64_t* nnz_dev = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(ctx->check) + 256);
+  uint64_t max_rows = 0;
+  for (uint32_t m = 0; m < M; ++m) max_rows = ctx->n_rows[m] > max_rows ? ctx->n_rows[m] : max_rows;
+  uint32_t flag = 0;
+  auto read_flag = [&]() {
+    return hipMemcpyAsync(&flag, ctx->check, sizeof(flag), hipMemcpyDeviceToHost, ctx->stream) == hipSuccess &&
+           hipStreamSynchronize(ctx->stream) == hipSuccess;
+  };
+  if (hipMemcpyAsync(nnz_dev, nnz, M * sizeof(uint64_t), hipMemcpyHostToDevice, ctx->stream) != hipSuccess)
+    return TNG_ERR_HIP;
+  if (tng::launch_fill_u32(ctx->check, 1, 0u, ctx->stream) != hipSuccess) return TNG_ERR_HIP;
+  const tng::LogregData p = logreg_tables(ctx);
+  if (tng::launch_csr_validate_rowptr(p, M, max_rows, nnz_dev, ctx->check, ctx->stream) != hipSuccess)
+    return TNG_ERR_HIP;
+  if (!read_flag()) return TNG_ERR_HIP;
+  if (flag != 0) return TNG_ERR_INVALID_ARG;  // the column ids are not looked at: the row pointers cannot be trusted
+  if (tng::launch_csr_validate_cols(p, ctx->cfg.d, M, max_rows, ctx->check, ctx->stream) != hipSuccess)
+    return TNG_ERR_HIP;
+  if (!read_flag()) return TNG_ERR_HIP;
+  return flag != 0 ? TNG_ERR_INVALID_ARG : TNG_OK;
 }
 
 tng_status tng_set_noise(tng_ctx* ctx, const float* noise) {

@@ -9,6 +9,8 @@
 #include "tng_device.hpp"
 #include "tng_kernels.hpp"
 
+#include <mutex>
+
 namespace tng {
 
 namespace {
@@ -358,6 +360,45 @@ __global__ __launch_bounds__(kBlock) void csr_tile_index_kernel(const int64_t* c
     const uint32_t cur = k == nnz ? ntiles : ((uint32_t)c[k] >> tile_shift);
     for (uint32_t t = prev; t <= cur; ++t) out[t] = k;
   }
+}
+
+// Checks of caller-supplied CSR shards (tng_validate_csr).  Stage 1: the row pointers of worker m are
+// non-negative, non-decreasing, end within the nnz[m] stored entries, and no row holds 2^32 entries or
+// more.  Stage 2 (only launched when stage 1 found nothing, so every access below is in range): the
+// column ids of every row lie in [0, d) and ascend strictly.  A violation sets a bit of *flag.
+__global__ __launch_bounds__(kBlock) void csr_validate_rowptr_kernel(const int64_t* const* __restrict__ rowptrs,
+                                                                     const uint64_t* __restrict__ n_rows,
+                                                                     const uint64_t* __restrict__ nnz,
+                                                                     uint32_t* __restrict__ flag) {
+  const uint32_t m = blockIdx.y;
+  const uint64_t n = n_rows[m];
+  const GlobalPtr<int64_t> rp = as_global(rowptrs[m]);
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  uint32_t bad = 0;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+    const int64_t a = rp[i], b = rp[i + 1];
+    if (a < 0 || b < a || (uint64_t)b > nnz[m] || (uint64_t)(b - a) >= (1ull << 32)) bad = 1u;
+  }
+  if (bad != 0) atomicOr(flag, 1u);
+}
+
+__global__ __launch_bounds__(kBlock) void csr_validate_cols_kernel(const int64_t* const* __restrict__ rowptrs,
+                                                                   const int32_t* const* __restrict__ cols,
+                                                                   const uint64_t* __restrict__ n_rows, uint64_t d,
+                                                                   uint32_t* __restrict__ flag) {
+  const uint32_t m = blockIdx.y;
+  const uint64_t n = n_rows[m];
+  uint32_t bad = 0;
+  for (uint64_t row = blockIdx.x; row < n; row += gridDim.x) {
+    const int64_t a = as_global(rowptrs[m])[row], b = as_global(rowptrs[m])[row + 1];
+    const GlobalPtr<int32_t> c = as_global(cols[m]);
+    for (int64_t k = a + threadIdx.x; k < b; k += kBlock) {
+      const int32_t cur = c[k];
+      if (cur < 0 || (uint64_t)cur >= d) bad |= 2u;
+      if (k > a && c[k - 1] >= cur) bad |= 4u;
+    }
+  }
+  if (bad != 0) atomicOr(flag, bad);
 }
 
 // Per iteration, with the index: the index rows of the minibatch are transposed into the tile-major
@@ -944,6 +985,21 @@ uint32_t csr_tiles(uint64_t d) {
   return (uint32_t)((d + (1ull << shift) - 1) >> shift);
 }
 
+hipError_t launch_csr_validate_rowptr(const LogregData& p, uint32_t M, uint64_t max_rows, const uint64_t* nnz,
+                                      uint32_t* flag, hipStream_t s) {
+  const uint64_t bx = (max_rows + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL(csr_validate_rowptr_kernel, dim3((uint32_t)(bx < 4096 ? bx : 4096), M), dim3(kBlock), 0, s, p.rowptr,
+                     p.n_rows, nnz, flag);
+  return hipGetLastError();
+}
+
+hipError_t launch_csr_validate_cols(const LogregData& p, uint64_t d, uint32_t M, uint64_t max_rows, uint32_t* flag,
+                                    hipStream_t s) {
+  hipLaunchKernelGGL(csr_validate_cols_kernel, dim3((uint32_t)(max_rows < 65535 ? max_rows : 65535), M), dim3(kBlock), 0, s,
+                     p.rowptr, p.col, p.n_rows, d, flag);
+  return hipGetLastError();
+}
+
 hipError_t launch_csr_tile_index(const LogregData& p, uint64_t d, uint32_t M, uint64_t max_rows, hipStream_t s) {
   if (max_rows == 0 || max_rows > 0x7fffffffull || p.tile_index == nullptr) return hipErrorInvalidValue;
   hipLaunchKernelGGL(csr_tile_index_kernel, dim3((uint32_t)max_rows, M), dim3(kBlock), 0, s, p.rowptr, p.col, p.n_rows,
@@ -960,21 +1016,24 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
   const uint32_t shift = csr_tile_shift(d);
   const uint32_t ntiles = csr_tiles(d);
   const size_t lds_w = sizeof(float) << shift, lds_g = sizeof(double) << shift;
-  static bool attr_set = false;  // the g tile exceeds the 64 KiB default limit of dynamic LDS
-  if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_grad_kernel<false>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)(sizeof(double) << kCsrTileShift));
-    if (e != hipSuccess) return e;
-    const hipError_t e4 = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_grad_kernel<true>),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                                              (int)(sizeof(double) << kCsrTileShift));
-    if (e4 != hipSuccess) return e4;
-    const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(csr_z_wide_kernel),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                                              (int)(2 * sizeof(float) << kCsrTileShift));
-    if (e2 != hipSuccess) return e2;
-    attr_set = true;
+  {  // the g tile exceeds the 64 KiB default limit of dynamic LDS: raised once per device
+    static std::mutex attr_mutex;
+    static bool attr_done[64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> attr_lock(attr_mutex);
+    if (!attr_done[dev]) {
+      const void* big_lds[] = {reinterpret_cast<const void*>(csr_grad_kernel<false>),
+                               reinterpret_cast<const void*>(csr_grad_kernel<true>),
+                               reinterpret_cast<const void*>(csr_z_wide_kernel)};
+      const int bytes[] = {(int)(sizeof(double) << kCsrTileShift), (int)(sizeof(double) << kCsrTileShift),
+                           (int)(2 * sizeof(float) << kCsrTileShift)};
+      for (int k = 0; k < 3; ++k) {
+        const hipError_t e = hipFuncSetAttribute(big_lds[k], hipFuncAttributeMaxDynamicSharedMemorySize, bytes[k]);
+        if (e != hipSuccess) return e;
+      }
+      attr_done[dev] = true;
+    }
   }
   if (p.tile_index != nullptr) {
     dim3 grid((ntiles + 1 + kGatherTile - 1) / kGatherTile, (batch + kGatherTile - 1) / kGatherTile, M);

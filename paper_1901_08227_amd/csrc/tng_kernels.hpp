@@ -109,6 +109,14 @@ uint32_t csr_tiles(uint64_t d);
 // p.tile_index (optional): per worker uint32[n_rows][csr_tiles(d) + 1], entry [row][t] = offset within
 // the row of the first stored entry whose column is at or beyond the start of tile t; built once by
 // launch_csr_tile_index.  With it the per-iteration pass over the column ids is replaced by a gather.
+// Checks of the CSR shards (see the kernels): nnz device uint64[M] = entries stored per worker; flag:
+// device uint32, cleared by the caller; bit 0 = bad row pointers, bit 1 = column out of [0, d),
+// bit 2 = columns of a row not strictly ascending.  The column pass reads what the row pointers name,
+// so it may only run after the row-pointer pass has come back clean.
+hipError_t launch_csr_validate_rowptr(const LogregData& p, uint32_t M, uint64_t max_rows, const uint64_t* nnz,
+                                      uint32_t* flag, hipStream_t s);
+hipError_t launch_csr_validate_cols(const LogregData& p, uint64_t d, uint32_t M, uint64_t max_rows, uint32_t* flag,
+                                    hipStream_t s);
 hipError_t launch_csr_tile_index(const LogregData& p, uint64_t d, uint32_t M, uint64_t max_rows, hipStream_t s);
 hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                   const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,

@@ -442,6 +442,45 @@ def test_csr_tile_index_changes_nothing_but_the_speed():
     ctx.close()
 
 
+def test_csr_validation_finds_what_the_gradient_kernels_cannot_check():
+    # tng_validate_csr: sound shards pass; a column id at d, a negative one, columns out of order, equal
+    # neighbours, row pointers that decrease or run past the stored entries are each reported (the pass over
+    # the column ids only runs when the row pointers are sound, so it never reads out of range)
+    M, n, d, nnz_row, seed = 3, 50, (1 << 15) + 9, 40, 17
+    shards, _ = synth.logreg_csr(M, n, d, nnz_row, seed, device=DEV)
+    ctx = make_ctx(d, M, 2, B.NORM_SUB, seed=seed, batch=8, problem=B.PROB_LOGREG_CSR)
+
+    def verdict(mutate=None):
+        parts = [[s[k].clone() for s in shards] for k in range(4)]
+        if mutate is not None:
+            mutate(parts)
+        ctx.set_logreg_csr(*parts)
+        try:
+            ctx.validate_csr()
+            return B.TNG_OK
+        except B.TngError as e:
+            return e.status
+
+    def set_col(parts, m, pos, value):
+        parts[1][m][pos] = value
+
+    def set_rowptr(parts, m, pos, value):
+        parts[0][m][pos] = value
+
+    assert verdict() == B.TNG_OK
+    assert verdict(lambda p: set_col(p, 1, 7 * nnz_row + nnz_row - 1, d)) == B.TNG_ERR_INVALID_ARG       # column == d
+    assert verdict(lambda p: set_col(p, 0, 0, -1)) == B.TNG_ERR_INVALID_ARG                             # negative column
+    first, second = int(shards[2][1][3 * nnz_row + 5]), int(shards[2][1][3 * nnz_row + 6])
+    assert verdict(lambda p: (set_col(p, 2, 3 * nnz_row + 5, second), set_col(p, 2, 3 * nnz_row + 6, first))) \
+        == B.TNG_ERR_INVALID_ARG                                                                        # out of order
+    assert verdict(lambda p: set_col(p, 2, 3 * nnz_row + 6, first)) == B.TNG_ERR_INVALID_ARG             # equal neighbours
+    assert verdict(lambda p: set_rowptr(p, 1, 10, int(shards[1][0][9]) - 1)) == B.TNG_ERR_INVALID_ARG    # decreasing
+    assert verdict(lambda p: set_rowptr(p, 0, n, n * nnz_row + 1)) == B.TNG_ERR_INVALID_ARG              # past the entries
+    assert verdict(lambda p: set_rowptr(p, 0, 0, -3)) == B.TNG_ERR_INVALID_ARG                           # negative start
+    assert verdict() == B.TNG_OK
+    ctx.close()
+
+
 def test_external_gradients_and_separate_calls_equal_the_fused_step():
     d, M = 4096 * 3 + 4, 4
     g, gref0 = synth.codec_inputs(M, d, 9, device=DEV)
