@@ -135,6 +135,19 @@ tng_status tng_set_logreg_dense(tng_ctx* ctx, const float* const* X, const float
 tng_status tng_set_logreg_csr(tng_ctx* ctx, const int64_t* const* rowptr,
                               const int32_t* const* col, const float* const* val,
                               const float* const* y, const uint64_t* n_rows);
+/* The same shards with the stored entries of a row as (column, value) pairs in one array instead of two
+ * parallel arrays: entries[m] is a device array of tng_csr_entry, 8-byte aligned, entry k of row i at
+ * rowptr[i] + k, columns ascending within each row as above.  The gradient kernels read the entries of a
+ * row in short runs (the part of the row that falls into one column tile); with pairs such a run is one
+ * contiguous piece of memory instead of two, which is what their speed depends on: prefer this layout
+ * (faster per iteration at d = 2^24, 0.1 % density).  The two layouts give the same results.
+ * Everything said for tng_set_logreg_csr applies. */
+typedef struct {
+  int32_t col;
+  float val;
+} tng_csr_entry;
+tng_status tng_set_logreg_csr_pairs(tng_ctx* ctx, const int64_t* const* rowptr, const tng_csr_entry* const* entries,
+                                    const float* const* y, const uint64_t* n_rows);
 /* Optional, CSR problem: checks the shards given to the last tng_set_logreg_csr against what the
  * gradient kernels assume and cannot check on the hot path: row pointers non-negative and
  * non-decreasing, ending within the nnz[m] entries stored for worker m (nnz: host array of M counts =

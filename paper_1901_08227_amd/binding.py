@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
             "tng_set_logreg_dense": [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(u64)],
             "tng_set_logreg_csr": [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                    ctypes.POINTER(vp), ctypes.POINTER(u64)],
+            "tng_set_logreg_csr_pairs": [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                         ctypes.POINTER(u64)],
             "tng_validate_csr": [vp, ctypes.POINTER(u64)],
             "tng_set_noise": [vp, vp],
             "tng_set_noise_variance": [vp, ctypes.c_float],
@@ -115,6 +117,15 @@ def _ptr(t, dtype, numel, name):
     if t.numel() < numel:
         raise ValueError(f"{name}: needs {numel} elements, has {t.numel()}")
     return ctypes.c_void_p(t.data_ptr())
+
+
+def csr_pairs(col, val):
+    """(column, value) pairs for set_logreg_csr_pairs from parallel arrays: an int32 tensor [nnz][2] whose
+    second column holds the bit patterns of the float32 values (layout only; nothing is computed)."""
+    out = torch.empty((col.numel(), 2), dtype=torch.int32, device=col.device)
+    out[:, 0] = col
+    out[:, 1] = val.view(torch.int32)
+    return out
 
 
 class Context:
@@ -178,13 +189,28 @@ class Context:
         tv = self._table(val, torch.float32, nnz, "val")
         ty = self._table(y, torch.float32, n, "y")
         self._keep["data"] = (list(rowptr), list(col), list(val), list(y))
+        self._keep["nnz"] = nnz
         self.n_rows = n
         _check(lib().tng_set_logreg_csr(self.handle, tr, tc, tv, ty, rows), "tng_set_logreg_csr")
+
+    def set_logreg_csr_pairs(self, rowptr, entries, y):
+        """entries: list of M int32 tensors [nnz_m][2]: column id and the bit pattern of the float32 value
+        (see csr_pairs), i.e. an array of tng_csr_entry."""
+        n = [int(r.numel()) - 1 for r in rowptr]
+        rows = (ctypes.c_uint64 * self.M)(*n)
+        nnz = [int(e.numel()) // 2 for e in entries]
+        tr = self._table(rowptr, torch.int64, [k + 1 for k in n], "rowptr")
+        te = self._table(entries, torch.int32, [2 * k for k in nnz], "entries")
+        ty = self._table(y, torch.float32, n, "y")
+        self._keep["data"] = (list(rowptr), list(entries), None, list(y))
+        self._keep["nnz"] = nnz
+        self.n_rows = n
+        _check(lib().tng_set_logreg_csr_pairs(self.handle, tr, te, ty, rows), "tng_set_logreg_csr_pairs")
 
     def validate_csr(self):
         """Device pass over the CSR shards set last: raises TngError(TNG_ERR_INVALID_ARG) if row pointers or
         column ids break what the gradient kernels assume."""
-        nnz = (ctypes.c_uint64 * self.M)(*[int(c.numel()) for c in self._keep["data"][1]])
+        nnz = (ctypes.c_uint64 * self.M)(*self._keep["nnz"])
         _check(lib().tng_validate_csr(self.handle, nnz), "tng_validate_csr")
 
     def build_csr_index(self):

@@ -25,6 +25,7 @@ struct tng_ctx {
   uint32_t* bounds;       // [M][tiles+1][batch] segment bounds of the CSR gradient
   float* zpart;           // [M][tiles][batch] per-tile partial dot products of the CSR gradient
   bool have_dense, have_csr;
+  bool csr_pairs;         // the CSR shards hold (column, value) pairs instead of two arrays
   const float* noise;     // Rosenbrock noise, may be null
   float noise_sigma;      // > 0: Gaussian noise is generated on the device instead
   const float* gref2;     // second reference of the combined normalisation
@@ -161,6 +162,7 @@ tng::LogregData logreg_tables(const tng_ctx* ctx) {
   p.y = reinterpret_cast<const float* const*>(t + 3 * (size_t)M);
   p.n_rows = reinterpret_cast<const uint64_t*>(t + 4 * (size_t)M);
   p.tile_index = ctx->have_index ? reinterpret_cast<const uint32_t* const*>(t + 5 * (size_t)M) : nullptr;
+  p.pairs = ctx->csr_pairs;
   return p;
 }
 
@@ -357,6 +359,7 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->check = reinterpret_cast<uint32_t*>(base + p.check_off);
   ctx->have_dense = ctx->have_csr = false;
   ctx->have_index = false;
+  ctx->csr_pairs = false;
   ctx->noise = nullptr;
   ctx->noise_sigma = 0.f;
   ctx->gref2 = nullptr;
@@ -395,7 +398,30 @@ tng_status tng_set_logreg_csr(tng_ctx* ctx, const int64_t* const* rowptr, const 
                                      reinterpret_cast<const void* const*>(col),
                                      reinterpret_cast<const void* const*>(val),
                                      reinterpret_cast<const void* const*>(y), n_rows);
-  if (s == TNG_OK) ctx->have_csr = true;
+  if (s == TNG_OK) {
+    ctx->have_csr = true;
+    ctx->csr_pairs = false;
+  }
+  return s;
+}
+
+tng_status tng_set_logreg_csr_pairs(tng_ctx* ctx, const int64_t* const* rowptr, const tng_csr_entry* const* entries,
+                                    const float* const* y, const uint64_t* n_rows) {
+  if (ctx == nullptr || rowptr == nullptr || entries == nullptr || y == nullptr || n_rows == nullptr)
+    return TNG_ERR_INVALID_ARG;
+  if (ctx->cfg.problem != TNG_PROB_LOGREG_CSR) return TNG_ERR_BAD_STATE;
+  for (uint32_t m = 0; m < ctx->cfg.M; ++m)
+    if (!aligned(entries[m], 8)) return TNG_ERR_INVALID_ARG;
+  // the pairs take the place of the column array; the value slot repeats the pointer so that the
+  // common table check (no null entries) applies unchanged
+  const tng_status s = upload_tables(ctx, reinterpret_cast<const void* const*>(rowptr),
+                                     reinterpret_cast<const void* const*>(entries),
+                                     reinterpret_cast<const void* const*>(entries),
+                                     reinterpret_cast<const void* const*>(y), n_rows);
+  if (s == TNG_OK) {
+    ctx->have_csr = true;
+    ctx->csr_pairs = true;
+  }
   return s;
 }
 

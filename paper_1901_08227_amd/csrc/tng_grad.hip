@@ -73,6 +73,22 @@ __device__ __forceinline__ void load_refs4(const ScaleFusion& f, uint64_t q, flo
   if (f.norm == kNormComb) r2 = reinterpret_cast<const float4*>(f.gref2)[q];
 }
 
+// The same two helpers with the kind of normalisation known at compile time: no branch around the loads,
+// so the compiler can count them (see the pipelined CSR gradient kernel).
+template <int NORM>
+__device__ __forceinline__ void load_refs4_t(const ScaleFusion& f, uint64_t q, float4& r1, float4& r2) {
+  r1 = make_float4(0.f, 0.f, 0.f, 0.f);
+  r2 = make_float4(1.f, 1.f, 1.f, 1.f);
+  if (NORM != kNormNone) r1 = reinterpret_cast<const float4*>(f.gref)[q];
+  if (NORM == kNormComb) r2 = reinterpret_cast<const float4*>(f.gref2)[q];
+}
+
+template <int NORM>
+__device__ __forceinline__ float absmax4_t(const ScaleFusion& f, const float4& g, const float4& r1, const float4& r2) {
+  return fmaxf(fmaxf(fabsf(normalize_dyn(NORM, g.x, r1.x, r2.x, f.eps)), fabsf(normalize_dyn(NORM, g.y, r1.y, r2.y, f.eps))),
+               fmaxf(fabsf(normalize_dyn(NORM, g.z, r1.z, r2.z, f.eps)), fabsf(normalize_dyn(NORM, g.w, r1.w, r2.w, f.eps))));
+}
+
 // sigma(z) - y without cancellation for the labels 0 and 1.
 __device__ __forceinline__ float logistic_residual(float z, float y) {
   const float e = expf(-fabsf(z));           // in (0, 1]
@@ -318,9 +334,49 @@ constexpr int kCsrUnroll = 16;     // row segments in flight per lane group
 constexpr uint32_t kCsrGroups = kCsrThreads / kCsrLanes;
 static_assert(kCsrGroups * kCsrUnroll == kCsrRows, "one sweep of the lane groups covers one trip");
 
+// The stored entries of one worker's shard, in either of the two layouts the library takes: separate
+// column and value arrays, or one array of (column, value) pairs.  With pairs a row segment of a
+// tile is one contiguous piece of 8 bytes per entry instead of two pieces of 4: segments are short
+// (16 entries per row and tile at 0.1 % density), and what such reads deliver is set by the 128-byte
+// memory lines they touch, so one piece of twice the length moves the same entries in about two
+// thirds of the line traffic, with half the load instructions.
+typedef int v2i_t __attribute__((ext_vector_type(2)));
+template <bool PAIRS>
+struct CsrEntries {
+  GlobalPtr<int32_t> c;  // column ids, or the pairs viewed as 32-bit words (column at 2 pos, value at 2 pos + 1)
+  GlobalPtr<float> v;    // values (unused with pairs)
+  __device__ __forceinline__ CsrEntries(const int32_t* cols, const float* vals) : c(as_global(cols)), v(as_global(vals)) {}
+  __device__ __forceinline__ int32_t col(int64_t pos) const { return PAIRS ? c[2 * pos] : c[pos]; }
+  __device__ __forceinline__ void load(int64_t pos, int32_t& col, float& val) const {
+    if (PAIRS) {
+      const v2i_t p = reinterpret_cast<GlobalPtr<v2i_t>>(c)[pos];
+      col = p.x;
+      val = __int_as_float(p.y);
+    } else {
+      col = c[pos];
+      val = v[pos];
+    }
+  }
+  // The same without a branch: entry pos if on, else whatever lies at dummy (any 8 valid bytes, 8-byte aligned).
+  __device__ __forceinline__ void load_or(bool on, int64_t pos, const void* dummy, int32_t& col, float& val) const {
+    if (PAIRS) {
+      const GlobalPtr<v2i_t> at = on ? reinterpret_cast<GlobalPtr<v2i_t>>(c) + pos : (GlobalPtr<v2i_t>)dummy;
+      const v2i_t p = *at;
+      col = p.x;
+      val = __int_as_float(p.y);
+    } else {
+      const GlobalPtr<int32_t> ac = on ? c + pos : (GlobalPtr<int32_t>)dummy;
+      const GlobalPtr<float> av = on ? v + pos : (GlobalPtr<float>)dummy;
+      col = *ac;
+      val = *av;
+    }
+  }
+};
+
 // rowbase[m][i] = position of minibatch row i in worker m's col / val arrays; bounds[m][t][i]
 // (tile-major, so that a workgroup reads the bounds of all its rows contiguously) = offset within
 // the row of the first entry whose column is at or beyond the start of tile t; t = 0 .. ntiles.
+template <bool PAIRS>
 __global__ __launch_bounds__(kBlock) void csr_bounds_kernel(const int64_t* const* __restrict__ rowptrs,
                                                             const int32_t* const* __restrict__ cols,
                                                             const uint32_t* __restrict__ idx,
@@ -331,18 +387,19 @@ __global__ __launch_bounds__(kBlock) void csr_bounds_kernel(const int64_t* const
   const uint32_t row = idx[(uint64_t)m * batch + i];
   const int64_t a = as_global(rowptrs[m])[row];
   const uint32_t nnz = (uint32_t)(as_global(rowptrs[m])[row + 1] - a);
-  const GlobalPtr<int32_t> c = as_global(cols[m]) + a;
+  const CsrEntries<PAIRS> e(cols[m], nullptr);
   if (threadIdx.x == 0) rowbase[(uint64_t)m * batch + i] = a;
   uint32_t* __restrict__ out = bounds + (uint64_t)m * (ntiles + 1) * batch + i;
   // entry k opens every tile after the tile of entry k-1 up to its own tile
   for (uint32_t k = threadIdx.x; k <= nnz; k += kBlock) {
-    const uint32_t prev = k == 0 ? 0u : ((uint32_t)c[k - 1] >> tile_shift) + 1u;
-    const uint32_t cur = k == nnz ? ntiles : ((uint32_t)c[k] >> tile_shift);
+    const uint32_t prev = k == 0 ? 0u : ((uint32_t)e.col(a + k - 1) >> tile_shift) + 1u;
+    const uint32_t cur = k == nnz ? ntiles : ((uint32_t)e.col(a + k) >> tile_shift);
     for (uint32_t t = prev; t <= cur; ++t) out[(uint64_t)t * batch] = k;
   }
 }
 
 // One-off: the same offsets for every row of every shard, row-major (index[m][row][t]).
+template <bool PAIRS>
 __global__ __launch_bounds__(kBlock) void csr_tile_index_kernel(const int64_t* const* __restrict__ rowptrs,
                                                                 const int32_t* const* __restrict__ cols,
                                                                 const uint64_t* __restrict__ n_rows,
@@ -353,11 +410,11 @@ __global__ __launch_bounds__(kBlock) void csr_tile_index_kernel(const int64_t* c
   if (row >= n_rows[m]) return;
   const int64_t a = as_global(rowptrs[m])[row];
   const uint32_t nnz = (uint32_t)(as_global(rowptrs[m])[row + 1] - a);
-  const GlobalPtr<int32_t> c = as_global(cols[m]) + a;
+  const CsrEntries<PAIRS> e(cols[m], nullptr);
   uint32_t* __restrict__ out = const_cast<uint32_t*>(index[m]) + row * (ntiles + 1);
   for (uint32_t k = threadIdx.x; k <= nnz; k += kBlock) {
-    const uint32_t prev = k == 0 ? 0u : ((uint32_t)c[k - 1] >> tile_shift) + 1u;
-    const uint32_t cur = k == nnz ? ntiles : ((uint32_t)c[k] >> tile_shift);
+    const uint32_t prev = k == 0 ? 0u : ((uint32_t)e.col(a + k - 1) >> tile_shift) + 1u;
+    const uint32_t cur = k == nnz ? ntiles : ((uint32_t)e.col(a + k) >> tile_shift);
     for (uint32_t t = prev; t <= cur; ++t) out[t] = k;
   }
 }
@@ -382,6 +439,7 @@ __global__ __launch_bounds__(kBlock) void csr_validate_rowptr_kernel(const int64
   if (bad != 0) atomicOr(flag, 1u);
 }
 
+template <bool PAIRS>
 __global__ __launch_bounds__(kBlock) void csr_validate_cols_kernel(const int64_t* const* __restrict__ rowptrs,
                                                                    const int32_t* const* __restrict__ cols,
                                                                    const uint64_t* __restrict__ n_rows, uint64_t d,
@@ -391,11 +449,11 @@ __global__ __launch_bounds__(kBlock) void csr_validate_cols_kernel(const int64_t
   uint32_t bad = 0;
   for (uint64_t row = blockIdx.x; row < n; row += gridDim.x) {
     const int64_t a = as_global(rowptrs[m])[row], b = as_global(rowptrs[m])[row + 1];
-    const GlobalPtr<int32_t> c = as_global(cols[m]);
+    const CsrEntries<PAIRS> e(cols[m], nullptr);
     for (int64_t k = a + threadIdx.x; k < b; k += kBlock) {
-      const int32_t cur = c[k];
+      const int32_t cur = e.col(k);
       if (cur < 0 || (uint64_t)cur >= d) bad |= 2u;
-      if (k > a && c[k - 1] >= cur) bad |= 4u;
+      if (k > a && e.col(k - 1) >= cur) bad |= 4u;
     }
   }
   if (bad != 0) atomicOr(flag, bad);
@@ -455,23 +513,20 @@ struct CsrBatch {
   float val[kCsrUnroll];
 };
 
-__device__ __forceinline__ void csr_load_batch(GlobalPtr<int32_t> c, GlobalPtr<float> v,
-                                               const int64_t* sLo, const uint32_t* sLen, uint32_t j0, uint32_t count,
-                                               uint32_t gl, CsrBatch& b) {
+template <bool PAIRS>
+__device__ __forceinline__ void csr_load_batch(const CsrEntries<PAIRS>& e, const int64_t* sLo, const uint32_t* sLen,
+                                               uint32_t j0, uint32_t count, uint32_t gl, CsrBatch& b) {
 #pragma unroll
   for (int u = 0; u < kCsrUnroll; ++u) {
     const uint32_t j = j0 + u;
     b.len[u] = j < count ? sLen[j] : 0u;
     b.col[u] = 0;
     b.val[u] = 0.f;
-    if (gl < b.len[u]) {
-      const int64_t lo = sLo[j];
-      b.col[u] = c[lo + gl];
-      b.val[u] = v[lo + gl];
-    }
+    if (gl < b.len[u]) e.load(sLo[j] + gl, b.col[u], b.val[u]);
   }
 }
 
+template <bool PAIRS>
 __global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int32_t* const* __restrict__ cols,
                                                             const float* const* __restrict__ vals,
                                                             const int64_t* __restrict__ rowbase,
@@ -480,8 +535,8 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int32_t* const
                                                             uint64_t d, uint32_t batch, uint32_t ntiles,
                                                             uint32_t tile_shift) {
   extern __shared__ float wtile[];  // w over the tile's columns
-  __shared__ int64_t sLo[kCsrRows];
-  __shared__ uint32_t sLen[kCsrRows];
+  __shared__ __align__(16) int64_t sLo[kCsrRows];
+  __shared__ __align__(16) uint32_t sLen[kCsrRows];
   // workers vary fastest across the grid: the workgroups that run side by side share one tile of w
   const uint32_t m = blockIdx.x, t = blockIdx.y;
   const uint32_t T = 1u << tile_shift;
@@ -500,8 +555,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int32_t* const
   } else {
     for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) wtile[j] = c0 + j < d ? w[c0 + j] : 0.f;
   }
-  const GlobalPtr<int32_t> c = as_global(cols[m]);
-  const GlobalPtr<float> v = as_global(vals[m]);
+  const CsrEntries<PAIRS> e(cols[m], vals[m]);
   const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
   for (uint32_t first = 0; first < batch; first += kCsrRows) {
     const uint32_t count = min((uint32_t)kCsrRows, batch - first);
@@ -510,13 +564,17 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int32_t* const
     __syncthreads();
     const uint32_t j0 = group * kCsrUnroll;
     CsrBatch b;
-    csr_load_batch(c, v, sLo, sLen, j0, count, gl, b);
+    csr_load_batch(e, sLo, sLen, j0, count, gl, b);
     float acc[kCsrUnroll];
 #pragma unroll
     for (int u = 0; u < kCsrUnroll; ++u) {
       acc[u] = gl < b.len[u] ? b.val[u] * wtile[(uint32_t)b.col[u] - (uint32_t)c0] : 0.f;
-      for (uint32_t k = gl + kCsrLanes; k < b.len[u]; k += kCsrLanes)  // rare: segments longer than the lane group
-        acc[u] = __builtin_fmaf(v[sLo[j0 + u] + k], wtile[(uint32_t)c[sLo[j0 + u] + k] - (uint32_t)c0], acc[u]);
+      for (uint32_t k = gl + kCsrLanes; k < b.len[u]; k += kCsrLanes) {  // rare: segments longer than the lane group
+        int32_t ck;
+        float vk;
+        e.load(sLo[j0 + u] + k, ck, vk);
+        acc[u] = __builtin_fmaf(vk, wtile[(uint32_t)ck - (uint32_t)c0], acc[u]);
+      }
     }
     // 16 sums over 32 lanes by halving: after the four exchange steps lane l holds the partial sum
     // of segment (bit4 bit3 bit2 bit1 of l) over the lanes that share those bits.
@@ -541,6 +599,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_kernel(const int32_t* const
 // partial ones.  (Random contiguous segments deliver 2.2 TB/s of useful bytes at 64 bytes per
 // segment and 3.2 TB/s at 128; this pass is bound by exactly that.)  One partial sum per row and pair
 // of tiles: zparts[m][pair][i].
+template <bool PAIRS>
 __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* const* __restrict__ cols,
                                                                  const float* const* __restrict__ vals,
                                                                  const int64_t* __restrict__ rowbase,
@@ -550,8 +609,8 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
                                                                  uint32_t batch, uint32_t ntiles, uint32_t npairs,
                                                                  uint32_t M, uint32_t workers_per_block) {
   extern __shared__ float wtile[];  // w over the columns of both tiles
-  __shared__ int64_t sLoBuf[2][kCsrRows];  // segment starts and lengths, this step's and the next one's
-  __shared__ uint32_t sLenBuf[2][kCsrRows];
+  __shared__ __align__(16) int64_t sLoBuf[2][kCsrRows];  // segment starts and lengths, this step's and the next one's
+  __shared__ __align__(16) uint32_t sLenBuf[2][kCsrRows];
   const uint32_t pair = blockIdx.y;
   const uint32_t t_lo = 2 * pair, t_hi = min(2 * pair + 2, ntiles);
   constexpr uint32_t T = 2u << kCsrTileShift;
@@ -599,8 +658,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
   {
     const uint32_t m = m_first + step / trips, first = (step % trips) * kCsrRows;
     float* __restrict__ zpart = zparts + ((uint64_t)m * npairs + pair) * batch;
-    const GlobalPtr<int32_t> c = as_global(cols[m]);
-    const GlobalPtr<float> v = as_global(vals[m]);
+    const CsrEntries<PAIRS> e(cols[m], vals[m]);
     const uint32_t count = min((uint32_t)kCsrRows, batch - first);
     const int64_t* sLo = sLoBuf[step & 1];
     const uint32_t* sLen = sLenBuf[step & 1];
@@ -617,11 +675,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
       for (int q = 0; q < 2; ++q) {
         col[u][q] = 0;
         val[u][q] = 0.f;
-        if (gl + (uint32_t)q * kCsrLanes < len[u]) {
-          const int64_t pos = sLo[j] + gl + q * kCsrLanes;
-          col[u][q] = c[pos];
-          val[u][q] = v[pos];
-        }
+        if (gl + (uint32_t)q * kCsrLanes < len[u]) e.load(sLo[j] + gl + q * kCsrLanes, col[u][q], val[u][q]);
       }
     }
     float acc[kCsrUnroll];
@@ -634,8 +688,12 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
     for (int u = 0; u < kCsrUnroll; ++u) {
       if (len[u] > 2u * kCsrLanes) {  // rare: longer than what the registers hold
         const int64_t lo = sLo[j0 + u];
-        for (uint32_t k = gl + 2 * kCsrLanes; k < len[u]; k += kCsrLanes)
-          acc[u] = __builtin_fmaf(v[lo + k], wtile[(uint32_t)c[lo + k] - (uint32_t)c0], acc[u]);
+        for (uint32_t k = gl + 2 * kCsrLanes; k < len[u]; k += kCsrLanes) {
+          int32_t ck;
+          float vk;
+          e.load(lo + k, ck, vk);
+          acc[u] = __builtin_fmaf(vk, wtile[(uint32_t)ck - (uint32_t)c0], acc[u]);
+        }
       }
     }
     float r8[8], r4[4], r2[2];
@@ -703,7 +761,7 @@ __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __res
 // keep a workgroup alive across tiles have in common: loads and stores share one in-order counter,
 // so the wait for the next tile's entries is also a wait for the previous tile's stores to be
 // acknowledged, while a workgroup that ends after its write-out leaves them to drain behind it.
-template <bool FUSE>
+template <bool FUSE, bool PAIRS>
 __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* const* __restrict__ cols,
                                                                const float* const* __restrict__ vals,
                                                                const int64_t* __restrict__ rowbase,
@@ -713,8 +771,8 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
                                                                uint64_t d, uint32_t batch, uint32_t ntiles,
                                                                uint32_t tile_shift, float l2, ScaleFusion fuse) {
   extern __shared__ double gtile[];  // g over the tile's columns, accumulated in fp64
-  __shared__ int64_t sLo[kCsrRows];
-  __shared__ uint32_t sLen[kCsrRows];
+  __shared__ __align__(16) int64_t sLo[kCsrRows];
+  __shared__ __align__(16) uint32_t sLen[kCsrRows];
   __shared__ float sR[kCsrRows];
   __shared__ float red[kCsrThreads / kWave];
   const uint32_t m = blockIdx.x, t = blockIdx.y;
@@ -728,8 +786,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
 #pragma unroll
     for (int k = 0; k < kPer; ++k) load_refs4(fuse, c0 / 4 + (uint32_t)k * kCsrThreads + threadIdx.x, r1[k], r2[k]);
   }
-  const GlobalPtr<int32_t> c = as_global(cols[m]);
-  const GlobalPtr<float> v = as_global(vals[m]);
+  const CsrEntries<PAIRS> e(cols[m], vals[m]);
   const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
   for (uint32_t first = 0; first < batch; first += kCsrRows) {
     const uint32_t count = min((uint32_t)kCsrRows, batch - first);
@@ -739,7 +796,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
     __syncthreads();
     const uint32_t j0 = group * kCsrUnroll;
     CsrBatch b;
-    csr_load_batch(c, v, sLo, sLen, j0, count, gl, b);
+    csr_load_batch(e, sLo, sLen, j0, count, gl, b);
     // LDS operations complete in order, so a read issued after an atomic add waits for it: the
     // residuals are read before the first add and the adds go out back to back.
     float r[kCsrUnroll];
@@ -752,8 +809,12 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
     for (int u = 0; u < kCsrUnroll; ++u) {
       if (b.len[u] > (uint32_t)kCsrLanes) {  // rare: segments longer than the lane group
         const int64_t lo = sLo[j0 + u];
-        for (uint32_t k = gl + kCsrLanes; k < b.len[u]; k += kCsrLanes)
-          atomicAdd(&gtile[(uint32_t)c[lo + k] - (uint32_t)c0], (double)(r[u] * v[lo + k]));
+        for (uint32_t k = gl + kCsrLanes; k < b.len[u]; k += kCsrLanes) {
+          int32_t ck;
+          float vk;
+          e.load(lo + k, ck, vk);
+          atomicAdd(&gtile[(uint32_t)ck - (uint32_t)c0], (double)(r[u] * vk));
+        }
       }
     }
   }
@@ -794,6 +855,147 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
       if (c0 + j < d) out[c0 + j] = l2 != 0.f ? __builtin_fmaf(l2, w[c0 + j], (float)gtile[j]) : (float)gtile[j];
     }
   }
+}
+
+// Workgroup barrier that orders LDS traffic only: global loads and stores still in flight are not
+// waited for (__syncthreads would wait until every one of them has come back).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// The gradient pass with the fused scale pass for the common case -- full tiles, no l2 term, at most
+// kCsrRows minibatch rows, 16-byte aligned rows of g -- as a software pipeline over a run of consecutive
+// tiles of one worker.  With one 128 KiB workgroup per compute unit nothing else hides a tile's chain of
+// dependent memory round trips (segment bounds, then entries, then the write-out), so the workgroup
+// overlaps them itself:
+//   while tile t's entries are added into the LDS tile, the segment bounds of tile t+1 are on their way;
+//   after the barrier that ends the adds, the entries of tile t+1 are requested BEFORE tile t is written
+//   out: loads and stores retire through one in-order counter, so the wait for those entries at the
+//   top of the next round only has to leave the (younger) stores outstanding, and the write-out, the
+//   clearing of the tile and the stores' acknowledgement all run under the entries' latency.
+// The barriers order LDS traffic only.  Lanes beyond a segment's length carry an invalid column.
+template <bool PAIRS, int NORM>
+__global__ __launch_bounds__(kCsrThreads) void csr_grad_run_kernel(const int32_t* const* __restrict__ cols,
+                                                                   const float* const* __restrict__ vals,
+                                                                   const int64_t* __restrict__ rowbase,
+                                                                   const uint32_t* __restrict__ bounds,
+                                                                   const float* __restrict__ resid,
+                                                                   float* __restrict__ g, uint64_t d, uint32_t batch,
+                                                                   uint32_t ntiles, uint32_t run, ScaleFusion fuse) {
+  extern __shared__ double gtile[];  // g over the tile's columns, accumulated in fp64
+  __shared__ __align__(16) int64_t sLoBuf[2][kCsrRows];
+  __shared__ __align__(16) uint32_t sLenBuf[2][kCsrRows];
+  __shared__ float sR[kCsrRows];
+  __shared__ float red[kCsrThreads / kWave];
+  constexpr uint32_t T = 1u << kCsrTileShift;
+  constexpr int kPer = (int)(T / (4 * kCsrThreads));
+  const uint32_t m = blockIdx.x;
+  const uint32_t t_first = blockIdx.y * run, t_end = min(t_first + run, ntiles);
+  const uint32_t row = min(threadIdx.x, batch - 1);  // every thread fetches bounds: no load under a condition
+  const uint32_t* __restrict__ b = bounds + (uint64_t)m * (ntiles + 1) * batch + row;
+  const int64_t base = rowbase[(uint64_t)m * batch + row];
+  const bool has_row = threadIdx.x < batch;
+  {
+    const uint32_t lo = b[(uint64_t)t_first * batch], hi = b[(uint64_t)(t_first + 1) * batch];
+    for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) gtile[j] = 0.0;
+    if (threadIdx.x < (uint32_t)kCsrRows) {
+      sR[threadIdx.x] = has_row ? resid[(uint64_t)m * batch + threadIdx.x] : 0.f;
+      sLoBuf[0][threadIdx.x] = base + lo;
+      sLenBuf[0][threadIdx.x] = has_row ? hi - lo : 0u;
+    }
+  }
+  const CsrEntries<PAIRS> e(cols[m], vals[m]);
+  const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
+  const uint32_t j0 = group * kCsrUnroll;
+  float* __restrict__ out = g + (uint64_t)m * d;
+  int32_t ncol[kCsrUnroll];
+  float nval[kCsrUnroll];
+  uint32_t nmask = 0;  // bit u: this lane holds an entry of segment u
+  uint32_t nlong = 0;  // bit u: segment u is longer than the lane group
+  // The first lane-width of entries of the group's segments.  Lanes beyond a segment's length read a
+  // harmless valid address (the worker's first row start) instead of skipping the load: the compiler
+  // cannot count loads that sit under a condition, and would then make every later wait a wait for all.
+  const void* dummy = rowbase + (uint64_t)m * batch;
+  auto request = [&](uint32_t buf) {
+    nmask = 0;
+    nlong = 0;
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u) {
+      const uint32_t len = sLenBuf[buf][j0 + u];
+      const bool on = gl < len;
+      e.load_or(on, sLoBuf[buf][j0 + u] + gl, dummy, ncol[u], nval[u]);
+      nmask |= on ? 1u << u : 0u;
+      nlong |= len > (uint32_t)kCsrLanes ? 1u << u : 0u;
+    }
+  };
+  auto store_maximum = [&](uint32_t t) {  // by thread 0, once red holds tile t's wavefront maxima
+    float mx = red[0];
+#pragma unroll
+    for (int k = 1; k < kCsrThreads / kWave; ++k) mx = fmaxf(mx, red[k]);
+    fuse.partials[(uint64_t)t * gridDim.x + m] = mx;
+  };
+  auto round = [&](uint32_t t) {
+    const uint32_t cur = (t - t_first) & 1u;
+    const uint64_t c0 = (uint64_t)t << kCsrTileShift;
+    // bounds of the next tile (clamped: a fetch, never a branch); past the run's end the lengths become 0
+    const uint32_t tn = min(t + 1, t_end - 1);
+    const uint32_t nlo = b[(uint64_t)tn * batch], nhi = b[(uint64_t)(tn + 1) * batch];
+    // LDS operations complete in order: the residuals are read before the first add
+    float r[kCsrUnroll];
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u) r[u] = sR[j0 + u];
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u)
+      if ((nmask >> u) & 1u) atomicAdd(&gtile[(uint32_t)ncol[u] - (uint32_t)c0], (double)(r[u] * nval[u]));
+    if (nlong != 0) {  // rare: segments longer than the lane group
+#pragma unroll
+      for (int u = 0; u < kCsrUnroll; ++u) {
+        if ((nlong >> u) & 1u) {
+          const uint32_t len = sLenBuf[cur][j0 + u];
+          const int64_t lo = sLoBuf[cur][j0 + u];
+          for (uint32_t k = gl + kCsrLanes; k < len; k += kCsrLanes) {
+            int32_t ck;
+            float vk;
+            e.load(lo + k, ck, vk);
+            atomicAdd(&gtile[(uint32_t)ck - (uint32_t)c0], (double)(r[u] * vk));
+          }
+        }
+      }
+    }
+    if (threadIdx.x < (uint32_t)kCsrRows) {
+      sLoBuf[cur ^ 1u][threadIdx.x] = base + nlo;
+      sLenBuf[cur ^ 1u][threadIdx.x] = (has_row && t + 1 < t_end) ? nhi - nlo : 0u;
+    }
+    lds_barrier();  // every add of tile t has been made; the segments of tile t+1 are staged
+    if (t > t_first && threadIdx.x == 0) store_maximum(t - 1);  // older than the request below: need not be counted
+    // the reference of the thread's columns for the fused scale pass, asked for ahead of the entries (loads
+    // come back in order: asked for after them, its arrival would be theirs); the kind of normalisation is a
+    // template argument so that no branch surrounds these loads either
+    float4 r1[kPer], r2[kPer];
+#pragma unroll
+    for (int k = 0; k < kPer; ++k)
+      load_refs4_t<NORM>(fuse, c0 / 4 + (uint32_t)k * kCsrThreads + threadIdx.x, r1[k], r2[k]);
+    request(cur ^ 1u);  // before the stores below
+    float4* __restrict__ out4 = reinterpret_cast<float4*>(out + c0);
+    float amax = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      const uint32_t q = (uint32_t)k * kCsrThreads + threadIdx.x;
+      const float4 o = make_float4((float)gtile[4 * q], (float)gtile[4 * q + 1], (float)gtile[4 * q + 2],
+                                   (float)gtile[4 * q + 3]);
+      gtile[4 * q] = gtile[4 * q + 1] = gtile[4 * q + 2] = gtile[4 * q + 3] = 0.0;
+      store_stream(out4 + q, o);
+      amax = fmaxf(amax, absmax4_t<NORM>(fuse, o, r1[k], r2[k]));
+    }
+    amax = wave_max(amax);
+    if (threadIdx.x % kWave == 0) red[threadIdx.x / kWave] = amax;
+    lds_barrier();  // the tile is clear again; red is complete
+  };
+  lds_barrier();
+  request(0);
+  // The first round stands apart from the loop: at the loop's head the compiler takes the weaker of what
+  // its two ways in allow to stay in flight, and only after a write-out are there stores that may.
+  round(t_first);
+  for (uint32_t t = t_first + 1; t < t_end; ++t) round(t);
+  if (threadIdx.x == 0) store_maximum(t_end - 1);
 }
 
 // Chain Rosenbrock gradient ("Nonconvex Problems", d-dimensional form) plus per-worker noise.
@@ -995,23 +1197,36 @@ hipError_t launch_csr_validate_rowptr(const LogregData& p, uint32_t M, uint64_t 
 
 hipError_t launch_csr_validate_cols(const LogregData& p, uint64_t d, uint32_t M, uint64_t max_rows, uint32_t* flag,
                                     hipStream_t s) {
-  hipLaunchKernelGGL(csr_validate_cols_kernel, dim3((uint32_t)(max_rows < 65535 ? max_rows : 65535), M), dim3(kBlock), 0, s,
-                     p.rowptr, p.col, p.n_rows, d, flag);
+  const dim3 grid((uint32_t)(max_rows < 65535 ? max_rows : 65535), M);
+  if (p.pairs)
+    hipLaunchKernelGGL(csr_validate_cols_kernel<true>, grid, dim3(kBlock), 0, s, p.rowptr, p.col, p.n_rows, d, flag);
+  else
+    hipLaunchKernelGGL(csr_validate_cols_kernel<false>, grid, dim3(kBlock), 0, s, p.rowptr, p.col, p.n_rows, d, flag);
   return hipGetLastError();
 }
 
 hipError_t launch_csr_tile_index(const LogregData& p, uint64_t d, uint32_t M, uint64_t max_rows, hipStream_t s) {
   if (max_rows == 0 || max_rows > 0x7fffffffull || p.tile_index == nullptr) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(csr_tile_index_kernel, dim3((uint32_t)max_rows, M), dim3(kBlock), 0, s, p.rowptr, p.col, p.n_rows,
-                     p.tile_index, csr_tiles(d), csr_tile_shift(d));
+  const dim3 grid((uint32_t)max_rows, M);
+  if (p.pairs)
+    hipLaunchKernelGGL(csr_tile_index_kernel<true>, grid, dim3(kBlock), 0, s, p.rowptr, p.col, p.n_rows, p.tile_index,
+                       csr_tiles(d), csr_tile_shift(d));
+  else
+    hipLaunchKernelGGL(csr_tile_index_kernel<false>, grid, dim3(kBlock), 0, s, p.rowptr, p.col, p.n_rows, p.tile_index,
+                       csr_tiles(d), csr_tile_shift(d));
   return hipGetLastError();
 }
 
-hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
-                                  const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,
-                                  const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
-                                  hipStream_t s) {
-  if (fused_rows != nullptr) *fused_rows = 0;
+namespace {
+
+// Tiles per workgroup of the pipelined gradient pass: 4.89 ms per iteration at 8, 4.81 at 16, 4.78 at 32
+// (d = 2^24, 64 workers, minibatch 512; 5.18 ms with one tile per workgroup).
+constexpr uint32_t kCsrRun = 16;
+
+template <bool PAIRS>
+hipError_t csr_grad_launches(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2, const uint32_t* idx,
+                             int64_t* rowbase, uint32_t* bounds, float* zpart, float* z, const float* w, float* g,
+                             const ScaleFusion* fuse, uint32_t* fused_rows, hipStream_t s) {
   const float inv_b = 1.0f / (float)batch;
   const uint32_t shift = csr_tile_shift(d);
   const uint32_t ntiles = csr_tiles(d);
@@ -1023,12 +1238,17 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     std::lock_guard<std::mutex> attr_lock(attr_mutex);
     if (!attr_done[dev]) {
-      const void* big_lds[] = {reinterpret_cast<const void*>(csr_grad_kernel<false>),
-                               reinterpret_cast<const void*>(csr_grad_kernel<true>),
-                               reinterpret_cast<const void*>(csr_z_wide_kernel)};
-      const int bytes[] = {(int)(sizeof(double) << kCsrTileShift), (int)(sizeof(double) << kCsrTileShift),
+      const int lds_double = (int)(sizeof(double) << kCsrTileShift);
+      const void* big_lds[] = {reinterpret_cast<const void*>(csr_grad_kernel<false, PAIRS>),
+                               reinterpret_cast<const void*>(csr_grad_kernel<true, PAIRS>),
+                               reinterpret_cast<const void*>(csr_grad_run_kernel<PAIRS, kNormNone>),
+                               reinterpret_cast<const void*>(csr_grad_run_kernel<PAIRS, kNormSub>),
+                               reinterpret_cast<const void*>(csr_grad_run_kernel<PAIRS, kNormQuot>),
+                               reinterpret_cast<const void*>(csr_grad_run_kernel<PAIRS, kNormComb>),
+                               reinterpret_cast<const void*>(csr_z_wide_kernel<PAIRS>)};
+      const int bytes[] = {lds_double, lds_double, lds_double, lds_double, lds_double, lds_double,
                            (int)(2 * sizeof(float) << kCsrTileShift)};
-      for (int k = 0; k < 3; ++k) {
+      for (int k = 0; k < 7; ++k) {
         const hipError_t e = hipFuncSetAttribute(big_lds[k], hipFuncAttributeMaxDynamicSharedMemorySize, bytes[k]);
         if (e != hipSuccess) return e;
       }
@@ -1040,7 +1260,7 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
     hipLaunchKernelGGL(csr_gather_bounds_kernel, grid, dim3(kBlock), 0, s, p.rowptr, p.tile_index, idx, rowbase, bounds,
                        batch, ntiles);
   } else {
-    hipLaunchKernelGGL(csr_bounds_kernel, dim3(batch, M), dim3(kBlock), 0, s, p.rowptr, p.col, idx, rowbase, bounds,
+    hipLaunchKernelGGL(csr_bounds_kernel<PAIRS>, dim3(batch, M), dim3(kBlock), 0, s, p.rowptr, p.col, idx, rowbase, bounds,
                        batch, ntiles, shift);
   }
   uint32_t nparts = ntiles;  // partial dot products per row
@@ -1048,10 +1268,10 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
     nparts = (ntiles + 1) / 2;
     uint32_t wpb = 1;  // workers per workgroup while 2048 workgroups remain
     while (wpb < 8 && wpb * 2 <= M && (uint64_t)nparts * (M / (wpb * 2)) >= 2048) wpb *= 2;
-    hipLaunchKernelGGL(csr_z_wide_kernel, dim3((M + wpb - 1) / wpb, nparts), dim3(kCsrThreads), 2 * lds_w, s, p.col, p.val,
-                       rowbase, bounds, w, zpart, d, batch, ntiles, nparts, M, wpb);
+    hipLaunchKernelGGL(csr_z_wide_kernel<PAIRS>, dim3((M + wpb - 1) / wpb, nparts), dim3(kCsrThreads), 2 * lds_w, s, p.col,
+                       p.val, rowbase, bounds, w, zpart, d, batch, ntiles, nparts, M, wpb);
   } else {
-    hipLaunchKernelGGL(csr_z_kernel, dim3(M, ntiles), dim3(kCsrThreads), lds_w, s, p.col, p.val, rowbase, bounds, w,
+    hipLaunchKernelGGL(csr_z_kernel<PAIRS>, dim3(M, ntiles), dim3(kCsrThreads), lds_w, s, p.col, p.val, rowbase, bounds, w,
                        zpart, d, batch, ntiles, shift);
   }
   hipLaunchKernelGGL(csr_z_reduce_kernel, dim3((batch + kBlock - 1) / kBlock, M), dim3(kBlock), 0, s, zpart, p.y, idx,
@@ -1059,14 +1279,40 @@ hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, u
   // The scale pass rides along when every tile is a full one and the write-out is the plain one.
   if (fuse != nullptr && fused_rows != nullptr && shift == kCsrTileShift && d % (1ull << kCsrTileShift) == 0 &&
       l2 == 0.f && ntiles <= kAbsmaxMaxBlocks && aligned16(g) && aligned16(fuse->gref) && aligned16(fuse->gref2)) {
-    hipLaunchKernelGGL(csr_grad_kernel<true>, dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, rowbase, bounds,
-                       z, w, g, d, batch, ntiles, shift, l2, *fuse);
+    if (batch <= (uint32_t)kCsrRows) {
+      const uint32_t run = kCsrRun;
+      const dim3 grid(M, (ntiles + run - 1) / run);
+#define TNG_RUN(NORM)                                                                                                   \
+  hipLaunchKernelGGL((csr_grad_run_kernel<PAIRS, NORM>), grid, dim3(kCsrThreads), lds_g, s, p.col, p.val, rowbase, bounds, \
+                     z, g, d, batch, ntiles, run, *fuse)
+      switch (fuse->norm) {
+        case kNormSub: TNG_RUN(kNormSub); break;
+        case kNormQuot: TNG_RUN(kNormQuot); break;
+        case kNormComb: TNG_RUN(kNormComb); break;
+        default: TNG_RUN(kNormNone); break;
+      }
+#undef TNG_RUN
+    } else {
+      hipLaunchKernelGGL((csr_grad_kernel<true, PAIRS>), dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val,
+                         rowbase, bounds, z, w, g, d, batch, ntiles, shift, l2, *fuse);
+    }
     *fused_rows = ntiles;
   } else {
-    hipLaunchKernelGGL(csr_grad_kernel<false>, dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, rowbase,
+    hipLaunchKernelGGL((csr_grad_kernel<false, PAIRS>), dim3(M, ntiles), dim3(kCsrThreads), lds_g, s, p.col, p.val, rowbase,
                        bounds, z, w, g, d, batch, ntiles, shift, l2, ScaleFusion{});
   }
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_logreg_csr_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
+                                  const uint32_t* idx, int64_t* rowbase, uint32_t* bounds, float* zpart, float* z,
+                                  const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
+                                  hipStream_t s) {
+  if (fused_rows != nullptr) *fused_rows = 0;
+  return p.pairs ? csr_grad_launches<true>(p, d, M, batch, l2, idx, rowbase, bounds, zpart, z, w, g, fuse, fused_rows, s)
+                 : csr_grad_launches<false>(p, d, M, batch, l2, idx, rowbase, bounds, zpart, z, w, g, fuse, fused_rows, s);
 }
 
 hipError_t launch_rosenbrock_grad(uint64_t d, uint32_t M, const float* x, const float* noise, NoiseGen gen, float* g,

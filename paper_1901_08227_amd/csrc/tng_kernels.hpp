@@ -85,8 +85,9 @@ hipError_t launch_single_pass(const CodecShape& c, uint32_t iter, const float* g
 struct LogregData {
   const float* const* X;        // device table [M] of dense shards (dense problem)
   const int64_t* const* rowptr; // device tables [M] (CSR problem)
-  const int32_t* const* col;
-  const float* const* val;
+  const int32_t* const* col;    // column ids; with pairs: the (column, value) pair arrays
+  const float* const* val;      // values; unused with pairs
+  bool pairs;                   // CSR entries are stored as (int32 column, float value) pairs
   const float* const* y;        // device table [M]
   const uint64_t* n_rows;       // device [M]
   const uint32_t* const* tile_index;  // device table [M] of per-row tile indices (CSR), or nullptr

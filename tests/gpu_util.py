@@ -15,6 +15,14 @@ def make_ctx(d, M, bits, norm, seed=0, **kw):
     return B.Context(d=d, M=M, bits=bits, norm=norm, seed=seed, device=DEV, **kw)
 
 
+def set_csr(ctx, shards, pairs):
+    """Hands CSR shards (rowptr, col, val, y per worker) to the library in either entry layout."""
+    if pairs:
+        ctx.set_logreg_csr_pairs([s[0] for s in shards], [B.csr_pairs(s[1], s[2]) for s in shards], [s[3] for s in shards])
+    else:
+        ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+
+
 def oracle_cfg(ctx, **kw):
     c = ctx.cfg
     return O.Config(d=int(c.d), M=int(c.M), bits=int(c.bits), norm=int(c.norm), quot_eps=float(c.quot_eps),

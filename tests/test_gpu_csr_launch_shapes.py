@@ -1,6 +1,7 @@
 """GPU parity of the CSR logistic iteration in the launch shapes of the sparse workload at its full
 dimension: d = 2^24, 0.1 % density, minibatch 512, 4-bit codes, subtraction normalisation, with the
-per-row tile index (what bench.py times).  At this dimension the dot-product pass hands a pair of
+per-row tile index and the entries stored as (column, value) pairs (what bench.py times), and with
+separate column and value arrays.  At this dimension the dot-product pass hands a pair of
 column tiles to a workgroup that serves 2, 4 or 8 workers in turn (1 in every small test): 64
 workers as in the workload (8 per workgroup), 8 and 16 workers (2 and 4), worker counts that the
 group size does not divide, and a minibatch longer than one staging trip together with a group of
@@ -17,7 +18,7 @@ import pytest
 import torch
 
 from oracle import tng_oracle as O
-from gpu_util import DEV, buffers, make_ctx, oracle_cfg, oracle_step_threaded, say, u32
+from gpu_util import DEV, buffers, make_ctx, oracle_cfg, oracle_step_threaded, say, set_csr, u32
 from oracle_pool import CsrGradientChecker
 from paper_1901_08227_amd import binding as B
 from paper_1901_08227_amd import synth
@@ -28,20 +29,22 @@ D = 1 << 24
 HOST_WORKERS = max(2, min(16, os.cpu_count() or 2))
 
 
-@pytest.mark.parametrize("M,batch,nnz_row,steps", [
-    (64, 512, 16777, 2),    # the sparse workload itself: 8 workers per workgroup in the dot-product pass
-    (8, 512, 16777, 2),     # 2 workers per workgroup
-    (16, 512, 16777, 2),    # 4 workers per workgroup
-    (9, 600, 4000, 2),      # 2 per workgroup, the last group short, two staging trips per worker
-    (18, 512, 4000, 1),     # 4 per workgroup, the last group holds 2
-    (36, 100, 2000, 1),     # 8 per workgroup, the last group holds 4, a short minibatch
+@pytest.mark.parametrize("M,batch,nnz_row,steps,pairs", [
+    (64, 512, 16777, 2, True),    # the sparse workload itself: 8 workers per workgroup in the dot-product pass
+    (64, 512, 16777, 1, False),   # the same with separate column and value arrays
+    (8, 512, 16777, 2, True),     # 2 workers per workgroup
+    (16, 512, 16777, 2, False),   # 4 workers per workgroup
+    (9, 600, 4000, 2, True),      # 2 per workgroup, the last group short, two staging trips per worker
+    (9, 600, 4000, 1, False),
+    (18, 512, 4000, 1, True),     # 4 per workgroup, the last group holds 2
+    (36, 100, 2000, 1, False),    # 8 per workgroup, the last group holds 4, a short minibatch
 ])
-def test_csr_logistic_full_dimension_worker_groups(M, batch, nnz_row, steps):
+def test_csr_logistic_full_dimension_worker_groups(M, batch, nnz_row, steps, pairs):
     n, seed = 512, 6 + M
-    say(f"csr logistic d=2^24 M={M} B={batch} nnz/row={nnz_row}: generating shards")
+    say(f"csr logistic d=2^24 M={M} B={batch} nnz/row={nnz_row} pairs={pairs}: generating shards")
     shards, _ = synth.logreg_csr(M, n, D, nnz_row, seed, device=DEV)
     ctx = make_ctx(D, M, 4, B.NORM_SUB, seed=seed, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR)
-    ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    set_csr(ctx, shards, pairs)
     ctx.build_csr_index()
     cfg = oracle_cfg(ctx)
     host = [tuple(t.cpu().numpy() for t in s) for s in shards]

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 from oracle import tng_oracle as O
-from gpu_util import (DEV, assert_row_sums_are_the_exact_ones, buffers, grad_close, logistic_condition, logistic_condition_csr, make_ctx, oracle_cfg,
+from gpu_util import (DEV, assert_row_sums_are_the_exact_ones, buffers, set_csr, grad_close, logistic_condition, logistic_condition_csr, make_ctx, oracle_cfg,
                       say, u32)
 from paper_1901_08227_amd import binding as B
 from paper_1901_08227_amd import synth
@@ -286,18 +286,19 @@ def test_every_normalisation_through_the_fused_step():
             ctx.close()
 
 
-@pytest.mark.parametrize("use_index,bits,norm,T", [(False, 4, B.NORM_SUB, 6), (True, 4, B.NORM_SUB, 100),
-                                                   (True, 2, B.NORM_QUOT, 6), (True, 4, B.NORM_NONE, 6)])
-def test_csr_logistic_scaled(use_index, bits, norm, T):
+@pytest.mark.parametrize("use_index,bits,norm,T,pairs", [(False, 4, B.NORM_SUB, 6, False), (True, 4, B.NORM_SUB, 100, True),
+                                                         (True, 4, B.NORM_SUB, 6, False), (False, 4, B.NORM_SUB, 6, True),
+                                                         (True, 2, B.NORM_QUOT, 6, True), (True, 4, B.NORM_NONE, 6, False)])
+def test_csr_logistic_scaled(use_index, bits, norm, T, pairs):
     # shape of the sparse configuration scaled to d=2^16, M=8, 0.1% density, 4-bit, subtraction, with the
     # prebuilt per-row tile index: all 100 iterations; without the index, and the other normalisations
     # through the scale pass that rides along with the gradient kernel's write-out: the first 6
     M, n, d, batch, seed = 8, 1024, 1 << 16, 128, 4
     nnz_row = round(1e-3 * d)
-    say(f"csr logistic d={d} M={M} nnz/row={nnz_row} index={use_index} bits={bits} norm={norm}")
+    say(f"csr logistic d={d} M={M} nnz/row={nnz_row} index={use_index} bits={bits} norm={norm} pairs={pairs}")
     shards, _ = synth.logreg_csr(M, n, d, nnz_row, seed, device=DEV)
     ctx = make_ctx(d, M, bits, norm, seed=seed, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR)
-    ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    set_csr(ctx, shards, pairs)
     if use_index:
         ctx.build_csr_index()
     cfg = oracle_cfg(ctx)
@@ -371,9 +372,10 @@ def _ragged_csr(M, n, d, lengths_fn, seed):
     return shards
 
 
+@pytest.mark.parametrize("pairs", [False, True])
 @pytest.mark.parametrize("use_index", [False, True])
 @pytest.mark.parametrize("case", ["ragged", "tiny_d", "odd_d_many_rows", "dense_rows"])
-def test_csr_logistic_edge_cases(case, use_index):
+def test_csr_logistic_edge_cases(case, use_index, pairs):
     if case == "ragged":        # empty rows, one-entry rows, rows longer than a lane group inside one tile
         M, n, d, batch = 3, 40, (1 << 15) + 24, 33
         lens = lambda m, i: [0, 1, 2, 700, 33, 5000][(i + m) % 6]
@@ -386,11 +388,11 @@ def test_csr_logistic_edge_cases(case, use_index):
     else:                       # nearly dense rows: many entries per (row, tile) segment
         M, n, d, batch = 2, 12, 1 << 14, 12
         lens = lambda m, i: (1 << 14) - 1 - i
-    say(f"csr edge case {case}: d={d} M={M} n={n} B={batch} index={use_index}")
+    say(f"csr edge case {case}: d={d} M={M} n={n} B={batch} index={use_index} pairs={pairs}")
     seed = 11
     shards = _ragged_csr(M, n, d, lens, seed)
     ctx = make_ctx(d, M, 4, B.NORM_SUB, seed=seed, lr=0.1, l2=0.001, batch=batch, problem=B.PROB_LOGREG_CSR)
-    ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    set_csr(ctx, shards, pairs)
     if use_index:
         ctx.build_csr_index()
     cfg = oracle_cfg(ctx)
@@ -412,6 +414,46 @@ def test_csr_logistic_edge_cases(case, use_index):
                 cond[m] = logistic_condition(Xb, host[m][3][ids[m]], w0, 0.001)
             return ref, cond
         _teacher_forced_step(ctx, cfg, it, w, gref, buf, grad_ref)
+    ctx.close()
+
+
+@pytest.mark.parametrize("pairs", [False, True])
+@pytest.mark.parametrize("norm", [B.NORM_SUB, B.NORM_QUOT, B.NORM_NONE, B.NORM_COMB])
+def test_csr_logistic_pipelined_gradient_pass(norm, pairs):
+    # full tiles, no l2 term, minibatch <= 512: the gradient pass that keeps a workgroup on a run of 16
+    # consecutive tiles (next tile's entries requested before this tile is written out), with the scale pass
+    # fused for each normalisation.  20 tiles: one full run and one of 4; empty rows, one-entry rows and rows
+    # with far more entries per tile than a lane group holds; fewer minibatch rows than staging slots
+    M, n, d, batch, seed = 3, 60, 20 << 14, 130, 23
+    lens = lambda m, i: [0, 1, 300, 9000, 40, 2500][(i + m) % 6]
+    say(f"csr pipelined gradient pass d={d} M={M} B={batch} norm={norm} pairs={pairs}")
+    shards = _ragged_csr(M, n, d, lens, seed)
+    ctx = make_ctx(d, M, 4, norm, seed=seed, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR)
+    set_csr(ctx, shards, pairs)
+    ctx.build_csr_index()
+    cfg = oracle_cfg(ctx)
+    host = [tuple(t.cpu().numpy() for t in s) for s in shards]
+    gen = torch.Generator(device=DEV).manual_seed(seed)
+    w = 0.1 * torch.randn(d, device=DEV, generator=gen)
+    gref = 1e-3 * torch.randn(d, device=DEV, generator=gen)
+    gref[::5] = 0.0
+    gref2 = torch.rand(d, device=DEV, generator=gen) + 0.5
+    if norm == B.NORM_COMB:
+        ctx.set_second_reference(gref2)
+    buf = buffers(ctx)
+    for it in range(2):
+        w0, r0 = w.cpu().numpy(), gref.cpu().numpy()
+        ctx.step(it, w, gref, buf["g"], buf["codes"], buf["scales"], buf["vbar"])
+        torch.cuda.synchronize()
+        gh = buf["g"].cpu().numpy()
+        for m in range(M):
+            ids = O.minibatch_indices(seed, it, m, batch, n)
+            ref = O.grad_logreg_csr(*host[m], w0, ids, d)
+            assert grad_close(gh[m], ref, logistic_condition_csr(*host[m], w0, ids, d)), f"it={it} m={m}: local gradient"
+        w1, r1, c1, s1, v1 = O.step(cfg, it, w0, r0, gh, gref2.cpu().numpy())
+        assert np.array_equal(buf["scales"].cpu().numpy(), s1), f"it={it}: scales from the fused partial maxima"
+        assert np.array_equal(u32(buf["codes"]), c1) and np.array_equal(buf["vbar"].cpu().numpy(), v1)
+        assert np.array_equal(w.cpu().numpy(), w1) and np.array_equal(gref.cpu().numpy(), r1)
     ctx.close()
 
 
@@ -439,6 +481,15 @@ def test_csr_tile_index_changes_nothing_but_the_speed():
     ctx.local_grad(3, w, g2)
     torch.cuda.synchronize()
     assert torch.equal(g0, g1) and torch.equal(g0, g2)
+    # the same shards as (column, value) pairs: the same gradient, bit for bit, with and without the index
+    # (per row and tile the same products are added in the same order)
+    g3, g4 = torch.empty((M, d), device=DEV), torch.empty((M, d), device=DEV)
+    set_csr(ctx, shards, pairs=True)
+    ctx.local_grad(3, w, g3)
+    ctx.build_csr_index()
+    ctx.local_grad(3, w, g4)
+    torch.cuda.synchronize()
+    assert torch.equal(g0, g3) and torch.equal(g0, g4)
     ctx.close()
 
 
@@ -450,11 +501,11 @@ def test_csr_validation_finds_what_the_gradient_kernels_cannot_check():
     shards, _ = synth.logreg_csr(M, n, d, nnz_row, seed, device=DEV)
     ctx = make_ctx(d, M, 2, B.NORM_SUB, seed=seed, batch=8, problem=B.PROB_LOGREG_CSR)
 
-    def verdict(mutate=None):
+    def verdict(mutate=None, pairs=False):
         parts = [[s[k].clone() for s in shards] for k in range(4)]
         if mutate is not None:
             mutate(parts)
-        ctx.set_logreg_csr(*parts)
+        set_csr(ctx, list(zip(*parts)), pairs)
         try:
             ctx.validate_csr()
             return B.TNG_OK
@@ -478,6 +529,11 @@ def test_csr_validation_finds_what_the_gradient_kernels_cannot_check():
     assert verdict(lambda p: set_rowptr(p, 0, n, n * nnz_row + 1)) == B.TNG_ERR_INVALID_ARG              # past the entries
     assert verdict(lambda p: set_rowptr(p, 0, 0, -3)) == B.TNG_ERR_INVALID_ARG                           # negative start
     assert verdict() == B.TNG_OK
+    # the same checks read the (column, value) pair layout
+    assert verdict(pairs=True) == B.TNG_OK
+    assert verdict(lambda p: set_col(p, 1, 7 * nnz_row + nnz_row - 1, d), pairs=True) == B.TNG_ERR_INVALID_ARG
+    assert verdict(lambda p: set_col(p, 2, 3 * nnz_row + 6, first), pairs=True) == B.TNG_ERR_INVALID_ARG
+    assert verdict(lambda p: set_rowptr(p, 0, n, n * nnz_row + 1), pairs=True) == B.TNG_ERR_INVALID_ARG
     ctx.close()
 
 
