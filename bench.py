@@ -181,20 +181,52 @@ def oracle_step_seconds(ctx, grads, w0):
     return time.perf_counter() - t0
 
 
-def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup, with_oracle=False):
+def step_bytes(kind, M, d, words, batch=0, nnz=0, ntiles=0, noise_tensor=False):
+    """HBM bytes of one tng_step, two ways.  `moved`: what the path as built transfers (every kernel's
+    operands once per kernel; the scale pass rides along with the gradient kernel, so g is written once and
+    read once).  `compulsory`: every operand of the iteration once (minibatch data once, g written and read
+    once, codes written and read once, the d-vectors w, g~, v once each way)."""
+    codes = 4 * M * words
+    vectors = 4 * d * 6                      # decode: g~ read, v written, w read + written, g~ refreshed; gradient: w read
+    codec = 4 * M * d + 4 * d + codes + codes   # quantise: g + g~ read, codes written; decode: codes read
+    if kind == "dense":
+        x = 4 * M * batch * d
+        return {"moved": 2 * x + 4 * M * d + codec + vectors, "compulsory": x + 4 * M * d + codec + vectors}
+    if kind == "csr":
+        entries = 8 * nnz
+        bounds = 4 * M * batch * (ntiles + 1)
+        # gather reads the index rows and writes the bounds; both passes read the bounds; partial dot products
+        # written and read once
+        side = 4 * bounds + 2 * 4 * M * batch * ((ntiles + 1) // 2)
+        return {"moved": 2 * entries + side + 4 * M * d + codec + vectors,
+                "compulsory": entries + 4 * M * d + codec + vectors}
+    if kind == "rosenbrock":
+        noise = 4 * M * d if noise_tensor else 0
+        both = noise + 4 * M * d + codec + vectors
+        return {"moved": both, "compulsory": both}
+    raise ValueError(kind)
+
+
+def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup, with_oracle=False, csr_rows=16384, dense_rows=0):
     """tng_step (local gradient + encode + decode + update + reference refresh) on the four training
-    workloads.  The two large logistic workloads keep their per-step shape (d, M, minibatch, density) but
-    hold fewer rows per worker than described: a step touches only the minibatch rows, so its traffic
-    does not depend on the shard size."""
+    workloads.  The sparse workload holds its full shards (64 workers x 16384 rows x 16777 entries, 141 GB)
+    when they fit; the wide dense workload holds the largest power-of-two number of rows per worker that
+    fits next to the other buffers (the full 65536 rows per worker are 256 GiB)."""
     out = []
 
-    def record(name, ms, algo_bytes, note, oracle=None):
-        out.append({"workload": name, "ms_per_step": round(ms, 4), "steps_per_s": round(1e3 / ms, 1),
-                    "algorithmic_GBps": round(algo_bytes / (ms * 1e-3) / 1e9, 1),
-                    "pct_hbm_peak": round(100 * algo_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2), "note": note})
+    def record(name, ms, nbytes, note, oracle=None, bound="hbm"):
+        rec = {"workload": name, "ms_per_step": round(ms, 4), "steps_per_s": round(1e3 / ms, 1),
+               "bytes_moved": nbytes["moved"], "bytes_compulsory": nbytes["compulsory"], "bound": bound}
+        if bound == "hbm":
+            rec["pct_hbm_peak_moved"] = round(100 * nbytes["moved"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)
+            rec["pct_hbm_peak_compulsory"] = round(100 * nbytes["compulsory"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)
+        else:       # no HBM percentage: the time is not set by HBM traffic
+            rec["pct_hbm_peak_moved"] = rec["pct_hbm_peak_compulsory"] = None
+        rec["note"] = note
         if oracle is not None:      # (seconds, what was timed): the numpy oracle, one iteration, single thread
-            out[-1]["oracle_ms_per_step"] = round(oracle[0] * 1e3, 2)
-            out[-1]["oracle_sample"] = oracle[1]
+            rec["oracle_ms_per_step"] = round(oracle[0] * 1e3, 2)
+            rec["oracle_sample"] = oracle[1]
+        out.append(rec)
 
     def logistic_oracle(ctx, Xs, ys, n, d, dense=True, shards=None):
         """Times the oracle on the rows the first minibatch touches (copied to the host beforehand)."""
@@ -213,6 +245,11 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup, with_oracle=
         host = [tuple(t.cpu().numpy() for t in sh) for sh in shards]
         return oracle_step_seconds(ctx, lambda O: [O.grad_logreg_csr(*host[m], w0, ids[m], d) for m in range(M)], w0)
 
+    def free_bytes():
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        return torch.cuda.mem_get_info(dev)[0]
+
     # small dense logistic regression: latency bound
     M, n, d, batch = 4, 2000, 1000, 64
     X, y, _ = synth.logreg_dense(M, n, d, seed=0, device=dev)
@@ -220,8 +257,9 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup, with_oracle=
     ctx.set_logreg_dense([X[m] for m in range(M)], [y[m] for m in range(M)])
     ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), steps * 4, warmup)
     orc = (logistic_oracle(ctx, X, y, n, d), "same shape") if with_oracle else None
-    record("dense logistic d=1000 M=4 B=64 ternary sub", ms, 2 * 4 * M * batch * d + 2 * (4 * M * d) + M * ctx.words * 8 + 24 * d,
-           "launch-latency bound", orc)
+    record("dense logistic d=1000 M=4 B=64 ternary sub", ms, step_bytes("dense", M, d, ctx.words, batch),
+           "3 kernel launches per iteration, 1 MB of minibatch rows: bound by launch latency, not by memory", orc,
+           bound="launch latency")
     ctx.close()
     del X, y
 
@@ -235,42 +273,64 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup, with_oracle=
     if with_oracle:
         x0, nz = synth.rosenbrock_start(d, 1, device=dev).cpu().numpy(), noises[0].cpu().numpy()
         orc = (oracle_step_seconds(ctx, lambda O: [O.grad_rosenbrock(x0, nz[m]) for m in range(M)], x0), "same shape")
-    record("Rosenbrock chain d=2^20 M=8 ternary sub", ms, 4 * M * d * 2 + 4 * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
-           "noise read + g write + two encode passes + decode/update", orc)
+    cache_note = ("3 launches; the 32 MiB of gradients written by one kernel are read by the next out of the 256 MB "
+                  "last-level cache: bound by launches and cache, not an HBM figure")
+    record("Rosenbrock chain d=2^20 M=8 ternary sub", ms, step_bytes("rosenbrock", M, d, ctx.words, noise_tensor=True),
+           "noise tensors of 8 iterations resident; " + cache_note, orc, bound="launch latency and last-level cache")
     del noises
     ctx.set_noise_variance(0.01)
     ms = time_steps(torch, ctx, step_state(torch, ctx, synth.rosenbrock_start(d, 1, device=dev)), steps, warmup)
     record("Rosenbrock chain d=2^20 M=8 ternary sub, noise generated on the device", ms,
-           4 * M * d + 4 * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
-           "g write + two encode passes + decode/update; Box-Muller on Philox draws inside the gradient kernel")
+           step_bytes("rosenbrock", M, d, ctx.words),
+           "Box-Muller on Philox draws inside the gradient kernel; " + cache_note,
+           bound="launch latency and last-level cache")
     ctx.close()
 
     # wide dense logistic regression, quotient normalisation
-    M, n, d, batch = 16, 8192, 1 << 16, 256
+    M, d, batch = 16, 1 << 16, 256
+    n = dense_rows
+    if n == 0:      # the largest power of two that fits, up to the 65536 rows of the workload
+        n = 65536
+        while n > 256 and M * n * d * 4 > free_bytes() - (12 << 30):
+            n //= 2
     X = [torch.randn((n, d), device=dev, generator=torch.Generator(device=dev).manual_seed(m)) for m in range(M)]
     y = [(torch.rand(n, device=dev) < 0.5).float() for _ in range(M)]
     ctx = B.Context(d=d, M=M, bits=2, norm=B.NORM_QUOT, seed=2, lr=0.1, batch=batch, problem=B.PROB_LOGREG_DENSE, device=dev)
     ctx.set_logreg_dense(X, y)
     ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), steps, warmup)
     orc = (logistic_oracle(ctx, X, y, n, d), "same shape, minibatch rows already on the host") if with_oracle else None
-    record("dense logistic d=2^16 M=16 B=256 2-bit quot", ms, 2 * 4 * M * batch * d + 3 * (4 * M * d) + M * ctx.words * 8 + 24 * d,
-           f"{n} rows per worker held (per-step traffic is that of the minibatch rows, read twice)", orc)
+    record("dense logistic d=2^16 M=16 B=256 2-bit quot", ms, step_bytes("dense", M, d, ctx.words, batch),
+           f"{n} of 65536 rows per worker resident ({M * n * d * 4 / 2**30:.0f} GiB: the largest power of two that fits); "
+           "the minibatch rows are read by the residual pass and again by the accumulation pass", orc)
     ctx.close()
-    del X, y
+    del X, y, ctx
 
     # sparse logistic regression at d = 2^24
-    M, n, d, batch = 64, 2048, 1 << 24, 512
+    M, d, batch = 64, 1 << 24, 512
     nnz_row = round(1e-3 * d)
-    shards, _ = synth.logreg_csr(M, n, d, nnz_row, seed=3, device=dev)
+    n = csr_rows
+    per_row = nnz_row * 8 + 8 + 4 * (d // 16384 + 1)        # entries + row pointer + tile index
+    while n > 512 and M * n * per_row + 3 * n * nnz_row * 8 > free_bytes() - (16 << 30):
+        n //= 2
+    log(f"  sparse shards: {M} workers x {n} rows x {nnz_row} entries ({M * n * nnz_row * 8 / 1e9:.0f} GB), (column, value) pairs")
+    rowptrs, pairs, ys = [], [], []
+    for m in range(M):       # one worker at a time: the generator's temporaries are three times a shard
+        (rp, col, val, yy), = synth.logreg_csr(1, n, d, nnz_row, seed=3 + m, device=dev)[0]
+        rowptrs.append(rp)
+        pairs.append(B.csr_pairs(col, val))
+        ys.append(yy)
+        del col, val
     ctx = B.Context(d=d, M=M, bits=4, norm=B.NORM_SUB, seed=3, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR, device=dev)
-    ctx.set_logreg_csr([s[0] for s in shards], [s[1] for s in shards], [s[2] for s in shards], [s[3] for s in shards])
+    ctx.set_logreg_csr_pairs(rowptrs, pairs, ys)
     ctx.build_csr_index()          # one-off, depends on the shards only
     ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), max(steps // 2, 5), max(warmup // 2, 2))
     nnz = M * batch * nnz_row
+    words = ctx.words
     ctx.close()
+    del rowptrs, pairs, ys, ctx
     orc = None
     if with_oracle:     # the oracle on the scaled shape the parity tests use: d = 2^16, 8 workers, same density
-        del shards
+        torch.cuda.empty_cache()
         Ms, ns, ds = 8, 2048, 1 << 16
         small, _ = synth.logreg_csr(Ms, ns, ds, round(1e-3 * ds), seed=3, device=dev)
         sctx = B.Context(d=ds, M=Ms, bits=4, norm=B.NORM_SUB, seed=3, lr=0.1, batch=batch, problem=B.PROB_LOGREG_CSR, device=dev)
@@ -278,9 +338,10 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup, with_oracle=
                "scaled to d=2^16, M=8, B=512, nnz/row=66 (1/2048 of the entries of the timed shape)")
         sctx.close()
     record("sparse logistic d=2^24 M=64 B=512 nnz/row=16777 4-bit sub", ms,
-           2 * 8 * nnz + 4 * M * d + 2 * (4 * M * d + 4 * d) + M * ctx.words * 8 + 24 * d,
-           f"{n} rows per worker held, per-row tile index prebuilt; bytes: (col, val) twice (z pass, g pass), "
-           "g written once, two encode passes, decode/update", orc)
+           step_bytes("csr", M, d, words, batch, nnz=nnz, ntiles=d // 16384),
+           f"{n} of 16384 rows per worker resident ({M * n * nnz_row * 8 / 1e9:.0f} GB of entries as (column, value) pairs), "
+           "per-row tile index prebuilt; the minibatch rows' entries are read by the dot-product pass and again by "
+           "the gradient pass", orc)
     return out
 
 
@@ -307,6 +368,11 @@ def measured_traffic(kernel, M, d, bits, norm_name):
     return rec["traffic_bytes_per_launch"].get(kernel)
 
 
+TRAFFIC_SOURCE = ("not measured in this run: from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary "
+                  "profiles/codec_M8_d2p27_ternary_sub_hbm_traffic.md, valid while the kernel sources hash to the value "
+                  "recorded there (null otherwise)")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -319,6 +385,10 @@ def main():
     ap.add_argument("--no-variants", action="store_true", help="time only the headline variant")
     ap.add_argument("--no-codec", action="store_true", help="skip the encode/decode microbenchmark (development aid)")
     ap.add_argument("--no-steps", action="store_true", help="skip the whole-iteration (tng_step) workloads")
+    ap.add_argument("--csr-rows", type=int, default=16384, help="rows per worker of the sparse workload's shards "
+                    "(halved until they fit)")
+    ap.add_argument("--dense-rows", type=int, default=0, help="rows per worker of the wide dense workload "
+                    "(0 = the largest power of two that fits)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain copy kernel of known size (d floats read, d floats written) three "
                          "times, as the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -335,7 +405,17 @@ def main():
     B.lib()  # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     if args.no_codec:
-        for r in whole_iteration_benchmarks(torch, B, synth, dev, 20, 5):
+        if args.copy_calibration:      # reference for scaling the counters of a profiler run over this mode
+            cal = torch.randn(1 << 27, device=dev)
+            cctx = B.Context(d=1 << 27, M=1, bits=2, norm=B.NORM_SUB, ref_policy=B.REF_LAST_AVG, ref_period=1, device=dev)
+            dst = torch.empty(1 << 27, device=dev)
+            for _ in range(3):
+                cctx.update_reference(0, cal, dst)   # copy_f32x4_kernel: reads 2^29 bytes, writes 2^29 bytes
+            torch.cuda.synchronize()
+            cctx.close()
+            del cal, dst
+        for r in whole_iteration_benchmarks(torch, B, synth, dev, args.steps, args.warmup, csr_rows=args.csr_rows,
+                                            dense_rows=args.dense_rows):
             print(json.dumps(r), flush=True)
         return
     M, d, seed = args.workers, 1 << args.log2d, 1
@@ -391,7 +471,8 @@ def main():
         del g, gref
         torch.cuda.empty_cache()
         log("timing whole iterations (tng_step) on the training workloads")
-        iteration_results = whole_iteration_benchmarks(torch, B, synth, dev, 20, 5, with_oracle=not args.no_cpu)
+        iteration_results = whole_iteration_benchmarks(torch, B, synth, dev, 20, 5, with_oracle=not args.no_cpu,
+                                                       csr_rows=args.csr_rows, dense_rows=args.dense_rows)
         g = gref = None
 
     dom_name = max(head["kernels"], key=lambda k: head["kernels"][k]["ms"])
@@ -425,7 +506,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(dom["GBps"], 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": dom["bytes"],
-                     "traffic": measured_traffic(dom_name, M, d, 2, "sub")},
+                     "traffic": measured_traffic(dom_name, M, d, 2, "sub"), "traffic_source": TRAFFIC_SOURCE},
     }
     if cpu is not None:
         out["cpu_baseline"] = cpu
