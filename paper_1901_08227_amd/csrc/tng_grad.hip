@@ -1070,39 +1070,68 @@ __global__ __launch_bounds__(kBlock) void rosenbrock_vec_kernel(const float* __r
                                                                 const float* __restrict__ noise, NoiseGen gen,
                                                                 float* __restrict__ g, uint64_t d, uint32_t M,
                                                                 ScaleFusion fuse) {
-  __shared__ float red[16];
+  constexpr int MC = 8;  // workers per trip: their noise loads are all in flight before the first is used
+  __shared__ float red[kWavesPerBlock][MC];
   const uint64_t nvec = d / 4;
   const uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   const bool active = q < nvec;
-  float4 base = make_float4(0.f, 0.f, 0.f, 0.f), r1 = base, r2 = base;
-  if (active) {
-    const float4 xv = reinterpret_cast<const float4*>(x)[q];
-    const bool first = q == 0, last = 4 * q + 4 >= d;
-    const float xl = first ? 0.f : x[4 * q - 1];
-    const float xr = last ? 0.f : x[4 * q + 4];
+  const uint64_t qc = active ? q : nvec - 1;  // idle threads of the last workgroup repeat its last float4 (and store nothing)
+  float4 base, r1, r2;
+  {
+    const float4 xv = reinterpret_cast<const float4*>(x)[qc];
+    const bool first = qc == 0, last = 4 * qc + 4 >= d;
+    const float xl = first ? 0.f : x[4 * qc - 1];
+    const float xr = last ? 0.f : x[4 * qc + 4];
     base.x = rosenbrock_component(xl, xv.x, xv.y, !first, true);
     base.y = rosenbrock_component(xv.x, xv.y, xv.z, true, true);
     base.z = rosenbrock_component(xv.y, xv.z, xv.w, true, true);
     base.w = rosenbrock_component(xv.z, xv.w, xr, true, !last);
-    if (FUSE) load_refs4(fuse, q, r1, r2);
+    r1 = r2 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (FUSE) load_refs4(fuse, qc, r1, r2);
   }
-  for (uint32_t m = 0; m < M; ++m) {
-    float amax = 0.f;
-    if (active) {
-      float4 o = base;
-      if (gen.sigma > 0.f || noise != nullptr) {
-        const float4 n = gen.sigma > 0.f ? gaussian4(gen, q, m) : load4_stream_any(as_global(noise) + (uint64_t)m * d, q);
-        o.x = base.x + n.x;
-        o.y = base.y + n.y;
-        o.z = base.z + n.z;
-        o.w = base.w + n.w;
-      }
-      store4_any(g + (uint64_t)m * d, q, o);
-      if (FUSE) amax = absmax4(fuse, o, r1, r2);
+  const bool from_tensor = !(gen.sigma > 0.f) && noise != nullptr;
+  const bool generated = gen.sigma > 0.f;
+  for (uint32_t m0 = 0; m0 < M; m0 += MC) {
+    float4 n[MC];
+    if (from_tensor) {
+#pragma unroll
+      for (int k = 0; k < MC; ++k)  // worker index clamped: a load, never a branch
+        n[k] = load4_stream_any(as_global(noise) + (uint64_t)min(m0 + k, M - 1) * d, qc);
     }
-    if (FUSE) {
-      amax = block_max(amax, red);
-      if (threadIdx.x == 0) fuse.partials[(uint64_t)blockIdx.x * M + m] = amax;
+    float amax[MC];
+#pragma unroll
+    for (int k = 0; k < MC; ++k) {
+      amax[k] = 0.f;
+      if (m0 + k < M) {
+        float4 o = base;
+        if (generated) n[k] = gaussian4(gen, qc, m0 + k);
+        if (generated || from_tensor) {
+          o.x = base.x + n[k].x;
+          o.y = base.y + n[k].y;
+          o.z = base.z + n[k].z;
+          o.w = base.w + n[k].w;
+        }
+        if (active) {
+          store4_any(g + (uint64_t)(m0 + k) * d, q, o);
+          if (FUSE) amax[k] = absmax4(fuse, o, r1, r2);
+        }
+      }
+    }
+    if (FUSE) {  // the workgroup's maxima of the trip's workers with one pair of barriers
+      const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+#pragma unroll
+      for (int k = 0; k < MC; ++k) {
+        const float v = wave_max(amax[k]);
+        if (lane == 0) red[wave][k] = v;
+      }
+      __syncthreads();
+      if (threadIdx.x < (uint32_t)MC && m0 + threadIdx.x < M) {
+        float v = red[0][threadIdx.x];
+#pragma unroll
+        for (int wv = 1; wv < kWavesPerBlock; ++wv) v = fmaxf(v, red[wv][threadIdx.x]);
+        fuse.partials[(uint64_t)blockIdx.x * M + m0 + threadIdx.x] = v;
+      }
+      __syncthreads();  // red is reused by the next trip
     }
   }
 }
