@@ -181,7 +181,7 @@ def oracle_step_seconds(ctx, grads, w0):
     return time.perf_counter() - t0
 
 
-def step_bytes(kind, M, d, words, batch=0, nnz=0, ntiles=0, noise_tensor=False):
+def step_bytes(kind, M, d, words, batch=0, nnz=0, ntiles=0, noise_tensor=False, row_splits=0):
     """HBM bytes of one tng_step, two ways.  `moved`: what the path as built transfers (every kernel's
     operands once per kernel; the scale pass rides along with the gradient kernel, so g is written once and
     read once).  `compulsory`: every operand of the iteration once (minibatch data once, g written and read
@@ -191,7 +191,10 @@ def step_bytes(kind, M, d, words, batch=0, nnz=0, ntiles=0, noise_tensor=False):
     codec = 4 * M * d + 4 * d + codes + codes   # quantise: g + g~ read, codes written; decode: codes read
     if kind == "dense":
         x = 4 * M * batch * d
-        return {"moved": 2 * x + 4 * M * d + codec + vectors, "compulsory": x + 4 * M * d + codec + vectors}
+        # rows kept on chip (row_splits workgroups per worker): the minibatch rows once, and the workgroups'
+        # partial gradients written and read; otherwise the rows twice (residual pass, accumulation pass)
+        grad = x + 2 * 4 * M * row_splits * d if row_splits else 2 * x
+        return {"moved": grad + 4 * M * d + codec + vectors, "compulsory": x + 4 * M * d + codec + vectors}
     if kind == "csr":
         entries = 8 * nnz
         bounds = 4 * M * batch * (ntiles + 1)
@@ -299,9 +302,10 @@ def whole_iteration_benchmarks(torch, B, synth, dev, steps, warmup, with_oracle=
     ctx.set_logreg_dense(X, y)
     ms = time_steps(torch, ctx, step_state(torch, ctx, torch.zeros(d, device=dev)), steps, warmup)
     orc = (logistic_oracle(ctx, X, y, n, d), "same shape, minibatch rows already on the host") if with_oracle else None
-    record("dense logistic d=2^16 M=16 B=256 2-bit quot", ms, step_bytes("dense", M, d, ctx.words, batch),
+    record("dense logistic d=2^16 M=16 B=256 2-bit quot", ms, step_bytes("dense", M, d, ctx.words, batch, row_splits=256 // M),
            f"{n} of 65536 rows per worker resident ({M * n * d * 4 / 2**30:.0f} GiB: the largest power of two that fits); "
-           "the minibatch rows are read by the residual pass and again by the accumulation pass", orc)
+           "every minibatch row is read once and kept on chip (LDS + registers) between the dot product and the "
+           f"accumulation, {256 // M} workgroups per worker whose partial gradients are then added", orc)
     ctx.close()
     del X, y, ctx
 

@@ -30,6 +30,7 @@ struct tng_ctx {
   float noise_sigma;      // > 0: Gaussian noise is generated on the device instead
   const float* gref2;     // second reference of the combined normalisation
   float* history;         // [ref_window][d] ring of decoded averages (window-average reference)
+  float* parts;           // dense problem, wide rows: partial gradients [M][splits][d] of the one-pass kernel, or null
   uint32_t* check;        // CSR problem: flag word of tng_validate_csr, then uint64[M] entry counts at +256 bytes
   double* sums;           // chunk and group sums of the order-pinned row sums (mean reference, l2 scale)
   std::vector<hipEvent_t> prof;  // optional timing events, 5 per slot
@@ -71,7 +72,8 @@ bool config_valid(const tng_config* c) {
 }
 
 struct Partition {
-  size_t idx_off, resid_off, tables_off, partials_off, rowbase_off, bounds_off, zpart_off, sums_off, check_off, total;
+  size_t idx_off, resid_off, tables_off, partials_off, rowbase_off, bounds_off, zpart_off, sums_off, check_off, parts_off,
+      total;
 };
 
 Partition partition(const tng_config* c) {
@@ -100,6 +102,9 @@ Partition partition(const tng_config* c) {
     off += round_up(tng::tree_sum_scratch(c->d, c->M) * sizeof(double));
   p.check_off = off;  // tng_validate_csr: a flag word and the per-worker entry counts
   if (c->problem == TNG_PROB_LOGREG_CSR) off += round_up(256 + (size_t)c->M * sizeof(uint64_t));
+  p.parts_off = off;  // dense problem, wide rows: per-workgroup partial gradients of the one-pass kernel
+  if (c->problem == TNG_PROB_LOGREG_DENSE)
+    off += round_up((size_t)tng::dense_row_splits(c->d, c->M, c->batch) * c->M * c->d * sizeof(float));
   p.total = off;
   return p;
 }
@@ -246,7 +251,7 @@ tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g
     case TNG_PROB_LOGREG_DENSE: {
       if (!ctx->have_dense) return TNG_ERR_BAD_STATE;
       const tng::LogregData p = logreg_tables(ctx);
-      e = tng::launch_logreg_dense_grad(p, c.d, c.M, c.batch, c.l2, k0, k1, iter, ctx->idx, ctx->resid, w, g, fuse,
+      e = tng::launch_logreg_dense_grad(p, c.d, c.M, c.batch, c.l2, k0, k1, iter, ctx->idx, ctx->resid, ctx->parts, w, g, fuse,
                                         fused_rows, ctx->stream);
       return hip_status(e);
     }
@@ -357,6 +362,7 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->zpart = reinterpret_cast<float*>(base + p.zpart_off);
   ctx->sums = reinterpret_cast<double*>(base + p.sums_off);
   ctx->check = reinterpret_cast<uint32_t*>(base + p.check_off);
+  ctx->parts = p.total > p.parts_off ? reinterpret_cast<float*>(base + p.parts_off) : nullptr;
   ctx->have_dense = ctx->have_csr = false;
   ctx->have_index = false;
   ctx->csr_pairs = false;

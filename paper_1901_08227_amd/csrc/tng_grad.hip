@@ -308,6 +308,183 @@ __global__ __launch_bounds__(kSplitThreads) void logreg_dense_grad_split_kernel(
   }
 }
 
+// One pass over the minibatch rows for wide dense problems (4096 <= d / 4 <= 16384 float4 columns): a
+// workgroup takes whole rows, one at a time, and KEEPS the row on chip between the two uses it has -- the
+// dot product z = x . w, and, once sigma(z) - y is known, the accumulation r x into the workgroup's
+// partial gradient -- so that X_B is read from memory once instead of twice (the separate residual and
+// accumulation passes each stream it at 6.2 TB/s, which is all the memory system gives; re-reading a
+// block right after it was read, out of the 256 MB last-level cache, measured no faster than HBM).
+// A row of up to 256 KiB fits neither store alone: each of the 512 threads (one workgroup per compute
+// unit, so 256 registers per thread) parks NL = min(NV, 16) float4 of the row in LDS (128 KiB per
+// workgroup; a thread reads back only what it wrote) and holds the other NV - NL in registers, next to its
+// NV float4 of partial gradient.  The register half is requested first and stays in flight while the LDS
+// half goes through a few transit registers at a time.
+// The workgroups of a worker split its minibatch rows; their partial gradients go to scratch
+// parts[m][s][d] and logreg_dense_parts_kernel adds them in workgroup order.
+constexpr int kRowsThreads = 512;
+constexpr int kRowsWaves = kRowsThreads / kWave;
+constexpr int kRowsLds = 16;  // float4 per thread kept in LDS
+template <int NV, bool FULL>
+__global__ __launch_bounds__(kRowsThreads) void logreg_dense_rows_kernel(const float* const* __restrict__ Xs,
+                                                                         const float* const* __restrict__ ys,
+                                                                         const uint64_t* __restrict__ n_rows,
+                                                                         uint32_t* __restrict__ idx,
+                                                                         const float* __restrict__ w,
+                                                                         float* __restrict__ parts, uint64_t d,
+                                                                         uint32_t batch, uint32_t k0, uint32_t k1,
+                                                                         uint32_t iter) {
+  constexpr int NL = NV < kRowsLds ? NV : kRowsLds;
+  constexpr int NR = NV - NL;
+  constexpr int TR = 4;  // transit registers (float4) of the LDS half
+  static_assert(NL % TR == 0 && NR % TR == 0, "both halves are worked through in whole batches");
+  extern __shared__ float4 rowl[];  // [NL][kRowsThreads]
+  __shared__ float red[2][kRowsWaves];
+  const uint32_t m = blockIdx.y, s = blockIdx.x, S = gridDim.x, t = threadIdx.x;
+  const uint32_t nvec = (uint32_t)(d / 4);
+  const GlobalPtr<float> X = as_global(Xs[m]);
+  const GlobalPtr<float> y = as_global(ys[m]);
+  const uint64_t n = n_rows[m];
+  const float4* __restrict__ w4 = reinterpret_cast<const float4*>(w);
+  // float4 column k of the thread: LDS half first (k < NL), register half after; clamped so that every load
+  // is unconditional (FULL: d / 4 = NV * 512, nothing to clamp or mask)
+  // (the thread index goes through an opaque copy per use site: otherwise the compiler computes all NV
+  // column addresses of x and of w once, ahead of the row loop, and keeps them in 3 NV registers)
+  auto opaque_t = [&]() {
+    uint32_t v = t;
+    asm volatile("" : "+v"(v));
+    return v;
+  };
+  auto column_of = [&](uint32_t tt, int k) {
+    return FULL ? tt + (uint32_t)k * kRowsThreads : min(tt + (uint32_t)k * kRowsThreads, nvec - 1);
+  };
+  auto column = [&](int k) { return column_of(t, k); };
+  auto live = [&](int k) { return FULL || t + (uint32_t)k * kRowsThreads < nvec; };
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 acc[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) acc[k] = zero4;
+  uint32_t parity = 0;
+  for (uint32_t i = s; i < batch; i += S, parity ^= 1u) {
+    const uint32_t row = minibatch_row(k0, k1, iter, m, i, n);
+    if (t == 0) idx[(uint64_t)m * batch + i] = row;
+    const GlobalPtr<float> x = X + (uint64_t)row * d;
+    float4 xr[NR > 0 ? NR : 1];
+    {
+      const uint32_t tt = opaque_t();
+#pragma unroll
+      for (int k = 0; k < NR; ++k) xr[k] = load4_stream(x, column_of(tt, NL + k));
+    }
+    float z0 = 0.f, z1 = 0.f, z2 = 0.f, z3 = 0.f;
+#pragma unroll
+    for (int k0b = 0; k0b < NL; k0b += TR) {
+      float4 xa[TR], wa[TR];
+      const uint32_t tt = opaque_t();
+#pragma unroll
+      for (int k = 0; k < TR; ++k) xa[k] = load4_stream(x, column_of(tt, k0b + k));
+#pragma unroll
+      for (int k = 0; k < TR; ++k) wa[k] = w4[column_of(tt, k0b + k)];
+#pragma unroll
+      for (int k = 0; k < TR; ++k) {
+        const float4 xv = live(k0b + k) ? xa[k] : zero4;
+        z0 = __builtin_fmaf(xv.x, wa[k].x, z0);
+        z1 = __builtin_fmaf(xv.y, wa[k].y, z1);
+        z2 = __builtin_fmaf(xv.z, wa[k].z, z2);
+        z3 = __builtin_fmaf(xv.w, wa[k].w, z3);
+        rowl[(k0b + k) * kRowsThreads + t] = xv;
+      }
+      asm volatile("" ::: "memory");  // keeps the next batch's loads behind this batch's use: registers are the scarce thing here
+    }
+#pragma unroll
+    for (int k0b = 0; k0b < NR; k0b += TR) {
+      float4 wa[TR];
+      const uint32_t tt = opaque_t();
+#pragma unroll
+      for (int k = 0; k < TR; ++k) wa[k] = w4[column_of(tt, NL + k0b + k)];
+#pragma unroll
+      for (int k = 0; k < TR; ++k) {
+        if (!live(NL + k0b + k)) xr[k0b + k] = zero4;
+        z0 = __builtin_fmaf(xr[k0b + k].x, wa[k].x, z0);
+        z1 = __builtin_fmaf(xr[k0b + k].y, wa[k].y, z1);
+        z2 = __builtin_fmaf(xr[k0b + k].z, wa[k].z, z2);
+        z3 = __builtin_fmaf(xr[k0b + k].w, wa[k].w, z3);
+      }
+      asm volatile("" ::: "memory");
+    }
+    // z over the workgroup (two sets of slots alternate, so that one barrier per row is enough)
+    const float zw = wave_sum((z0 + z1) + (z2 + z3));
+    if (t % kWave == 0) red[parity][t / kWave] = zw;
+    __syncthreads();
+    float z = red[parity][0];
+#pragma unroll
+    for (int k = 1; k < kRowsWaves; ++k) z += red[parity][k];
+    const float r = logistic_residual(z, y[row]);
+#pragma unroll
+    for (int k = 0; k < NR; ++k) {
+      acc[NL + k].x = __builtin_fmaf(r, xr[k].x, acc[NL + k].x);
+      acc[NL + k].y = __builtin_fmaf(r, xr[k].y, acc[NL + k].y);
+      acc[NL + k].z = __builtin_fmaf(r, xr[k].z, acc[NL + k].z);
+      acc[NL + k].w = __builtin_fmaf(r, xr[k].w, acc[NL + k].w);
+    }
+#pragma unroll
+    for (int k0b = 0; k0b < NL; k0b += TR) {
+      const uint32_t tt = opaque_t();
+#pragma unroll
+      for (int k = k0b; k < k0b + TR; ++k) {
+        const float4 xv = rowl[k * kRowsThreads + tt];
+        acc[k].x = __builtin_fmaf(r, xv.x, acc[k].x);
+        acc[k].y = __builtin_fmaf(r, xv.y, acc[k].y);
+        acc[k].z = __builtin_fmaf(r, xv.z, acc[k].z);
+        acc[k].w = __builtin_fmaf(r, xv.w, acc[k].w);
+      }
+      asm volatile("" ::: "memory");
+    }
+  }
+  float4* __restrict__ out = reinterpret_cast<float4*>(parts + ((uint64_t)m * S + s) * d);
+#pragma unroll
+  for (int k = 0; k < NV; ++k)
+    if (live(k)) store_stream(out + column(k), acc[k]);
+}
+
+// g_m = (1/B) (sum over the S partial gradients of worker m, in order) + l2 w; FUSE as in logreg_dense_grad_kernel.
+template <bool FUSE>
+__global__ __launch_bounds__(kBlock) void logreg_dense_parts_kernel(const float* __restrict__ parts,
+                                                                    const float* __restrict__ w, float* __restrict__ g,
+                                                                    uint64_t d, uint32_t S, float inv_b, float l2,
+                                                                    ScaleFusion fuse) {
+  __shared__ float red[16];
+  const uint32_t m = blockIdx.y;
+  const uint64_t col = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool active = col < d / 4;
+  float amax = 0.f;
+  if (active) {
+    const float4* __restrict__ p = reinterpret_cast<const float4*>(parts + (uint64_t)m * S * d) + col;
+    float4 acc = load_stream(p);
+    for (uint32_t s = 1; s < S; ++s) {
+      const float4 v = load_stream(p + (uint64_t)s * (d / 4));
+      acc.x += v.x;
+      acc.y += v.y;
+      acc.z += v.z;
+      acc.w += v.w;
+    }
+    const float4 wv = reinterpret_cast<const float4*>(w)[col];
+    float4 o;
+    o.x = __builtin_fmaf(l2, wv.x, acc.x * inv_b);
+    o.y = __builtin_fmaf(l2, wv.y, acc.y * inv_b);
+    o.z = __builtin_fmaf(l2, wv.z, acc.z * inv_b);
+    o.w = __builtin_fmaf(l2, wv.w, acc.w * inv_b);
+    reinterpret_cast<float4*>(g + (uint64_t)m * d)[col] = o;
+    if (FUSE) {
+      float4 r1, r2;
+      load_refs4(fuse, col, r1, r2);
+      amax = absmax4(fuse, o, r1, r2);
+    }
+  }
+  if (FUSE) {
+    amax = block_max(amax, red);
+    if (threadIdx.x == 0) fuse.partials[(uint64_t)blockIdx.x * gridDim.y + m] = amax;
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // CSR logistic regression, column-tiled.
 //
@@ -1147,11 +1324,66 @@ hipError_t launch_minibatch_indices(uint32_t k0, uint32_t k1, uint32_t iter, uin
   return hipGetLastError();
 }
 
+uint32_t dense_row_splits(uint64_t d, uint32_t M, uint32_t batch) {
+  // one pass over whole rows kept on chip: rows of 16 K to 64 K columns (shorter ones leave the threads too
+  // little to do, longer ones do not fit), 16-byte aligned, and enough rows for two or more per workgroup
+  // (between 32 K and 64 K columns only the full width: the masked form of the widest variant does not fit the
+  // register file)
+  if (d % 4 != 0 || d < 16384 || (d > 32768 && d != 65536) || (uint64_t)M * batch < 512) return 0;
+  uint32_t S = 256 / (M < 256 ? M : 256);
+  S = S < 1 ? 1 : S;
+  return S < batch ? S : batch;
+}
+
 hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                     uint32_t k0, uint32_t k1, uint32_t iter, uint32_t* idx, float* resid,
-                                    const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
-                                    hipStream_t s) {
+                                    float* parts, const float* w, float* g, const ScaleFusion* fuse,
+                                    uint32_t* fused_rows, hipStream_t s) {
   if (fused_rows != nullptr) *fused_rows = 0;
+  const uint32_t S = parts != nullptr && aligned16(w) && aligned16(g) ? dense_row_splits(d, M, batch) : 0;
+  if (S != 0) {
+    const int nv = d <= 16384 ? 8 : d <= 32768 ? 16 : 32;
+    const bool full = d / 4 == (uint64_t)nv * kRowsThreads;
+    const size_t lds = (size_t)(nv < kRowsLds ? nv : kRowsLds) * kRowsThreads * sizeof(float4);
+    const void* fns[] = {reinterpret_cast<const void*>(logreg_dense_rows_kernel<8, false>),
+                         reinterpret_cast<const void*>(logreg_dense_rows_kernel<8, true>),
+                         reinterpret_cast<const void*>(logreg_dense_rows_kernel<16, false>),
+                         reinterpret_cast<const void*>(logreg_dense_rows_kernel<16, true>),
+                         reinterpret_cast<const void*>(logreg_dense_rows_kernel<32, false>),
+                         reinterpret_cast<const void*>(logreg_dense_rows_kernel<32, true>)};
+    {  // 128 KiB of dynamic LDS: raised once per device
+      static std::mutex attr_mutex;
+      static bool attr_done[64] = {};
+      int dev = -1;
+      if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+      std::lock_guard<std::mutex> attr_lock(attr_mutex);
+      if (!attr_done[dev]) {
+        for (const void* fn : fns) {
+          const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   kRowsLds * kRowsThreads * (int)sizeof(float4));
+          if (e != hipSuccess) return e;
+        }
+        attr_done[dev] = true;
+      }
+    }
+    const dim3 grid(S, M);
+    void* args[] = {(void*)&p.X, (void*)&p.y, (void*)&p.n_rows, (void*)&idx, (void*)&w, (void*)&parts,
+                    (void*)&d,   (void*)&batch, (void*)&k0, (void*)&k1, (void*)&iter};
+    const int which = (nv == 8 ? 0 : nv == 16 ? 2 : 4) + (full ? 1 : 0);
+    const hipError_t el = hipLaunchKernel(fns[which], grid, dim3(kRowsThreads), args, lds, s);
+    if (el != hipSuccess) return el;
+    const float inv_batch = 1.0f / (float)batch;
+    dim3 grid_p((uint32_t)((d / 4 + kBlock - 1) / kBlock), M);
+    if (fuse != nullptr && fused_rows != nullptr && grid_p.x <= kAbsmaxMaxBlocks && aligned16(fuse->gref) &&
+        aligned16(fuse->gref2)) {
+      hipLaunchKernelGGL(logreg_dense_parts_kernel<true>, grid_p, dim3(kBlock), 0, s, parts, w, g, d, S, inv_batch, l2, *fuse);
+      *fused_rows = grid_p.x;
+    } else {
+      hipLaunchKernelGGL(logreg_dense_parts_kernel<false>, grid_p, dim3(kBlock), 0, s, parts, w, g, d, S, inv_batch, l2,
+                         ScaleFusion{});
+    }
+    return hipGetLastError();
+  }
   // Rows of X and of g start at any 4-byte boundary when d is not a multiple of 4: the vector kernels
   // read and write them with 16-byte accesses that assume no more, over the first 4 * (d / 4) columns.
   const bool vec = d >= 4 && aligned16(w);

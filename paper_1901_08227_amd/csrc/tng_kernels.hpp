@@ -96,10 +96,13 @@ struct LogregData {
 hipError_t launch_minibatch_indices(uint32_t k0, uint32_t k1, uint32_t iter, uint32_t M, uint32_t batch,
                                     const uint64_t* n_rows, uint32_t* idx, hipStream_t s);
 // The minibatch row ids of iteration iter are drawn inside (Philox key k0, k1) and left in idx.
+// parts: device scratch of dense_row_splits(d, M, batch) * M * d floats (per-workgroup partial gradients of
+// the one-pass kernel for wide rows), or nullptr; dense_row_splits returns 0 where that kernel does not apply.
+uint32_t dense_row_splits(uint64_t d, uint32_t M, uint32_t batch);
 hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M, uint32_t batch, float l2,
                                     uint32_t k0, uint32_t k1, uint32_t iter, uint32_t* idx, float* resid,
-                                    const float* w, float* g, const ScaleFusion* fuse, uint32_t* fused_rows,
-                                    hipStream_t s);
+                                    float* parts, const float* w, float* g, const ScaleFusion* fuse,
+                                    uint32_t* fused_rows, hipStream_t s);
 // Column tiles of the CSR gradient: 2^kCsrTileShift coordinates (128 KiB of fp64 in LDS).
 constexpr uint32_t kCsrTileShift = 14;
 uint32_t csr_tiles(uint64_t d);

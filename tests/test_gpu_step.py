@@ -154,6 +154,16 @@ def test_dense_logistic_wide_rows_first_iterations():
     _dense_case(M=16, n=512, d=65536, batch=256, bits=2, norm=B.NORM_QUOT, T=3, seed=7)
 
 
+@pytest.mark.parametrize("d,M,batch", [(16384, 8, 64), (16388, 4, 130), (32768, 3, 200), (20000, 16, 33), (32764, 2, 256)])
+def test_dense_logistic_rows_kept_on_chip(d, M, batch):
+    # 16 K to 64 K columns and at least 512 minibatch rows in all: the gradient kernel that reads every
+    # minibatch row once and keeps it in LDS and registers between the dot product and the accumulation;
+    # full and ragged widths of both narrower variants (the widest, d = 2^16, is the test above), worker
+    # counts that give 32 to 128 workgroups per worker, row counts the workgroups do not divide
+    say(f"dense logistic, rows kept on chip: d={d} M={M} B={batch}")
+    _dense_case(M=M, n=300, d=d, batch=batch, bits=4, norm=B.NORM_SUB, T=3, seed=d % 97 + M, l2=0.001)
+
+
 def test_rosenbrock_chain_first_iterations_at_full_shape():
     # d = 2^20, M = 8, noise N(0, 0.01), ternary, subtraction; reference refreshed every 16 iterations
     # ("Nonconvex Problems"): the first 48 of the 500 iterations, three refreshes
