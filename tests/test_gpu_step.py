@@ -384,7 +384,7 @@ def _ragged_csr(M, n, d, lengths_fn, seed):
 
 @pytest.mark.parametrize("pairs", [False, True])
 @pytest.mark.parametrize("use_index", [False, True])
-@pytest.mark.parametrize("case", ["ragged", "tiny_d", "odd_d_many_rows", "dense_rows"])
+@pytest.mark.parametrize("case", ["ragged", "tiny_d", "odd_d_many_rows", "dense_rows", "one_entry"])
 def test_csr_logistic_edge_cases(case, use_index, pairs):
     if case == "ragged":        # empty rows, one-entry rows, rows longer than a lane group inside one tile
         M, n, d, batch = 3, 40, (1 << 15) + 24, 33
@@ -395,6 +395,9 @@ def test_csr_logistic_edge_cases(case, use_index, pairs):
     elif case == "odd_d_many_rows":   # more minibatch rows than one staging trip, d not a multiple of 4 (scalar codec)
         M, n, d, batch = 2, 900, 3 * (1 << 14) + 1, 1100
         lens = lambda m, i: 20 + (i % 50)
+    elif case == "one_entry":   # a worker that stores one entry in all; another whose arrays end on an odd segment
+        M, n, d, batch = 2, 5, 1 << 15, 9
+        lens = lambda m, i: [[0, 0, 1, 0, 0], [3, 0, 5, 0, 7]][m][i]
     else:                       # nearly dense rows: many entries per (row, tile) segment
         M, n, d, batch = 2, 12, 1 << 14, 12
         lens = lambda m, i: (1 << 14) - 1 - i
