@@ -96,6 +96,7 @@ __global__ __launch_bounds__(kBlock) void rng_draws_kernel(uint32_t k0, uint32_t
 template <int NORM>
 struct RefTile {
   float4 r1, r2;
+  double inv[4];  // binary64 reciprocals of the divisor (Eq. 2: r1, combined form: r2), see reciprocals()
   // STREAM: the tile is read once by this kernel (non-temporal); otherwise it is re-read soon and
   // should stay in cache.
   template <bool STREAM = true>
@@ -112,7 +113,55 @@ struct RefTile {
       r2 = make_float4(clamp_ref(r.x, eps), clamp_ref(r.y, eps), clamp_ref(r.z, eps), clamp_ref(r.w, eps));
     }
   }
+  // Every worker divides by the same clamped reference (Eq. 2 and the combined form): the scale and the
+  // quantise pass take its binary64 reciprocal once per coordinate and multiply per worker
+  // (quotient_by_reciprocal), 4 operations per element instead of the 12 of a division.
+  __device__ __forceinline__ void reciprocals() {
+    const float4& b = NORM == kNormQuot ? r1 : r2;
+    if (NORM == kNormQuot || NORM == kNormComb) {
+      inv[0] = 1.0 / (double)b.x;
+      inv[1] = 1.0 / (double)b.y;
+      inv[2] = 1.0 / (double)b.z;
+      inv[3] = 1.0 / (double)b.w;
+    }
+  }
 };
+
+// Worth it from four workers per reference tile on: the reciprocal itself costs about two divisions.
+template <int NORM, int MC>
+constexpr bool kByReciprocal = (NORM == kNormQuot || NORM == kNormComb) && MC >= 4;
+
+// The four values one float4 of a worker's row hands to the coder, the divisions of Eq. 2 / the
+// combined form done through the reciprocals; the (rare) float4 with a subnormal quotient is redone
+// with the division itself, so the values are those of normalize_w bit for bit.
+template <int NORM, bool RECIP>
+__device__ __forceinline__ float4 normalize4(const float4& x, const RefTile<NORM>& rt, float mu) {
+  if (!RECIP) {
+    return make_float4(normalize_w<NORM>(x.x, rt.r1.x, rt.r2.x, mu), normalize_w<NORM>(x.y, rt.r1.y, rt.r2.y, mu),
+                       normalize_w<NORM>(x.z, rt.r1.z, rt.r2.z, mu), normalize_w<NORM>(x.w, rt.r1.w, rt.r2.w, mu));
+  }
+  float4 n = x;  // numerators
+  if (NORM == kNormComb) n = make_float4(x.x - rt.r1.x, x.y - rt.r1.y, x.z - rt.r1.z, x.w - rt.r1.w);
+  float4 v = make_float4(quotient_by_reciprocal(n.x, rt.inv[0]), quotient_by_reciprocal(n.y, rt.inv[1]),
+                         quotient_by_reciprocal(n.z, rt.inv[2]), quotient_by_reciprocal(n.w, rt.inv[3]));
+  if ((int)is_subnormal(v.x) | (int)is_subnormal(v.y) | (int)is_subnormal(v.z) | (int)is_subnormal(v.w)) {
+    const float4& b = NORM == kNormQuot ? rt.r1 : rt.r2;
+    v = make_float4(n.x / b.x, n.y / b.y, n.z / b.z, n.w / b.w);
+  }
+  return v;
+}
+
+// max |normalize4(x)| over one float4.  The maximum is taken in binary64 and rounded once (rounding is
+// monotone, so this is the maximum of the rounded quotients); it is right whenever it is 0 or at least
+// 2^-125, because then the largest quotient is of normal size and every subnormal one lies below it.
+template <int NORM>
+__device__ __forceinline__ double absmax4_by_reciprocal(const float4& x, const RefTile<NORM>& rt) {
+  float4 n = x;
+  if (NORM == kNormComb) n = make_float4(x.x - rt.r1.x, x.y - rt.r1.y, x.z - rt.r1.z, x.w - rt.r1.w);
+  const double q0 = fabs((double)n.x * rt.inv[0]), q1 = fabs((double)n.y * rt.inv[1]);
+  const double q2 = fabs((double)n.z * rt.inv[2]), q3 = fabs((double)n.w * rt.inv[3]);
+  return fmax(fmax(q0, q1), fmax(q2, q3));
+}
 
 template <int NORM>
 __device__ __forceinline__ void load_ref_scalar(const float* ref, const float* ref2, uint64_t e, float eps,
@@ -200,9 +249,18 @@ __device__ __forceinline__ void absmax_load(const v4f_u_t* __restrict__ row, con
   }
 }
 
-template <int NORM, bool FULL>
+template <int NORM, bool FULL, bool RECIP>
 __device__ __forceinline__ float absmax_reduce(const float4 (&x)[kAbsmaxLoads], const RefTile<NORM> (&rt)[kAbsmaxLoads],
                                                const uint64_t (&iv)[kAbsmaxLoads], uint64_t nvec, float mu) {
+  if (RECIP) {
+    double mx64 = 0.0;
+#pragma unroll
+    for (int j = 0; j < kAbsmaxLoads; ++j) {
+      if (FULL || iv[j] < nvec) mx64 = fmax(mx64, absmax4_by_reciprocal<NORM>(x[j], rt[j]));
+    }
+    if (!(mx64 > 0.0 && mx64 < 0x1p-125)) return (float)mx64;
+    // else (a tile whose quotients are all tiny): once more with the divisions themselves
+  }
   float mx = 0.f;
 #pragma unroll
   for (int j = 0; j < kAbsmaxLoads; ++j) {
@@ -230,10 +288,10 @@ __device__ __forceinline__ void absmax_rows(const GradRows& g, const RefTile<NOR
 #pragma unroll
   for (int mm = 0; mm < MC; mm += 2) {
     if (mm + 1 < MC) absmax_load<NORM, FULL>(row(mm + 1), iv, nvec, xb);
-    mx[mm] = fmaxf(mx[mm], absmax_reduce<NORM, FULL>(xa, rt, iv, nvec, mean_of(mm)));
+    mx[mm] = fmaxf(mx[mm], absmax_reduce<NORM, FULL, kByReciprocal<NORM, MC>>(xa, rt, iv, nvec, mean_of(mm)));
     if (mm + 1 < MC) {
       if (mm + 2 < MC) absmax_load<NORM, FULL>(row(mm + 2), iv, nvec, xa);
-      mx[mm + 1] = fmaxf(mx[mm + 1], absmax_reduce<NORM, FULL>(xb, rt, iv, nvec, mean_of(mm + 1)));
+      mx[mm + 1] = fmaxf(mx[mm + 1], absmax_reduce<NORM, FULL, kByReciprocal<NORM, MC>>(xb, rt, iv, nvec, mean_of(mm + 1)));
     }
   }
 }
@@ -259,7 +317,10 @@ __global__ __launch_bounds__(kBlock) void absmax_vec_kernel(GradRows g, const fl
 #pragma unroll
     for (int j = 0; j < L; ++j) {
       iv[j] = tile * kWaveTile + (uint64_t)j * kWave + lane;
-      if (full || iv[j] < nvec) rt[j].load(ref4, ref24, iv[j], eps);
+      if (full || iv[j] < nvec) {
+        rt[j].load(ref4, ref24, iv[j], eps);
+        if (kByReciprocal<NORM, MC>) rt[j].reciprocals();
+      }
     }
     if (full) {
       absmax_rows<NORM, MC, true>(g, rt, iv, nvec, m0, M, means, mx);
@@ -322,7 +383,7 @@ __device__ __forceinline__ void load_worker_tile(const QuantLane<NORM>& q, const
 }
 
 // Codes of one worker for this lane's 16 coordinates: four fragments of 4 codes each.
-template <int NORM, int BITS, bool FULL>
+template <int NORM, int BITS, bool FULL, bool RECIP>
 __device__ __forceinline__ void quantize_worker_tile(const QuantLane<NORM>& q, const float4 (&x)[kLoadsPerLane],
                                                      float R, float mu, uint32_t m, uint32_t iter, uint32_t k0,
                                                      uint32_t k1, uint32_t (&frag)[kLoadsPerLane]) {
@@ -337,11 +398,11 @@ __device__ __forceinline__ void quantize_worker_tile(const QuantLane<NORM>& q, c
     frag[j] = 0u;
     if (FULL || q.ok[j]) {
       const U32x4 rnd = philox4x32_10((uint32_t)q.iv[j], m, iter, 0u, k0, k1);
-      const RefTile<NORM>& rt = q.rt[j];
-      const uint32_t c0 = quantize_code<BITS>(normalize_w<NORM>(x[j].x, rt.r1.x, rt.r2.x, mu), inv_r, rnd.x);
-      const uint32_t c1 = quantize_code<BITS>(normalize_w<NORM>(x[j].y, rt.r1.y, rt.r2.y, mu), inv_r, rnd.y);
-      const uint32_t c2 = quantize_code<BITS>(normalize_w<NORM>(x[j].z, rt.r1.z, rt.r2.z, mu), inv_r, rnd.z);
-      const uint32_t c3 = quantize_code<BITS>(normalize_w<NORM>(x[j].w, rt.r1.w, rt.r2.w, mu), inv_r, rnd.w);
+      const float4 v = normalize4<NORM, RECIP>(x[j], q.rt[j], mu);
+      const uint32_t c0 = quantize_code<BITS>(v.x, inv_r, rnd.x);
+      const uint32_t c1 = quantize_code<BITS>(v.y, inv_r, rnd.y);
+      const uint32_t c2 = quantize_code<BITS>(v.z, inv_r, rnd.z);
+      const uint32_t c3 = quantize_code<BITS>(v.w, inv_r, rnd.w);
       frag[j] = c0 | (c1 << BITS) | (c2 << (2 * BITS)) | (c3 << (3 * BITS));
     }
   }
@@ -466,13 +527,13 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
     rb = scale_of(m + 1);
     mub = mean_of(m + 1);
     load_worker_tile<NORM, FULL>(q, g, m + 1, xb);
-    quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
+    quantize_worker_tile<NORM, BITS, FULL, kByReciprocal<NORM, SLOTS>>(q, xa, ra, mua, m, iter, k0, k1, frag);
     store_packed<BITS, WPW, SLOTS, DEFER>(lds, DEFER ? (int)(m - m0) : 0, wave, lane, frag, codes + (uint64_t)m * words, word_base,
                                           words);
     ra = scale_of(m + 2);
     mua = mean_of(m + 2);
     load_worker_tile<NORM, FULL>(q, g, m + 2, xa);
-    quantize_worker_tile<NORM, BITS, FULL>(q, xb, rb, mub, m + 1, iter, k0, k1, frag);
+    quantize_worker_tile<NORM, BITS, FULL, kByReciprocal<NORM, SLOTS>>(q, xb, rb, mub, m + 1, iter, k0, k1, frag);
     store_packed<BITS, WPW, SLOTS, DEFER>(lds, DEFER ? (int)(m + 1 - m0) : 0, wave, lane, frag,
                                           codes + (uint64_t)(m + 1) * words, word_base, words);
   }
@@ -481,14 +542,14 @@ __device__ __forceinline__ void quantize_rows(const QuantLane<NORM>& q, Fragment
     rb = scale_of(m + 1);
     mub = mean_of(m + 1);
     load_worker_tile<NORM, FULL>(q, g, m + 1, xb);
-    quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
+    quantize_worker_tile<NORM, BITS, FULL, kByReciprocal<NORM, SLOTS>>(q, xa, ra, mua, m, iter, k0, k1, frag);
     store_packed<BITS, WPW, SLOTS, DEFER>(lds, DEFER ? (int)(m - m0) : 0, wave, lane, frag, codes + (uint64_t)m * words, word_base,
                                           words);
-    quantize_worker_tile<NORM, BITS, FULL>(q, xb, rb, mub, m + 1, iter, k0, k1, frag);
+    quantize_worker_tile<NORM, BITS, FULL, kByReciprocal<NORM, SLOTS>>(q, xb, rb, mub, m + 1, iter, k0, k1, frag);
     store_packed<BITS, WPW, SLOTS, DEFER>(lds, DEFER ? (int)(m + 1 - m0) : 0, wave, lane, frag,
                                           codes + (uint64_t)(m + 1) * words, word_base, words);
   } else {
-    quantize_worker_tile<NORM, BITS, FULL>(q, xa, ra, mua, m, iter, k0, k1, frag);
+    quantize_worker_tile<NORM, BITS, FULL, kByReciprocal<NORM, SLOTS>>(q, xa, ra, mua, m, iter, k0, k1, frag);
     store_packed<BITS, WPW, SLOTS, DEFER>(lds, DEFER ? (int)(m - m0) : 0, wave, lane, frag, codes + (uint64_t)m * words, word_base,
                                           words);
   }
@@ -513,7 +574,10 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
   for (int j = 0; j < L; ++j) {
     q.iv[j] = wave_tile * (kWave * L) + (uint64_t)j * kWave + lane;
     q.ok[j] = q.iv[j] < nvec;
-    if (q.ok[j]) q.rt[j].load(ref4, ref24, q.iv[j], eps);
+    if (q.ok[j]) {
+      q.rt[j].load(ref4, ref24, q.iv[j], eps);
+      if (kByReciprocal<NORM, MC>) q.rt[j].reciprocals();
+    }
   }
 
   const uint32_t m0 = blockIdx.y * MC;

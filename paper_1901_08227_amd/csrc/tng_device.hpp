@@ -135,6 +135,24 @@ __device__ __forceinline__ float normalize(float g, float r1, float r2) {
   return g;
 }
 
+// The quotient g / b of Eq. 2 for many g and one b: with inv_b = the correctly rounded binary64
+// reciprocal of b, float(double(g) * inv_b) is the correctly rounded binary32 quotient whenever that
+// quotient is zero or of normal size.  Why: the product is within 2^-52 (relative) of g / b, while a
+// quotient of two binary32 numbers that is not itself a binary32 number stays at least 1 / (B N) >
+// 2^-49 (relative) away from every midpoint N 2^k of two neighbouring binary32 numbers (B, N the
+// integer significands of b and of the midpoint; N is odd and longer than 24 bits, so g = b N 2^k
+// has no solution) -- the two roundings cannot land on different sides.  Below 2^-126 the midpoints
+// are short enough to be hit exactly (g = 9 * 2^-149, b = 6), which is why callers test the result
+// with is_subnormal and redo those few with the division itself.  Infinities, NaNs and zeros of g
+// and an infinite b behave as in g / b (b is never zero: the reference is clamped away from it).
+__device__ __forceinline__ float quotient_by_reciprocal(float g, double inv_b) {
+  return (float)((double)g * inv_b);
+}
+
+__device__ __forceinline__ bool is_subnormal(float v) {
+  return __builtin_amdgcn_classf(v, (1 << 4) | (1 << 7));  // -subnormal | +subnormal
+}
+
 // The same including the per-worker mean reference (mu = mean of the worker's gradient).
 template <int NORM>
 __device__ __forceinline__ float normalize_w(float g, float r1, float r2, float mu) {

@@ -143,6 +143,36 @@ def test_degenerate_inputs(bits):
     ctx.close()
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+def test_quotients_of_subnormal_size(bits):
+    # Eq. 2 with quotients below 2^-126, most of them exactly half way between two subnormal numbers
+    # (g = k (2j+1) 2^-149 over a reference of 2k, k odd): the kernels' multiplication by the reference's
+    # reciprocal does not settle those and must hand them to the division.  Rows: scale of normal size far
+    # above the ties; every quotient subnormal (scale taken as 0); scale in [2^-126, 2^-125); ordinary data.
+    d = 4096 * 3 + 20
+    gen = torch.Generator(device=DEV).manual_seed(77)
+    for M in (8, 3):
+        k = torch.randint(0, 1 << 10, (d,), generator=gen, device=DEV) * 2 + 1
+        j = torch.randint(0, 1 << 11, (M, d), generator=gen, device=DEV)
+        sign = torch.randint(0, 2, (M, d), generator=gen, device=DEV) * 2 - 1
+        gref = (2 * k).float() * (torch.randint(0, 2, (d,), generator=gen, device=DEV) * 2 - 1).float()
+        g = ((k[None, :] * (2 * j + 1) * sign).double() * 2.0 ** -149).float()
+        assert bool((g != 0).all())
+        for m in range(M):
+            kind = m % 4
+            if kind == 0:
+                g[m, 5 + m] = gref[5 + m] * 2.0 ** -120
+            elif kind == 2:
+                g[m, 4096 + m] = gref[4096 + m] * (1.5 * 2.0 ** -126)
+            elif kind == 3:
+                g[m] = torch.randn(d, generator=gen, device=DEV)
+        zero = torch.zeros(d, device=DEV)
+        for norm, r1, r2 in ((B.NORM_QUOT, gref, gref), (B.NORM_COMB, zero, gref)):
+            ctx = make_ctx(d, M, bits, norm, seed=13)
+            _check_encode_decode(ctx, 3, g, r1, r2, "subnormal quotients")
+            ctx.close()
+
+
 def test_codes_do_not_depend_on_call_history_and_change_with_iteration_and_seed():
     d, M = 4096 * 4, 4
     g, gref, gref2 = _inputs(M, d, seed=1)
