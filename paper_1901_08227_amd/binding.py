@@ -141,10 +141,13 @@ class Context:
         if nbytes == 0:
             raise TngError(TNG_ERR_INVALID_ARG, "tng_workspace_bytes")
         self.device = torch.device(device)
-        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=self.device)
         if stream is None:
             stream = torch.cuda.current_stream(self.device)
         self.stream = stream
+        # the zero fill goes on the context's own stream: on another stream it could still be pending, and
+        # wipe the pointer tables, after the library has begun to use the workspace
+        with torch.cuda.stream(stream):
+            self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=self.device)
         self.handle = ctypes.c_void_p()
         _check(lib().tng_create(ctypes.byref(self.cfg), ctypes.c_void_p(self.workspace.data_ptr()), nbytes,
                                 ctypes.c_void_p(stream.cuda_stream), ctypes.byref(self.handle)), "tng_create")

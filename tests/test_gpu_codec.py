@@ -173,6 +173,20 @@ def test_quotients_of_subnormal_size(bits):
             ctx.close()
 
 
+def test_context_on_a_stream_of_its_own():
+    # a context created on a stream other than the current one: its workspace is cleared on that stream, so
+    # nothing queued elsewhere can wipe what the library keeps there (the test's own tensors are made first
+    # and the device synchronised, as a caller with several streams has to)
+    d, M = 4096 * 9 + 20, 8
+    g, gref, gref2 = _inputs(M, d, seed=41)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream(device=DEV)
+    for norm in (B.NORM_SUB, B.NORM_QUOT):
+        ctx = make_ctx(d, M, 4, norm, seed=6, stream=side)
+        _check_encode_decode(ctx, 2, g, gref, gref2, "side stream")
+        ctx.close()
+
+
 def test_codes_do_not_depend_on_call_history_and_change_with_iteration_and_seed():
     d, M = 4096 * 4, 4
     g, gref, gref2 = _inputs(M, d, seed=1)
