@@ -1178,12 +1178,12 @@ inline uint32_t div_up_u32(uint64_t a, uint64_t b) {
 // costs the scale pass repeated loads of its last row (cache hits: repeat_cost 0.3 of a row there,
 // nothing in the quantiser, which stops at the last worker).  At least 2048 workgroups are kept to
 // fill 256 compute units.
-inline int pick_workers_per_block(uint32_t M, uint64_t tiles, double repeat_cost) {
+inline int pick_workers_per_block(uint32_t M, uint64_t tiles, double repeat_cost, int mc_max = 8) {
   int best = 1;
   double best_cost = (double)M;
-  for (int mc = 2; mc <= 8; mc *= 2) {
+  for (int mc = 2; mc <= mc_max; mc *= 2) {
     const uint32_t groups = (M + mc - 1) / mc;
-    if (tiles * groups < 2048) break;
+    if (tiles * groups < 2048 || (mc > 8 && M <= 8)) break;
     const double cost = groups + repeat_cost * (groups * mc - M);
     if (cost <= best_cost) {
       best = mc;
@@ -1282,7 +1282,7 @@ hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g,
   const uint64_t dv = vector_part(c.d, gref, gref2);
   const bool vec = dv != 0;
   const uint64_t tiles = (dv / 4 + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
-  const int mc = vec ? pick_workers_per_block(c.M, tiles, 0.0) : 1;
+  const int mc = vec ? pick_workers_per_block(c.M, tiles, 0.0, 16) : 1;
   FusedScale fs{partials, fused_rows, scales};
   if (fused_rows > kFusedScaleRows || (fused_rows > 0 && (mc != 1 || dv != c.d))) {
     hipLaunchKernelGGL(absmax_finish_kernel, dim3(c.M), dim3(kBlock), 0, s, partials, fused_rows, c.M, scales);
@@ -1296,6 +1296,7 @@ hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g,
       e = quantize_vec_launch<NORM, BITS, 1, true>(c, dv, iter, g, gref, gref2, scales, codes, fs, s);
     } else {
       switch (mc) {
+        case 16: e = quantize_vec_launch<NORM, BITS, 16, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
         case 8: e = quantize_vec_launch<NORM, BITS, 8, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
         case 4: e = quantize_vec_launch<NORM, BITS, 4, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
         case 2: e = quantize_vec_launch<NORM, BITS, 2, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
