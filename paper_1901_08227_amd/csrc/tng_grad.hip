@@ -1186,6 +1186,155 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_run_kernel(const int32_t
   if (threadIdx.x == 0) store_maximum(t_last);
 }
 
+// The same pipeline turned by ninety degrees: a workgroup stays on ONE column tile and takes the workers
+// m_first .. m_end - 1 in turn.  What a round needs of its worker -- segment bounds, row starts and
+// residuals of the minibatch rows, the shard's entry array -- is fetched during the round before, as the
+// next tile's bounds are above; what belongs to the tile -- the reference of the thread's columns for the
+// fused scale pass -- is fetched once and stays in registers, where the kernel above asks for it again
+// every round (64 workers: the reference read 64 times over, a quarter more load instructions per round
+// in a kernel bound by how fast a compute unit issues them; gradient pass 2.34 -> see the design notes).
+// Workgroups that run side by side are on adjacent tiles of the same worker, so the memory lines shared
+// by the end of one tile's row segment and the start of the next tile's are still fetched once.
+template <bool PAIRS, int NORM>
+__global__ __launch_bounds__(kCsrThreads) void csr_grad_workers_kernel(const int32_t* const* __restrict__ cols,
+                                                                       const float* const* __restrict__ vals,
+                                                                       const int64_t* __restrict__ rowbase,
+                                                                       const uint32_t* __restrict__ bounds,
+                                                                       const float* __restrict__ resid,
+                                                                       float* __restrict__ g, uint64_t d, uint32_t batch,
+                                                                       uint32_t ntiles, uint32_t M, uint32_t per_group,
+                                                                       ScaleFusion fuse) {
+  extern __shared__ double gtile[];  // g over the tile's columns, accumulated in fp64
+  __shared__ __align__(16) int64_t sLoBuf[2][kCsrRows];
+  __shared__ __align__(16) uint32_t sLenBuf[2][kCsrRows];
+  __shared__ float sRBuf[2][kCsrRows];
+  __shared__ float red[2][kCsrThreads / kWave];  // by parity of the round: read in the round after it was written
+  constexpr uint32_t T = 1u << kCsrTileShift;
+  constexpr int kPer = (int)(T / (4 * kCsrThreads));
+  const uint32_t t = blockIdx.x;
+  const uint32_t m_first = blockIdx.y * per_group;
+  const uint32_t m_end = min(m_first + per_group, M);
+  const uint64_t c0 = (uint64_t)t << kCsrTileShift;
+  const uint32_t row = min(threadIdx.x, batch - 1);  // every thread fetches its row's data: no load under a condition
+  const bool has_row = threadIdx.x < batch;
+  // Per-worker arrays are addressed as (wavefront-uniform start of the worker's part) + (the thread's 32-bit
+  // offset): no per-thread 64-bit pointer has to live across the rounds (registers are what this kernel is
+  // short of, and a spilled pointer's reload at the head of a round would wait for every load in flight).
+  const uint64_t per_worker = (uint64_t)(ntiles + 1) * batch;
+  const uint32_t tb_row = t * batch + row;  // bounds of worker m, this tile, this row: bounds[m per_worker + tb_row]
+  auto bounds_of = [&](uint32_t m) { return as_global(bounds + (uint64_t)m * per_worker); };
+  auto rowbase_of = [&](uint32_t m) { return as_global(rowbase + (uint64_t)m * batch); };
+  auto resid_of = [&](uint32_t m) { return as_global(resid + (uint64_t)m * batch); };
+  {
+    const uint32_t lo = bounds_of(m_first)[tb_row], hi = bounds_of(m_first)[tb_row + batch];
+    const int64_t base = rowbase_of(m_first)[row];
+    const float res = resid_of(m_first)[row];
+    for (uint32_t j = threadIdx.x; j < T; j += kCsrThreads) gtile[j] = 0.0;
+    if (threadIdx.x < (uint32_t)kCsrRows) {
+      sRBuf[0][threadIdx.x] = has_row ? res : 0.f;
+      sLoBuf[0][threadIdx.x] = base + lo;
+      sLenBuf[0][threadIdx.x] = has_row ? hi - lo : 0u;
+    }
+  }
+  // the reference of the thread's columns: the same for every worker
+  float4 r1[kPer], r2[kPer];
+#pragma unroll
+  for (int k = 0; k < kPer; ++k)
+    load_refs4_t<NORM>(fuse, c0 / 4 + (uint32_t)k * kCsrThreads + threadIdx.x, r1[k], r2[k]);
+  const uint32_t group = threadIdx.x / kCsrLanes, gl = threadIdx.x % kCsrLanes;
+  const uint32_t j0 = group * kCsrUnroll;
+  int32_t ncol[kCsrUnroll];
+  float nval[kCsrUnroll];
+  uint32_t nmask = 0;  // bit u: this lane holds an entry of segment u
+  uint32_t nlong = 0;  // bit u: segment u is longer than the lane group
+  // entries of worker mr's segments staged in buffer buf; lanes beyond a segment read the worker's first
+  // row start instead (a load, never a branch)
+  auto request = [&](const CsrEntries<PAIRS>& e, uint32_t mr, uint32_t buf) {
+    const void* dummy = rowbase + (uint64_t)mr * batch;
+    nmask = 0;
+    nlong = 0;
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u) {
+      const uint32_t len = sLenBuf[buf][j0 + u];
+      const bool on = gl < len;
+      e.load_or(on, sLoBuf[buf][j0 + u] + gl, dummy, ncol[u], nval[u]);
+      nmask |= on ? 1u << u : 0u;
+      nlong |= len > (uint32_t)kCsrLanes ? 1u << u : 0u;
+    }
+  };
+  auto store_maximum = [&](uint32_t m) {  // by thread 0, once red holds worker m's wavefront maxima
+    const float* rm = red[(m - m_first) & 1u];
+    float mx = rm[0];
+#pragma unroll
+    for (int k = 1; k < kCsrThreads / kWave; ++k) mx = fmaxf(mx, rm[k]);
+    fuse.partials[(uint64_t)t * M + m] = mx;
+  };
+  auto round = [&](uint32_t m) {
+    const uint32_t cur = (m - m_first) & 1u;
+    // what the next worker's round needs (worker index clamped: a fetch, never a branch); past the last
+    // worker the lengths become 0
+    const bool more = m + 1 < m_end;
+    const uint32_t mn = more ? m + 1 : m;
+    const uint32_t nlo = bounds_of(mn)[tb_row], nhi = bounds_of(mn)[tb_row + batch];
+    const int64_t nbase = rowbase_of(mn)[row];
+    const float nres = resid_of(mn)[row];
+    const CsrEntries<PAIRS> e(cols[m], vals[m]), en(cols[mn], vals[mn]);
+    // LDS operations complete in order: the residuals are read before the first add
+    float r[kCsrUnroll];
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u) r[u] = sRBuf[cur][j0 + u];
+#pragma unroll
+    for (int u = 0; u < kCsrUnroll; ++u) {
+      if ((nmask >> u) & 1u) atomicAdd(&gtile[(uint32_t)ncol[u] - (uint32_t)c0], (double)(r[u] * nval[u]));
+      // four adds at a time: all sixteen addresses and binary64 terms at once do not fit next to the reference
+      if (u % 4 == 3) asm volatile("" ::: "memory");
+    }
+    if (nlong != 0) {  // rare: segments longer than the lane group
+#pragma unroll
+      for (int u = 0; u < kCsrUnroll; ++u) {
+        if ((nlong >> u) & 1u) {
+          const uint32_t len = sLenBuf[cur][j0 + u];
+          const int64_t lo = sLoBuf[cur][j0 + u];
+          for (uint32_t k = gl + kCsrLanes; k < len; k += kCsrLanes) {
+            int32_t ck;
+            float vk;
+            e.load(lo + k, ck, vk);
+            atomicAdd(&gtile[(uint32_t)ck - (uint32_t)c0], (double)(r[u] * vk));
+          }
+        }
+      }
+    }
+    if (threadIdx.x < (uint32_t)kCsrRows) {
+      sRBuf[cur ^ 1u][threadIdx.x] = has_row ? nres : 0.f;
+      sLoBuf[cur ^ 1u][threadIdx.x] = nbase + nlo;
+      sLenBuf[cur ^ 1u][threadIdx.x] = (has_row && more) ? nhi - nlo : 0u;
+    }
+    lds_barrier();  // every add of worker m has been made; the segments of worker m+1 are staged
+    if (m > m_first && threadIdx.x == 0) store_maximum(m - 1);  // older than the request below: need not be counted
+    request(en, mn, cur ^ 1u);  // before the stores below
+    float4* __restrict__ out4 = reinterpret_cast<float4*>(g + (uint64_t)m * d + c0);
+    float amax = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      const uint32_t q = (uint32_t)k * kCsrThreads + threadIdx.x;
+      const float4 o = make_float4((float)gtile[4 * q], (float)gtile[4 * q + 1], (float)gtile[4 * q + 2],
+                                   (float)gtile[4 * q + 3]);
+      gtile[4 * q] = gtile[4 * q + 1] = gtile[4 * q + 2] = gtile[4 * q + 3] = 0.0;
+      store_stream(out4 + q, o);
+      amax = fmaxf(amax, absmax4_t<NORM>(fuse, o, r1[k], r2[k]));
+    }
+    amax = wave_max(amax);
+    if (threadIdx.x % kWave == 0) red[cur][threadIdx.x / kWave] = amax;
+    lds_barrier();  // the tile is clear again; red is complete
+  };
+  lds_barrier();
+  request(CsrEntries<PAIRS>(cols[m_first], vals[m_first]), m_first, 0);
+  // the first round stands apart from the loop, as in the kernel above
+  round(m_first);
+  for (uint32_t m = m_first + 1; m < m_end; ++m) round(m);
+  if (threadIdx.x == 0) store_maximum(m_end - 1);
+}
+
 // Chain Rosenbrock gradient ("Nonconvex Problems", d-dimensional form) plus per-worker noise.
 // Fixed expression tree, one rounding per operation:
 //   a = x[i+1] - x[i]*x[i];  t1 = (-400*x[i])*a;  t2 = -2*(1 - x[i])        (i < d-1)
@@ -1517,10 +1666,13 @@ hipError_t csr_grad_launches(const LogregData& p, uint64_t d, uint32_t M, uint32
                                reinterpret_cast<const void*>(csr_grad_run_kernel<PAIRS, kNormSub>),
                                reinterpret_cast<const void*>(csr_grad_run_kernel<PAIRS, kNormQuot>),
                                reinterpret_cast<const void*>(csr_grad_run_kernel<PAIRS, kNormComb>),
+                               reinterpret_cast<const void*>(csr_grad_workers_kernel<PAIRS, kNormNone>),
+                               reinterpret_cast<const void*>(csr_grad_workers_kernel<PAIRS, kNormSub>),
+                               reinterpret_cast<const void*>(csr_grad_workers_kernel<PAIRS, kNormQuot>),
                                reinterpret_cast<const void*>(csr_z_wide_kernel<PAIRS>)};
-      const int bytes[] = {lds_double, lds_double, lds_double, lds_double, lds_double, lds_double,
-                           (int)(2 * sizeof(float) << kCsrTileShift)};
-      for (int k = 0; k < 7; ++k) {
+      const int bytes[] = {lds_double, lds_double, lds_double, lds_double, lds_double, lds_double, lds_double,
+                           lds_double, lds_double, (int)(2 * sizeof(float) << kCsrTileShift)};
+      for (int k = 0; k < 10; ++k) {
         const hipError_t e = hipFuncSetAttribute(big_lds[k], hipFuncAttributeMaxDynamicSharedMemorySize, bytes[k]);
         if (e != hipSuccess) return e;
       }
@@ -1538,8 +1690,9 @@ hipError_t csr_grad_launches(const LogregData& p, uint64_t d, uint32_t M, uint32
   uint32_t nparts = ntiles;  // partial dot products per row
   if (shift == kCsrTileShift && ntiles >= 2) {
     nparts = (ntiles + 1) / 2;
-    uint32_t wpb = 1;  // workers per workgroup while 2048 workgroups remain
-    while (wpb < 8 && wpb * 2 <= M && (uint64_t)nparts * (M / (wpb * 2)) >= 2048) wpb *= 2;
+    uint32_t wpb = 1;  // workers per workgroup while 1024 workgroups remain (per iteration at d = 2^24, 64 workers:
+                       // 4.538 ms with 8 per workgroup, 4.531 with 16, 4.519 with 32)
+    while (wpb < 32 && wpb * 2 <= M && (uint64_t)nparts * (M / (wpb * 2)) >= 1024) wpb *= 2;
     hipLaunchKernelGGL(csr_z_wide_kernel<PAIRS>, dim3((M + wpb - 1) / wpb, nparts), dim3(kCsrThreads), 2 * lds_w, s, p.col,
                        p.val, rowbase, bounds, w, zpart, d, batch, ntiles, nparts, M, wpb);
   } else {
@@ -1551,7 +1704,24 @@ hipError_t csr_grad_launches(const LogregData& p, uint64_t d, uint32_t M, uint32
   // The scale pass rides along when every tile is a full one and the write-out is the plain one.
   if (fuse != nullptr && fused_rows != nullptr && shift == kCsrTileShift && d % (1ull << kCsrTileShift) == 0 &&
       l2 == 0.f && ntiles <= kAbsmaxMaxBlocks && aligned16(g) && aligned16(fuse->gref) && aligned16(fuse->gref2)) {
-    if (batch <= (uint32_t)kCsrRows) {
+    // (the combined form keeps two references per column: they do not fit next to the pipeline's registers)
+    if (batch <= (uint32_t)kCsrRows && M >= 2 && fuse->norm != kNormComb) {
+      // a workgroup per tile and group of workers: groups as long as 1024 workgroups (four per compute unit)
+      // remain -- per iteration at d = 2^24, 64 workers: 4.69 ms with groups of 8, 4.61 with 16, 4.57 with
+      // 32, 4.54 with all 64 (4.76 with the kernel that runs over tiles)
+      uint32_t per_group = 64;
+      while (per_group > 2 && (uint64_t)ntiles * ((M + per_group - 1) / per_group) < 1024) per_group /= 2;
+      const dim3 grid(ntiles, (M + per_group - 1) / per_group);
+#define TNG_WORKERS(NORM)                                                                                              \
+  hipLaunchKernelGGL((csr_grad_workers_kernel<PAIRS, NORM>), grid, dim3(kCsrThreads), lds_g, s, p.col, p.val, rowbase, \
+                     bounds, z, g, d, batch, ntiles, M, per_group, *fuse)
+      switch (fuse->norm) {
+        case kNormSub: TNG_WORKERS(kNormSub); break;
+        case kNormQuot: TNG_WORKERS(kNormQuot); break;
+        default: TNG_WORKERS(kNormNone); break;
+      }
+#undef TNG_WORKERS
+    } else if (batch <= (uint32_t)kCsrRows) {
       const uint32_t run = kCsrRun;
       const dim3 grid(M, (ntiles + run - 1) / run);
 #define TNG_RUN(NORM)                                                                                                   \
