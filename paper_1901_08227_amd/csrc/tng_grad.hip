@@ -518,6 +518,17 @@ static_assert(kCsrGroups * kCsrUnroll == kCsrRows, "one sweep of the lane groups
 // memory lines they touch, so one piece of twice the length moves the same entries in about two
 // thirds of the line traffic, with half the load instructions.
 typedef int v2i_t __attribute__((ext_vector_type(2)));
+// Which column tile (of n, one per workgroup along x) workgroup bx takes.  Workgroups are handed to the
+// eight compute dies in turn (bx mod 8), each die with an L2 of its own: die k gets the k-th eighth of the
+// tiles, in order, so that the workgroups running side by side on a die are on ADJACENT tiles and the memory
+// lines shared by the end of one tile's row segment and the start of the next tile's are fetched from HBM
+// once (a bijection for any n; only the traffic depends on how the hardware really deals workgroups out).
+__device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t bx, uint32_t n) {
+  constexpr uint32_t kDies = 8;
+  if (n % kDies != 0) return bx;  // rows of the grid would start on different dies: keep the plain order
+  return (bx % kDies) * (n / kDies) + bx / kDies;
+}
+
 template <bool PAIRS>
 struct CsrEntries {
   GlobalPtr<int32_t> c;  // column ids, or the pairs viewed as 32-bit words (column at 2 pos, value at 2 pos + 1)
@@ -788,7 +799,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
   extern __shared__ float wtile[];  // w over the columns of both tiles
   __shared__ __align__(16) int64_t sLoBuf[2][kCsrRows];  // segment starts and lengths, this step's and the next one's
   __shared__ __align__(16) uint32_t sLenBuf[2][kCsrRows];
-  const uint32_t pair = blockIdx.y;
+  const uint32_t pair = tile_of_workgroup(blockIdx.x, npairs);
   const uint32_t t_lo = 2 * pair, t_hi = min(2 * pair + 2, ntiles);
   constexpr uint32_t T = 2u << kCsrTileShift;
   const uint64_t c0 = (uint64_t)t_lo << kCsrTileShift;
@@ -813,7 +824,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
   // worker; the segment bounds of the next step are fetched while this step's entries are on their
   // way (every thread fetches, the row index clamped, so that no load sits under a condition).
   static_assert(kCsrThreads >= kCsrRows, "one thread per staged row");
-  const uint32_t m_first = blockIdx.x * workers_per_block, m_last = min(m_first + workers_per_block, M);
+  const uint32_t m_first = blockIdx.y * workers_per_block, m_last = min(m_first + workers_per_block, M);
   const uint32_t trips = (batch + kCsrRows - 1) / kCsrRows;
   const uint32_t steps = (m_last - m_first) * trips;
   auto fetch_bounds = [&](uint32_t step, int64_t& start, uint32_t& length) {
@@ -1211,7 +1222,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_workers_kernel(const int
   __shared__ float red[2][kCsrThreads / kWave];  // by parity of the round: read in the round after it was written
   constexpr uint32_t T = 1u << kCsrTileShift;
   constexpr int kPer = (int)(T / (4 * kCsrThreads));
-  const uint32_t t = blockIdx.x;
+  const uint32_t t = tile_of_workgroup(blockIdx.x, ntiles);
   const uint32_t m_first = blockIdx.y * per_group;
   const uint32_t m_end = min(m_first + per_group, M);
   const uint64_t c0 = (uint64_t)t << kCsrTileShift;
@@ -1693,7 +1704,7 @@ hipError_t csr_grad_launches(const LogregData& p, uint64_t d, uint32_t M, uint32
     uint32_t wpb = 1;  // workers per workgroup while 1024 workgroups remain (per iteration at d = 2^24, 64 workers:
                        // 4.538 ms with 8 per workgroup, 4.531 with 16, 4.519 with 32)
     while (wpb < 32 && wpb * 2 <= M && (uint64_t)nparts * (M / (wpb * 2)) >= 1024) wpb *= 2;
-    hipLaunchKernelGGL(csr_z_wide_kernel<PAIRS>, dim3((M + wpb - 1) / wpb, nparts), dim3(kCsrThreads), 2 * lds_w, s, p.col,
+    hipLaunchKernelGGL(csr_z_wide_kernel<PAIRS>, dim3(nparts, (M + wpb - 1) / wpb), dim3(kCsrThreads), 2 * lds_w, s, p.col,
                        p.val, rowbase, bounds, w, zpart, d, batch, ntiles, nparts, M, wpb);
   } else {
     hipLaunchKernelGGL(csr_z_kernel<PAIRS>, dim3(M, ntiles), dim3(kCsrThreads), lds_w, s, p.col, p.val, rowbase, bounds, w,
