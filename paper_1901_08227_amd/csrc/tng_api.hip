@@ -33,6 +33,7 @@ struct tng_ctx {
   float* parts;           // dense problem, wide rows: partial gradients [M][splits][d] of the one-pass kernel, or null
   uint32_t* check;        // CSR problem: flag word of tng_validate_csr, then uint64[M] entry counts at +256 bytes
   double* sums;           // chunk and group sums of the order-pinned row sums (mean reference, l2 scale)
+  void* cand;             // scratch of the ternary coder that reads g once (candidate slots), or null
   std::vector<hipEvent_t> prof;  // optional timing events, 5 per slot
   uint32_t prof_slots;
   uint64_t enc_calls, dec_calls;
@@ -71,9 +72,25 @@ bool config_valid(const tng_config* c) {
   return true;
 }
 
+tng::CodecShape shape_of(const tng_config* cfg) {
+  tng::CodecShape sh{};
+  const uint64_t per = 32 / cfg->bits;
+  sh.d = cfg->d;
+  sh.words = (cfg->d + per - 1) / per;
+  sh.M = cfg->M;
+  sh.bits = (int)cfg->bits;
+  sh.norm = cfg->norm;
+  sh.eps = cfg->quot_eps;
+  sh.k0 = (uint32_t)(cfg->seed & 0xFFFFFFFFull);
+  sh.k1 = (uint32_t)(cfg->seed >> 32);
+  sh.scale_l2 = cfg->scale == TNG_SCALE_L2 ? 1 : 0;
+  sh.means = nullptr;
+  return sh;
+}
+
 struct Partition {
   size_t idx_off, resid_off, tables_off, partials_off, rowbase_off, bounds_off, zpart_off, sums_off, check_off, parts_off,
-      total;
+      cand_off, cand_bytes, total;
 };
 
 Partition partition(const tng_config* c) {
@@ -105,6 +122,9 @@ Partition partition(const tng_config* c) {
   p.parts_off = off;  // dense problem, wide rows: per-workgroup partial gradients of the one-pass kernel
   if (c->problem == TNG_PROB_LOGREG_DENSE)
     off += round_up((size_t)tng::dense_row_splits(c->d, c->M, c->batch) * c->M * c->d * sizeof(float));
+  p.cand_off = off;  // ternary coder that reads g once: sample maxima and candidate slots
+  p.cand_bytes = tng::candidate_scratch_bytes(shape_of(c));
+  off += round_up(p.cand_bytes);
   p.total = off;
   return p;
 }
@@ -194,6 +214,7 @@ tng_status encode_impl(tng_ctx* ctx, uint32_t iter, const float* g, const float*
   const uint64_t call = ctx->enc_calls++;
   mark(ctx, call, 0);
   hipError_t e = hipSuccess;
+  bool by_candidates = false;
   const bool mean_ref = ctx->cfg.norm == TNG_NORM_MEAN;
   if (mean_ref) {  // the worker's own reference comes first; the maximum of |g - mu| comes out of the same pass
     e = tng::launch_worker_means(ctx->shape, g, ctx->sums, ctx->shape.means,
@@ -206,14 +227,23 @@ tng_status encode_impl(tng_ctx* ctx, uint32_t iter, const float* g, const float*
     e = tng::launch_l2_scales(ctx->shape, g, gref, ctx->gref2, ctx->sums, scales, ctx->stream);
   } else if (fused_rows > 0) {
     // the reduction of the fused partial maxima is left to the quantise launch
+  } else if (ctx->cand != nullptr && tng::candidates_apply(ctx->shape, g, gref, ctx->gref2, codes)) {
+    // long rows of ternary codes: the scale pass also picks out the elements that can code non-zero, and the
+    // quantise pass works from those instead of reading g again
+    by_candidates = true;
+    e = tng::launch_absmax_candidates(ctx->shape, iter, g, gref, ctx->gref2, ctx->partials, ctx->cand, scales,
+                                      ctx->stream);
   } else {
     e = tng::launch_absmax(ctx->shape, g, gref, ctx->gref2, ctx->partials, scales, ctx->stream);
   }
   if (e != hipSuccess) return TNG_ERR_HIP;
   mark(ctx, call, 1);
   const bool fused = fused_rows > 0 && !mean_ref && ctx->cfg.scale == TNG_SCALE_MAX;
-  e = tng::launch_quantize_pack(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, ctx->partials,
-                                fused ? fused_rows : 0u, ctx->stream);
+  if (by_candidates)
+    e = tng::launch_quantize_candidates(ctx->shape, iter, g, gref, ctx->gref2, scales, ctx->cand, codes, ctx->stream);
+  else
+    e = tng::launch_quantize_pack(ctx->shape, iter, g, gref, ctx->gref2, scales, codes, ctx->partials,
+                                  fused ? fused_rows : 0u, ctx->stream);
   mark(ctx, call, 2);
   return hip_status(e);
 }
@@ -273,19 +303,7 @@ tng_status local_grad_impl(tng_ctx* ctx, uint32_t iter, const float* w, float* g
   }
 }
 
-void set_shape(tng_ctx* ctx, const tng_config* cfg) {
-  const uint64_t per = 32 / cfg->bits;
-  ctx->shape.d = cfg->d;
-  ctx->shape.words = (cfg->d + per - 1) / per;
-  ctx->shape.M = cfg->M;
-  ctx->shape.bits = (int)cfg->bits;
-  ctx->shape.norm = cfg->norm;
-  ctx->shape.eps = cfg->quot_eps;
-  ctx->shape.k0 = (uint32_t)(cfg->seed & 0xFFFFFFFFull);
-  ctx->shape.k1 = (uint32_t)(cfg->seed >> 32);
-  ctx->shape.scale_l2 = cfg->scale == TNG_SCALE_L2 ? 1 : 0;
-  ctx->shape.means = nullptr;
-}
+void set_shape(tng_ctx* ctx, const tng_config* cfg) { ctx->shape = shape_of(cfg); }
 
 tng_status upload_tables(tng_ctx* ctx, const void* const* t0, const void* const* t1, const void* const* t2,
                          const void* const* t3, const uint64_t* n_rows) {
@@ -362,7 +380,8 @@ tng_status tng_create(const tng_config* cfg, void* workspace, size_t workspace_b
   ctx->zpart = reinterpret_cast<float*>(base + p.zpart_off);
   ctx->sums = reinterpret_cast<double*>(base + p.sums_off);
   ctx->check = reinterpret_cast<uint32_t*>(base + p.check_off);
-  ctx->parts = p.total > p.parts_off ? reinterpret_cast<float*>(base + p.parts_off) : nullptr;
+  ctx->parts = p.cand_off > p.parts_off ? reinterpret_cast<float*>(base + p.parts_off) : nullptr;
+  ctx->cand = p.cand_bytes != 0 ? static_cast<void*>(base + p.cand_off) : nullptr;
   ctx->have_dense = ctx->have_csr = false;
   ctx->have_index = false;
   ctx->csr_pairs = false;

@@ -300,7 +300,8 @@ template <int NORM, int MC>
 __global__ __launch_bounds__(kBlock) void absmax_vec_kernel(GradRows g, const float4* __restrict__ ref4,
                                                             const float4* __restrict__ ref24,
                                                             float* partials, uint64_t nvec,
-                                                            uint32_t M, float eps, const float* __restrict__ means) {
+                                                            uint32_t M, float eps, const float* __restrict__ means,
+                                                            uint32_t tile_stride) {
   constexpr int L = kAbsmaxLoads;
   constexpr uint64_t kWaveTile = (uint64_t)kWave * L;
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -309,8 +310,9 @@ __global__ __launch_bounds__(kBlock) void absmax_vec_kernel(GradRows g, const fl
 #pragma unroll
   for (int mm = 0; mm < MC; ++mm) mx[mm] = 0.f;
   const uint64_t ntiles = (nvec + kWaveTile - 1) / kWaveTile;  // wavefront tiles
-  for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < ntiles;
-       tile += (uint64_t)gridDim.x * kWavesPerBlock) {
+  // tile_stride > 1: the maximum over a sample of the row only (every tile_stride-th tile)
+  for (uint64_t tile = ((uint64_t)blockIdx.x * kWavesPerBlock + wave) * tile_stride; tile < ntiles;
+       tile += (uint64_t)gridDim.x * kWavesPerBlock * tile_stride) {
     RefTile<NORM> rt[L];
     uint64_t iv[L];
     const bool full = (tile + 1) * kWaveTile <= nvec;  // wave-uniform
@@ -561,10 +563,12 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
     GradRows g, const float4* __restrict__ ref4, const float4* __restrict__ ref24,
     const float* __restrict__ scales, uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words,
     uint32_t M, float eps, uint32_t k0, uint32_t k1, uint32_t iter, const float* __restrict__ means,
-    FusedScale fs) {
+    FusedScale fs, const uint32_t* __restrict__ skip_if_set) {
   constexpr int L = kLoadsPerLane;
   constexpr int WPW = kWave * L * 4 * BITS / 32;  // packed words per wavefront tile
   __shared__ __attribute__((aligned(16))) FragmentBuffer<WPW, MC> lds;
+  // the codes come from the candidate slots instead (quantize_candidates_kernel) when that word is set
+  if (skip_if_set != nullptr && skip_if_set[0] != 0u) return;
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const uint64_t wave_tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
   const uint64_t word_base = wave_tile * WPW;
@@ -594,6 +598,241 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
     quantize_rows<NORM, BITS, WPW, MC, false, FUSED, false>(q, lds, wave, lane, g, scales, codes, nvec, words,
                                                             word_base, m0, m_end, iter, k0, k1, means, fs, M);
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// Ternary coder without a second pass over g   (section "Gradient Compression": P(z = 1) = |v| / R)
+//
+// In high dimension nearly every element of a row codes to 0: the largest element R is far above the
+// typical |v|, and only a fraction E|v| / R of the elements -- a few percent -- draws z = 1.  Whether an
+// element CAN code non-zero is decided in the scale pass, before R is known, against any lower bound
+// R^ <= R at hand: fl(1 / R^) >= fl(1 / R) (the correctly rounded quotient is monotone) and
+// fl(|v| x) is monotone in x, so  u >= fl(|v| fl(1 / R^))  implies  u >= fl(|v| fl(1 / R)):  level 0
+// whatever R turns out to be.  The elements that fail this test -- the candidates -- are kept in a slot per
+// worker and wavefront tile, one 32-bit word each: sign, exponent and the upper 13 bits of the significand
+// of the normalised value, and in place of the lower 10 bits the position within the tile.  R^ is the
+// maximum over a sample of the row taken beforehand (one tile in kSampleStride).  The quantise pass then
+// reads the slots instead of g: the word brackets |v| between two numbers 2^-13 apart (relatively), the
+// level is monotone in |v|, so where both ends give the same level (the same draw, the same arithmetic as
+// quantize_code, the real R) that is the level; the few elements where they differ (the draw falls
+// between the two thresholds: one candidate in ten thousand) are fetched from g and coded from the value
+// itself.  Everything else is cleared, and the words are packed.  A slot that overflowed (a tile with more
+// than kCandCap candidates) sends its tile through the ordinary path.  The codes are those of the two-pass
+// coder bit for bit; what changes is that g is read once: 4 + 4/M bytes per element instead of 8 + 8/M.
+// Used for 2-bit codes with the largest-magnitude scale when every wavefront tile is a full one
+// (d a multiple of 1024) and the row is long enough for the second read to come from memory.
+// ------------------------------------------------------------------------------------------
+constexpr int kCandCap = 127;         // candidates a slot holds; word 0 of a slot is their count
+constexpr int kSlotEntries = 128;     // 32-bit words per slot: 512 bytes per worker and wavefront tile
+constexpr uint32_t kSampleStride = 128;  // the sample: every 128th wavefront tile of a row
+constexpr uint32_t kCandPosMask = 0x3FFu;  // low 10 bits of a candidate word: position within the tile
+
+template <int NORM, int MC>
+__global__ __launch_bounds__(kBlock) void absmax_select_kernel(GradRows g, const float4* __restrict__ ref4,
+                                                               const float4* __restrict__ ref24, float* partials,
+                                                               uint64_t nvec, uint32_t M, float eps,
+                                                               const float* __restrict__ sample_max,
+                                                               uint32_t* __restrict__ slots,
+                                                               uint32_t* __restrict__ overflowed, uint32_t k0,
+                                                               uint32_t k1, uint32_t iter) {
+  constexpr int L = kAbsmaxLoads;
+  constexpr uint64_t kWaveTile = (uint64_t)kWave * L;
+  constexpr bool RECIP = kByReciprocal<NORM, MC>;
+  static_assert(L == kLoadsPerLane, "the quantise pass reads the slots by the same tiles");
+  __shared__ __attribute__((aligned(16))) uint32_t stage[kWavesPerBlock][kWave * kAbsmaxLoads * 4 + 4];  // count + a whole tile
+  __shared__ uint32_t over[kWavesPerBlock];
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const uint32_t m0 = blockIdx.y * MC;
+  const uint32_t count = min((uint32_t)MC, M - m0);
+  uint32_t nover = 0;  // slots of this wavefront that overflowed
+  float mx[MC];
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) mx[mm] = 0.f;
+  const uint64_t ntiles = nvec / kWaveTile;  // every tile is a full one
+  const uint32_t lane4 = 4u * (uint32_t)lane;
+  // The lower bound R^ of a worker's scale is the maximum over the sample of its row.  The test
+  //   u < fl(|v| fl(1 / R^)),  u = (word >> 8) 2^-24,
+  // is made in three operations and from above:  float(word) < |v| c1 + 258  with
+  // c1 = fl(fl(1 / R^) 2^32 (1 + 2^-20)).  It holds whenever the exact test does (then word < 2^32 fl(|v| / R^) + 256;
+  // converting the word and the two roundings on the right move either side by less than 2^-23 relatively,
+  // which the factor 1 + 2^-20 and the 2 added to 256 cover) and passes 2^-20 more elements than it: the
+  // quantise pass codes a candidate exactly, so more is harmless.  Below 2^-90 no bound is claimed (c1 would
+  // overflow): every non-zero element is a candidate.
+  float c1[MC];
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) {
+    const float r_hat = sample_max[min(m0 + (uint32_t)mm, M - 1)];
+    c1[mm] = r_hat >= 0x1p-90f ? (1.0f / r_hat) * (0x1p32f * (1.0f + 0x1p-20f)) : INFINITY;
+  }
+  for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < ntiles;
+       tile += (uint64_t)gridDim.x * kWavesPerBlock) {
+    RefTile<NORM> rt[L];
+    uint64_t iv[L];
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+      iv[j] = tile * kWaveTile + (uint64_t)j * kWave + lane;
+      rt[j].load(ref4, ref24, iv[j], eps);
+      if (RECIP) rt[j].reciprocals();
+    }
+    // one worker's part of the tile: its maximum, and its candidates into the slot
+    auto worker = [&](const float4 (&x)[L], int mm) {
+      const uint32_t m = m0 + (uint32_t)mm;
+      float amax = 0.f;
+      uint32_t base = 1;  // entry 0 is the header
+#pragma unroll
+      for (int j = 0; j < L; ++j) {
+        const float4 v = normalize4<NORM, RECIP>(x[j], rt[j], 0.f);
+        amax = max3_abs(v.z, v.w, max3_abs(v.x, v.y, amax));
+        const U32x4 rnd = philox4x32_10((uint32_t)iv[j], m, iter, 0u, k0, k1);
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+        const uint32_t rr[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const bool cand = (float)rr[c] < __builtin_fmaf(fabsf(vv[c]), c1[mm], 258.0f);
+          const uint64_t mask = __builtin_amdgcn_ballot_w64(cand);
+          const uint32_t pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+          // (the staging area holds a whole tile: no test against the slot's capacity here)
+          if (cand) stage[wave][pos] = (__float_as_uint(vv[c]) & ~kCandPosMask) | (uint32_t)(256 * j + c) | lane4;
+          base += (uint32_t)__builtin_popcountll(mask);
+        }
+      }
+      mx[mm] = fmaxf(mx[mm], amax);
+      if (lane == 0) stage[wave][0] = base - 1;  // candidates found (more than kCandCap: the slot is not used)
+      wave_lds_fence();
+      // Words to write, the count included; of a slot that overflowed only the count.  Whole 128-byte memory
+      // lines are written (32 words, the last ones whatever the staging area holds).
+      const bool fits = base <= (uint32_t)kSlotEntries;
+      nover += fits ? 0u : 1u;
+      const uint32_t used = fits ? (base + 31u) & ~31u : 32u;
+      if (4u * lane < used) {
+        const v4u_t four = *reinterpret_cast<const v4u_t*>(&stage[wave][4 * lane]);
+        v4u_t* dst = reinterpret_cast<v4u_t*>(slots + ((uint64_t)m * ntiles + tile) * kSlotEntries) + lane;
+        asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(four) : "memory");
+      }
+      wave_lds_fence();
+    };
+    float4 xa[L], xb[L];
+    auto row = [&](int mm) { return g.row(min(m0 + (uint32_t)mm, M - 1)); };
+    absmax_load<NORM, true>(row(0), iv, nvec, xa);
+#pragma unroll
+    for (int mm = 0; mm < MC; mm += 2) {
+      if (mm + 1 < MC) absmax_load<NORM, true>(row(mm + 1), iv, nvec, xb);
+      if ((uint32_t)mm < count) worker(xa, mm);
+      if (mm + 1 < MC) {
+        if (mm + 2 < MC) absmax_load<NORM, true>(row(mm + 2), iv, nvec, xa);
+        if ((uint32_t)(mm + 1) < count) worker(xb, mm + 1);
+      }
+    }
+  }
+  if (lane == 0) over[wave] = nover;
+  block_max_to_partials<MC>(mx, m0, M, partials);  // has a workgroup barrier after its own LDS writes
+  if (threadIdx.x == 0) {
+    uint32_t total = 0;
+#pragma unroll
+    for (int k = 0; k < kWavesPerBlock; ++k) total += over[k];
+    overflowed[(uint64_t)blockIdx.y * gridDim.x + blockIdx.x] = total;
+  }
+}
+
+// Whether the slots are worth using: at most one tile in fifty may have overflowed (such tiles go through a
+// plain, unpipelined form of the ordinary path).  use_slots[0] = 1 or 0; one workgroup.
+__global__ __launch_bounds__(kBlock) void candidate_vote_kernel(const uint32_t* __restrict__ overflowed, uint32_t n,
+                                                                uint64_t tiles_in_all, uint32_t* __restrict__ use_slots) {
+  __shared__ unsigned long long sum;
+  if (threadIdx.x == 0) sum = 0ull;
+  __syncthreads();
+  unsigned long long mine = 0;
+  for (uint32_t i = threadIdx.x; i < n; i += kBlock) mine += overflowed[i];
+  atomicAdd(&sum, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) use_slots[0] = sum * 50ull <= tiles_in_all ? 1u : 0u;
+}
+
+// The packed codes of a tile from its slots.  One wavefront per tile as in the quantiser; the words of a
+// worker are cleared in LDS, the candidates' codes are or-ed in, and all workers' words are written at the
+// end as the quantiser writes them.
+template <int NORM, int MC>
+__global__ __launch_bounds__(kBlock) void quantize_candidates_kernel(
+    GradRows g, const float4* __restrict__ ref4, const float4* __restrict__ ref24, const float* __restrict__ scales,
+    const uint32_t* __restrict__ slots, uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words, uint32_t M,
+    float eps, uint32_t k0, uint32_t k1, uint32_t iter, const uint32_t* __restrict__ use_slots) {
+  constexpr int L = kLoadsPerLane;
+  constexpr int WPW = kWave * L * 4 * 2 / 32;  // 64 packed words per wavefront tile
+  static_assert(WPW == kWave, "one word per lane");
+  __shared__ __attribute__((aligned(16))) FragmentBuffer<WPW, MC> lds;
+  if (use_slots[0] == 0u) return;  // too many tiles overflowed: the ordinary quantiser runs instead
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const uint64_t ntiles = nvec / (kWave * L);
+  const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (tile >= ntiles) return;  // whole wavefronts; nothing below meets the other wavefronts
+  const uint64_t word_base = tile * WPW;
+  const uint32_t m0 = blockIdx.y * MC;
+  const uint32_t m_end = min(m0 + MC, M);
+  // Counts and the first 64 words of all the workers' slots are requested at once (a slot rarely holds
+  // more: the rest is fetched when its count says so), so that the workgroup waits for memory once and not
+  // once per worker.  Words past a slot's count are whatever an earlier call left there and are not used.
+  uint32_t cnt[MC];
+  uint32_t first[MC];
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) {
+    const uint32_t m = min(m0 + (uint32_t)mm, M - 1);
+    const uint32_t* __restrict__ sl = slots + ((uint64_t)m * ntiles + tile) * kSlotEntries;
+    cnt[mm] = sl[0];
+    first[mm] = sl[1 + lane];
+  }
+#pragma unroll
+  for (int mm = 0; mm < MC; ++mm) {
+    const uint32_t m = m0 + (uint32_t)mm;
+    if (m >= m_end) break;
+    const int slot = mm;
+    const float R = scales[m];
+    const uint32_t* __restrict__ sl = slots + ((uint64_t)m * ntiles + tile) * kSlotEntries;
+    const uint32_t n = R == 0.f ? 0u : cnt[mm];
+    if (n <= (uint32_t)kCandCap) {
+      lds.b32[slot][wave][lane] = 0u;
+      wave_lds_fence();
+      const float inv_r = R == 0.f ? 0.f : 1.0f / R;
+      auto code_one = [&](uint32_t e) {
+        const uint32_t pos = e & kCandPosMask;
+        const uint64_t coord = tile * (uint64_t)(kWave * L * 4) + pos;
+        const U32x4 rnd = philox4x32_10((uint32_t)(coord >> 2), m, iter, 0u, k0, k1);
+        const uint32_t sel = pos & 3u;
+        const uint32_t word = sel == 0u ? rnd.x : sel == 1u ? rnd.y : sel == 2u ? rnd.z : rnd.w;
+        // |v| lies between the word with its low bits cleared and the word with them set; quantize_code's
+        // level is [u < |v| inv_r], monotone in |v|
+        const float u = uniform24(word);
+        const float lo = __uint_as_float(e & 0x7FFFFC00u), hi = __uint_as_float((e & 0x7FFFFC00u) | kCandPosMask);
+        uint32_t code;
+        if (u < lo * inv_r) {
+          code = 1u | ((e >> 31) << 1);
+        } else if (!(u < hi * inv_r)) {
+          code = 0u;
+        } else {  // the draw falls between the two thresholds: from the value itself
+          float r1 = 0.f;
+          if (NORM == kNormSub) r1 = reinterpret_cast<const float*>(ref4)[coord];
+          code = quantize_code<2>(normalize_w<NORM>(g.base[(uint64_t)m * g.pitch + coord], r1, 1.f, 0.f), inv_r, word);
+        }
+        if (code != 0u) atomicOr(&lds.b32[slot][wave][pos >> 4], code << (2u * (pos & 15u)));
+      };
+      if ((uint32_t)lane < n) code_one(first[mm]);
+      if (n > (uint32_t)kWave && (uint32_t)(kWave + lane) < n) code_one(sl[1 + kWave + lane]);
+    } else {  // the slot overflowed: this worker's tile goes through the ordinary path
+      QuantLane<NORM> q;
+#pragma unroll
+      for (int j = 0; j < L; ++j) {
+        q.iv[j] = tile * (kWave * L) + (uint64_t)j * kWave + lane;
+        q.ok[j] = true;
+        q.rt[j].load(ref4, ref24, q.iv[j], eps);
+      }
+      float4 x[L];
+      uint32_t frag[L];
+      load_worker_tile<NORM, true>(q, g, m, x);
+      quantize_worker_tile<NORM, 2, true, false>(q, x, R, 0.f, m, iter, k0, k1, frag);
+      store_packed<2, WPW, MC, true>(lds, slot, wave, lane, frag, codes, word_base, words);
+    }
+  }
+  flush_packed<WPW, MC>(lds, wave, lane, codes, words, word_base, m0, m_end - m0);
 }
 
 // Any d (rows need not be 16-byte aligned): one thread per packed word.
@@ -1214,17 +1453,117 @@ inline bool vec_ok(uint64_t d, const void* a, const void* b, const void* c) {
 
 template <int NORM, int MC>
 hipError_t absmax_vec_launch(const CodecShape& c, uint64_t dv, const float* g, const float* gref, const float* gref2,
-                             float* partials, uint32_t* nblocks, hipStream_t s) {
+                             float* partials, uint32_t* nblocks, hipStream_t s, uint32_t tile_stride = 1) {
   const uint64_t nvec = dv / 4;
-  const uint32_t per_y = div_up_u32(nvec, (uint64_t)kBlock * kAbsmaxLoads);
+  const uint32_t per_y = div_up_u32(nvec, (uint64_t)kBlock * kAbsmaxLoads * tile_stride);
   const uint32_t cap = kAbsmaxMaxBlocks - 1;  // one row of partials is kept for the rows' scalar remainder
   const uint32_t gx = per_y < cap ? per_y : cap;
   *nblocks = gx;
   dim3 grid(gx, (c.M + MC - 1) / MC);
   hipLaunchKernelGGL((absmax_vec_kernel<NORM, MC>), grid, dim3(kBlock), 0, s, GradRows{g, c.d},
                      reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), partials, nvec,
-                     c.M, c.eps, c.means);
+                     c.M, c.eps, c.means, tile_stride);
   return hipGetLastError();
+}
+
+// Scratch of the ternary coder that reads g once: the word that says whether the slots are used, the
+// sample's maxima [M], the sample pass's partial maxima [kAbsmaxMaxBlocks][M], the overflow counts of the
+// scale pass's workgroups (as many), the slots [M][d / 1024] of 1 KiB.
+struct CandidateScratch {
+  uint32_t* use_slots;
+  float* sample_max;
+  float* sample_partials;
+  uint32_t* overflowed;
+  uint32_t* slots;
+};
+inline size_t round_up_256(size_t v) { return (v + 255) / 256 * 256; }
+inline size_t candidate_head_bytes(uint32_t M) {
+  return 256 + round_up_256((size_t)M * sizeof(float)) + 2 * round_up_256((size_t)kAbsmaxMaxBlocks * M * sizeof(float));
+}
+inline CandidateScratch candidate_scratch(const CodecShape& c, void* scratch) {
+  unsigned char* p = static_cast<unsigned char*>(scratch);
+  CandidateScratch cs;
+  cs.use_slots = reinterpret_cast<uint32_t*>(p);
+  p += 256;
+  cs.sample_max = reinterpret_cast<float*>(p);
+  p += round_up_256((size_t)c.M * sizeof(float));
+  cs.sample_partials = reinterpret_cast<float*>(p);
+  p += round_up_256((size_t)kAbsmaxMaxBlocks * c.M * sizeof(float));
+  cs.overflowed = reinterpret_cast<uint32_t*>(p);
+  p += round_up_256((size_t)kAbsmaxMaxBlocks * c.M * sizeof(float));
+  cs.slots = reinterpret_cast<uint32_t*>(p);
+  return cs;
+}
+
+template <int NORM>
+hipError_t absmax_candidates_dispatch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                                      const float* gref2, float* partials, const CandidateScratch& cs, float* scales,
+                                      hipStream_t s) {
+  const uint64_t nvec = c.d / 4;
+  const int mc = pick_workers_per_block(c.M, (nvec + kBlock * kAbsmaxLoads - 1) / (kBlock * kAbsmaxLoads), 0.3);
+  uint32_t nsample = 0, nblocks = 0;
+  hipError_t e;
+  // the sample: every kSampleStride-th wavefront tile of every row, workers in the same groups
+  switch (mc) {
+    case 8: e = absmax_vec_launch<NORM, 8>(c, c.d, g, gref, gref2, cs.sample_partials, &nsample, s, kSampleStride); break;
+    case 4: e = absmax_vec_launch<NORM, 4>(c, c.d, g, gref, gref2, cs.sample_partials, &nsample, s, kSampleStride); break;
+    case 2: e = absmax_vec_launch<NORM, 2>(c, c.d, g, gref, gref2, cs.sample_partials, &nsample, s, kSampleStride); break;
+    default: e = absmax_vec_launch<NORM, 1>(c, c.d, g, gref, gref2, cs.sample_partials, &nsample, s, kSampleStride); break;
+  }
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(absmax_finish_kernel, dim3(c.M), dim3(kBlock), 0, s, cs.sample_partials, nsample, c.M, cs.sample_max);
+  const uint32_t per_y = div_up_u32(nvec, (uint64_t)kBlock * kAbsmaxLoads);
+  const uint32_t cap = kAbsmaxMaxBlocks - 1;
+  nblocks = per_y < cap ? per_y : cap;
+#define TNG_SELECT(MC)                                                                                              \
+  hipLaunchKernelGGL((absmax_select_kernel<NORM, MC>), dim3(nblocks, (c.M + MC - 1) / MC), dim3(kBlock), 0, s,      \
+                     GradRows{g, c.d}, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), \
+                     partials, nvec, c.M, c.eps, cs.sample_max, cs.slots, cs.overflowed, c.k0, c.k1, iter)
+  switch (mc) {
+    case 8: TNG_SELECT(8); break;
+    case 4: TNG_SELECT(4); break;
+    case 2: TNG_SELECT(2); break;
+    default: TNG_SELECT(1); break;
+  }
+#undef TNG_SELECT
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(absmax_finish_kernel, dim3(c.M), dim3(kBlock), 0, s, partials, nblocks, c.M, scales);
+  hipLaunchKernelGGL(candidate_vote_kernel, dim3(1), dim3(kBlock), 0, s, cs.overflowed,
+                     nblocks * ((c.M + (uint32_t)mc - 1) / (uint32_t)mc), (uint64_t)c.M * (nvec / (kWave * kAbsmaxLoads)),
+                     cs.use_slots);
+  return hipGetLastError();
+}
+
+template <int NORM, int BITS>
+hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                             const float* gref2, float* scales, uint32_t* codes, const float* partials,
+                             uint32_t fused_rows, hipStream_t s, const uint32_t* skip_if_set = nullptr);
+
+template <int NORM>
+hipError_t quantize_candidates_dispatch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                                        const float* gref2, const float* scales, const CandidateScratch& cs,
+                                        uint32_t* codes, hipStream_t s) {
+  const uint64_t nvec = c.d / 4;
+  const uint64_t tiles = (nvec + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);  // workgroups of 4 wavefront tiles
+  const int mc = pick_workers_per_block(c.M, tiles, 0.0, 16);
+#define TNG_QC(MC)                                                                                                   \
+  hipLaunchKernelGGL((quantize_candidates_kernel<NORM, MC>), dim3((uint32_t)tiles, (c.M + MC - 1) / MC), dim3(kBlock), 0, \
+                     s, GradRows{g, c.d}, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), \
+                     scales, cs.slots, codes, nvec, c.words, c.M, c.eps, c.k0, c.k1, iter, cs.use_slots)
+  switch (mc) {
+    case 16: TNG_QC(16); break;
+    case 8: TNG_QC(8); break;
+    case 4: TNG_QC(4); break;
+    case 2: TNG_QC(2); break;
+    default: TNG_QC(1); break;
+  }
+#undef TNG_QC
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // the ordinary quantiser right behind it: one of the two returns at once, by the vote of the scale pass
+  return quantize_dispatch<NORM, 2>(c, iter, g, gref, gref2, const_cast<float*>(scales), codes, nullptr, 0, s,
+                                    cs.use_slots);
 }
 
 template <int NORM>
@@ -1262,13 +1601,13 @@ hipError_t absmax_dispatch(const CodecShape& c, const float* g, const float* gre
 template <int NORM, int BITS, int MC, bool FUSED>
 hipError_t quantize_vec_launch(const CodecShape& c, uint64_t dv, uint32_t iter, const float* g, const float* gref,
                                const float* gref2, const float* scales, uint32_t* codes, const FusedScale& fs,
-                               hipStream_t s) {
+                               hipStream_t s, const uint32_t* skip_if_set = nullptr) {
   const uint64_t nvec = dv / 4;
   const uint64_t tiles = (nvec + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
   dim3 grid((uint32_t)tiles, (c.M + MC - 1) / MC);
   hipLaunchKernelGGL((quantize_pack_vec_kernel<NORM, BITS, MC, FUSED>), grid, dim3(kBlock), 0, s, GradRows{g, c.d},
                      reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), scales, codes, nvec,
-                     c.words, c.M, c.eps, c.k0, c.k1, iter, c.means, fs);
+                     c.words, c.M, c.eps, c.k0, c.k1, iter, c.means, fs, skip_if_set);
   return hipGetLastError();
 }
 
@@ -1278,7 +1617,7 @@ hipError_t quantize_vec_launch(const CodecShape& c, uint64_t dv, uint32_t iter, 
 template <int NORM, int BITS>
 hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
                              const float* gref2, float* scales, uint32_t* codes, const float* partials,
-                             uint32_t fused_rows, hipStream_t s) {
+                             uint32_t fused_rows, hipStream_t s, const uint32_t* skip_if_set) {
   const uint64_t dv = vector_part(c.d, gref, gref2);
   const bool vec = dv != 0;
   const uint64_t tiles = (dv / 4 + kBlock * kLoadsPerLane - 1) / (kBlock * kLoadsPerLane);
@@ -1296,11 +1635,11 @@ hipError_t quantize_dispatch(const CodecShape& c, uint32_t iter, const float* g,
       e = quantize_vec_launch<NORM, BITS, 1, true>(c, dv, iter, g, gref, gref2, scales, codes, fs, s);
     } else {
       switch (mc) {
-        case 16: e = quantize_vec_launch<NORM, BITS, 16, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
-        case 8: e = quantize_vec_launch<NORM, BITS, 8, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
-        case 4: e = quantize_vec_launch<NORM, BITS, 4, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
-        case 2: e = quantize_vec_launch<NORM, BITS, 2, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
-        default: e = quantize_vec_launch<NORM, BITS, 1, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s); break;
+        case 16: e = quantize_vec_launch<NORM, BITS, 16, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s, skip_if_set); break;
+        case 8: e = quantize_vec_launch<NORM, BITS, 8, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s, skip_if_set); break;
+        case 4: e = quantize_vec_launch<NORM, BITS, 4, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s, skip_if_set); break;
+        case 2: e = quantize_vec_launch<NORM, BITS, 2, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s, skip_if_set); break;
+        default: e = quantize_vec_launch<NORM, BITS, 1, false>(c, dv, iter, g, gref, gref2, scales, codes, fs, s, skip_if_set); break;
       }
     }
     if (e != hipSuccess || dv == c.d) return e;
@@ -1511,6 +1850,35 @@ hipError_t launch_l2_scales(const CodecShape& c, const float* g, const float* gr
     case kNormMean: return tree_sum_launch<kNormMean, true, false>(c, g, nullptr, nullptr, sums, scales, nullptr, s);
     default: return tree_sum_launch<kNormComb, true, false>(c, g, gref, gref2, sums, scales, nullptr, s);
   }
+}
+
+size_t candidate_scratch_bytes(const CodecShape& c) {
+  // 2-bit codes, largest-magnitude scale, a shared reference or none, whole wavefront tiles, and enough
+  // elements (2^26: 256 MiB of gradients) for the extra launches of the sample to be noise
+  // (not the quotient forms: there |v| is near 1 everywhere and a third of the elements code non-zero)
+  if (c.bits != 2 || c.scale_l2 != 0 || (c.norm != kNormNone && c.norm != kNormSub) || c.d % 1024 != 0) return 0;
+  if ((uint64_t)c.M * c.d < (1ull << 26) || c.d / 1024 < 4 * (uint64_t)kSampleStride) return 0;
+  return candidate_head_bytes(c.M) + (size_t)c.M * (c.d / 1024) * kSlotEntries * sizeof(uint32_t);
+}
+
+bool candidates_apply(const CodecShape& c, const float* g, const float* gref, const float* gref2,
+                      const uint32_t* codes) {
+  return candidate_scratch_bytes(c) != 0 && aligned16_or_null(g, gref, gref2, codes);
+}
+
+hipError_t launch_absmax_candidates(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                                    const float* gref2, float* partials, void* scratch, float* scales, hipStream_t s) {
+  const CandidateScratch cs = candidate_scratch(c, scratch);
+  if (c.norm == kNormSub) return absmax_candidates_dispatch<kNormSub>(c, iter, g, gref, nullptr, partials, cs, scales, s);
+  return absmax_candidates_dispatch<kNormNone>(c, iter, g, nullptr, nullptr, partials, cs, scales, s);
+}
+
+hipError_t launch_quantize_candidates(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                                      const float* gref2, const float* scales, void* scratch, uint32_t* codes,
+                                      hipStream_t s) {
+  const CandidateScratch cs = candidate_scratch(c, scratch);
+  if (c.norm == kNormSub) return quantize_candidates_dispatch<kNormSub>(c, iter, g, gref, nullptr, scales, cs, codes, s);
+  return quantize_candidates_dispatch<kNormNone>(c, iter, g, nullptr, nullptr, scales, cs, codes, s);
 }
 
 hipError_t launch_quantize_pack(const CodecShape& c, uint32_t iter, const float* g, const float* gref,

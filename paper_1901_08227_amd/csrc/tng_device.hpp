@@ -225,6 +225,29 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// The largest of 64 non-negative floats, the same value in every lane (a wavefront-uniform register), by
+// the data-parallel lane moves of the vector unit: within rows of 16 lanes by quad swaps and mirrors, then
+// lane 15 of a row into the next row, lane 31 into the upper half; lane 63 holds the result.  Six
+// instructions and a read of lane 63, no LDS round trips (wave_max above makes six of them).  The values
+// are compared as integers, which for non-negative floats is the same order.
+__device__ __forceinline__ float wave_max_nonneg(float x) {
+  int v = (int)__float_as_uint(x);
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));   // quad_perm: [1, 0, 3, 2]
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));   // quad_perm: [2, 3, 0, 1]
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x140, 0xF, 0xF, false));  // row_mirror
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x142, 0xA, 0xF, false));  // row_bcast:15 into rows 1 and 3
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xC, 0xF, false));  // row_bcast:31 into rows 2 and 3
+  return __uint_as_float((uint32_t)__builtin_amdgcn_readlane(v, 63));
+}
+
+// max(|a|, |b|, c) in one instruction (the magnitudes are taken by the operand modifiers).
+__device__ __forceinline__ float max3_abs(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, |%1|, |%2|, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);

@@ -45,6 +45,21 @@ hipError_t launch_worker_means(const CodecShape& c, const float* g, double* sums
 hipError_t launch_l2_scales(const CodecShape& c, const float* g, const float* gref, const float* gref2, double* sums,
                             float* scales, hipStream_t s);
 
+// The ternary coder that reads g once (2-bit codes, largest-magnitude scale): the scale pass also keeps,
+// per worker and tile of 1024 coordinates, the few elements that can code non-zero whatever the scale turns
+// out to be (tested against a lower bound of it), and the quantise pass codes those from the slots instead
+// of reading g again; same codes and scales as launch_absmax + launch_quantize_pack, bit for bit.
+// candidate_scratch_bytes: device scratch needed (256-byte aligned), 0 where the path does not apply
+// (other code widths, scales and normalisations, rows that are not whole tiles, small problems);
+// candidates_apply: whether it may be used for these operands (scratch size non-zero, 16-byte alignment).
+size_t candidate_scratch_bytes(const CodecShape& c);
+bool candidates_apply(const CodecShape& c, const float* g, const float* gref, const float* gref2, const uint32_t* codes);
+hipError_t launch_absmax_candidates(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                                    const float* gref2, float* partials, void* scratch, float* scales, hipStream_t s);
+hipError_t launch_quantize_candidates(const CodecShape& c, uint32_t iter, const float* g, const float* gref,
+                                      const float* gref2, const float* scales, void* scratch, uint32_t* codes,
+                                      hipStream_t s);
+
 // Reduction of nblocks rows of per-workgroup partial maxima (partials[block][m]) to scales[m].
 hipError_t launch_absmax_finish(const float* partials, uint32_t nblocks, uint32_t M, float* scales, hipStream_t s);
 
