@@ -99,8 +99,20 @@ def time_codec(torch, B, g, gref, bits, norm, steps, warmup, seed, scale=0):
     b_scale = (2 if norm == B.NORM_MEAN and scale == B.SCALE_L2 else 1) * 4 * M * d + b_ref
     b_quant = 4 * M * d + b_ref + 4 * M * words
     b_dec = 4 * M * words + b_ref + 4 * d
+    two_pass = b_scale + b_quant + b_dec
+    # long rows of ternary codes (Eq. 1 or no normalisation, largest-magnitude scale): the scale pass keeps the
+    # elements that can code non-zero and the quantise pass codes those, so g is read once; what the quantise
+    # pass must move is then the packed codes (the candidate words, a few percent of the elements, are the
+    # method's own overhead and are not counted as algorithmic bytes)
+    single_read = (bits == 2 and scale == B.SCALE_MAX and norm in (B.NORM_NONE, B.NORM_SUB)
+                   and d % 1024 == 0 and M * d >= 1 << 26 and d // 1024 >= 512)
+    if single_read:
+        b_quant = 4 * M * words
     return {
         "ms_per_step": ms,
+        "path": "g read once (candidate slots)" if single_read else "two passes over g",
+        "compulsory_bytes": 4 * M * d + b_ref + 4 * M * words + b_dec,
+        "compulsory_GBps": (4 * M * d + b_ref + 4 * M * words + b_dec) / (ms * 1e-3) / 1e9,
         "fp32_in_GBps": 4.0 * M * d / (ms * 1e-3) / 1e9,
         "kernels": {
             "absmax": {"ms": k_scale, "bytes": b_scale, "GBps": b_scale / (k_scale * 1e-3) / 1e9, **spread(t_scale)},
@@ -109,8 +121,8 @@ def time_codec(torch, B, g, gref, bits, norm, steps, warmup, seed, scale=0):
             "decode": {"ms": k_dec, "bytes": b_dec, "GBps": b_dec / (k_dec * 1e-3) / 1e9, **spread(t_dec)},
         },
         "bits_per_element": (32.0 * words * M + 32.0 * M * (2 if norm == B.NORM_MEAN else 1)) / (M * d),
-        "two_pass_bytes": b_scale + b_quant + b_dec,
-        "two_pass_GBps": (b_scale + b_quant + b_dec) / (ms * 1e-3) / 1e9,
+        "two_pass_bytes": two_pass,
+        "two_pass_GBps": two_pass / (ms * 1e-3) / 1e9,
     }
 
 
@@ -437,7 +449,7 @@ def main():
                                         (2, B.NORM_SUB, B.SCALE_L2, "ternary/sub/l2")]:
             log(f"timing {name}")
             r = time_codec(torch, B, g, gref, bits, norm, args.steps, args.warmup, seed, scale)
-            variants.append({"variant": name, "ms_per_step": round(r["ms_per_step"], 4),
+            variants.append({"variant": name, "path": r["path"], "ms_per_step": round(r["ms_per_step"], 4),
                              "fp32_in_GBps": round(r["fp32_in_GBps"], 1),
                              "two_pass_GBps": round(r["two_pass_GBps"], 1),
                              "kernel_ms": {k: round(v["ms"], 4) for k, v in r["kernels"].items()}})
@@ -496,8 +508,13 @@ def main():
         "config": {"workload": f"encode+decode microbenchmark: M={M} workers x d=2^{args.log2d} fp32, "
                                "g = ref + N(0,0.1)|ref|, ref ~ N(0,1), ternary codes, subtraction normalisation, seed 1",
                    "M": M, "d": d, "bits": 2, "norm": "sub"},
+        "path": head["path"],
+        "pct_hbm_peak_compulsory": round(100.0 * head["compulsory_GBps"] / HBM_PEAK_GBPS, 2),
+        "compulsory_algorithmic_GBps": round(head["compulsory_GBps"], 1),
         "pct_hbm_peak_two_pass": round(100.0 * head["two_pass_GBps"] / HBM_PEAK_GBPS, 2),
         "two_pass_algorithmic_GBps": round(head["two_pass_GBps"], 1),
+        "note_two_pass": "bytes a coder with two passes over g would move, divided by this run's time: a yardstick "
+                         "kept for comparison (the headline path reads g once, so it moves fewer)",
         "kernel_ms": {k: round(v["ms"], 4) for k, v in head["kernels"].items()},
         "kernel_GBps": {k: round(v["GBps"], 1) for k, v in head["kernels"].items()},
         "kernel_ms_min_median": {k: [v["min"], v["median"]] for k, v in head["kernels"].items()},

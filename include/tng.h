@@ -112,7 +112,10 @@ typedef struct {
 /* ceil(d * bits / 32); 0 if bits is not 2 or 4. */
 uint64_t tng_words_per_row(uint64_t d, uint32_t bits);
 
-/* Device scratch bytes tng_create needs for this configuration; 0 if the configuration is invalid. */
+/* Device scratch bytes tng_create needs for this configuration; 0 if the configuration is invalid.
+ * (For 2-bit codes with the largest-magnitude scale and TNG_NORM_NONE / TNG_NORM_SUB over 2^26 elements or
+ * more, d a multiple of 1024, this includes M * d / 2 bytes: tng_normalize_encode then reads g once and
+ * keeps the few elements that can code non-zero there between its two passes; same codes, bit for bit.) */
 size_t tng_workspace_bytes(const tng_config* cfg);
 
 /* Creates a context.  cfg: host.  workspace: device, 256-byte aligned, at least
