@@ -678,7 +678,7 @@ __global__ __launch_bounds__(kBlock) void absmax_select_kernel(GradRows g, const
     auto worker = [&](const float4 (&x)[L], int mm) {
       const uint32_t m = m0 + (uint32_t)mm;
       float amax = 0.f;
-      uint32_t base = 1;  // entry 0 is the header
+      uint32_t base = 1;  // word 0 of the slot is the count
 #pragma unroll
       for (int j = 0; j < L; ++j) {
         const float4 v = normalize4<NORM, RECIP>(x[j], rt[j], 0.f);
@@ -701,8 +701,9 @@ __global__ __launch_bounds__(kBlock) void absmax_select_kernel(GradRows g, const
       if (lane == 0) stage[wave][0] = base - 1;  // candidates found (more than kCandCap: the slot is not used)
       wave_lds_fence();
       // Words to write, the count included (8 bytes per lane, the last one whatever the staging area holds);
-      // of a slot that overflowed only the count.  (Rounding the piece up to whole 128-byte lines measured the
-      // same: what the slots cost is their bytes, about 0.15 ms per launch for 0.2 GB next to 4.8 GB of reads.)
+      // of a slot that overflowed only the count.  (The slots cost about 0.15 ms per launch -- 0.2 GB next to
+      // 4.8 GB of reads -- and pieces rounded up to whole 128-byte lines, 16-byte stores or a quarter fewer bytes
+      // all measured the same; half of it remains when the stores never leave the caches.)
       const bool fits = base <= (uint32_t)kSlotEntries;
       nover += fits ? 0u : 1u;
       const uint32_t used = fits ? base : 1u;
