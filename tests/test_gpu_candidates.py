@@ -11,7 +11,7 @@ import pytest
 import torch
 
 from oracle import tng_oracle as O
-from gpu_util import DEV, buffers, make_ctx, oracle_cfg, say, u32
+from gpu_util import DEV, buffers, make_ctx, oracle_cfg, oracle_step_threaded, say, u32
 from paper_1901_08227_amd import binding as B
 from paper_1901_08227_amd import synth
 
@@ -148,3 +148,30 @@ def test_same_codes_as_the_two_pass_coder_on_shorter_rows():
         assert torch.equal(a["codes"][m, :half // 16], b["codes"][m]), f"worker {m}"
     long_ctx.close()
     short_ctx.close()
+
+
+def test_whole_iteration_with_gradients_from_the_caller():
+    # tng_step on gradients handed in by the caller (no problem attached): its encode part takes the same path,
+    # the decode part updates the iterate and refreshes the reference in place; two iterations, the second from
+    # the state the first one left
+    M, d = 8, 1 << 23
+    g, gref, _ = _inputs(M, d, seed=41)
+    ctx = B.Context(d=d, M=M, bits=2, norm=B.NORM_SUB, ref_policy=B.REF_LAST_AVG, ref_period=2, seed=12, lr=0.05,
+                    problem=B.PROB_EXTERNAL, device=DEV)
+    cfg = oracle_cfg(ctx)
+    buf = buffers(ctx)
+    w = torch.randn(d, generator=torch.Generator(device=DEV).manual_seed(5), device=DEV)
+    gref = gref.clone()
+    for it in range(2):
+        say(f"candidates case whole iteration: it={it}")
+        gi = g if it == 0 else (g * 0.5 + torch.roll(g, 1, dims=0) * 0.5).contiguous()
+        w0, r0 = w.cpu().numpy(), gref.cpu().numpy()
+        ctx.step(it, w, gref, gi, buf["codes"], buf["scales"], buf["vbar"])
+        torch.cuda.synchronize()
+        w1, r1, codes, scales, vbar = oracle_step_threaded(cfg, it, w0, r0, gi.cpu().numpy())
+        assert np.array_equal(buf["scales"].cpu().numpy(), scales), "scales"
+        assert np.array_equal(u32(buf["codes"]), codes), "packed codes"
+        assert np.array_equal(buf["vbar"].cpu().numpy(), vbar), "decoded average"
+        assert np.array_equal(w.cpu().numpy(), w1), "iterate"
+        assert np.array_equal(gref.cpu().numpy(), r1), "reference"
+    ctx.close()
