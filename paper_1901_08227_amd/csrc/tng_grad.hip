@@ -905,27 +905,38 @@ __global__ __launch_bounds__(kCsrThreads) void csr_z_wide_kernel(const int32_t* 
 }
 
 // r[m][i] = (sigma(z_i) - y_i) / B with z_i = sum over the tiles of the partial dot products
-// zpart[m][t][i]: what the gradient pass multiplies every stored entry of row i by.
+// zpart[m][t][i]: what the gradient pass multiplies every stored entry of row i by.  A workgroup takes
+// kReduceRows rows of one worker; four groups of threads add a quarter of the partial sums each (four
+// accumulators per thread, fixed order), and the quarters are added in order.
+constexpr int kReduceRows = kBlock / 4;
 __global__ __launch_bounds__(kBlock) void csr_z_reduce_kernel(const float* __restrict__ zpart,
                                                               const float* const* __restrict__ ys,
                                                               const uint32_t* __restrict__ idx, float* __restrict__ r,
                                                               uint32_t batch, uint32_t ntiles, float inv_b) {
+  __shared__ float quarter_sum[3][kReduceRows];
   const uint32_t m = blockIdx.y;
-  const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
-  if (i >= batch) return;
+  const uint32_t lane_row = threadIdx.x % kReduceRows, quarter = threadIdx.x / kReduceRows;
+  const uint32_t i = min(blockIdx.x * kReduceRows + lane_row, batch - 1);  // clamped: every thread meets the barrier
+  const uint32_t per = (ntiles + 3) / 4;
+  const uint32_t t_begin = min(quarter * per, ntiles), t_end = min(t_begin + per, ntiles);
   const float* __restrict__ p = zpart + (uint64_t)m * ntiles * batch + i;
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-  uint32_t t = 0;
-  for (; t + 4 <= ntiles; t += 4) {
+  uint32_t t = t_begin;
+  for (; t + 4 <= t_end; t += 4) {
     a0 += p[(uint64_t)t * batch];
     a1 += p[(uint64_t)(t + 1) * batch];
     a2 += p[(uint64_t)(t + 2) * batch];
     a3 += p[(uint64_t)(t + 3) * batch];
   }
-  for (; t < ntiles; ++t) a0 += p[(uint64_t)t * batch];
-  const float z = (a0 + a1) + (a2 + a3);
-  const uint64_t o = (uint64_t)m * batch + i;
-  r[o] = logistic_residual(z, as_global(ys[m])[idx[o]]) * inv_b;
+  for (; t < t_end; ++t) a0 += p[(uint64_t)t * batch];
+  const float part = (a0 + a1) + (a2 + a3);
+  if (quarter > 0) quarter_sum[quarter - 1][lane_row] = part;
+  __syncthreads();
+  if (quarter == 0 && blockIdx.x * kReduceRows + lane_row < batch) {
+    const float z = ((part + quarter_sum[0][lane_row]) + quarter_sum[1][lane_row]) + quarter_sum[2][lane_row];
+    const uint64_t o = (uint64_t)m * batch + i;
+    r[o] = logistic_residual(z, as_global(ys[m])[idx[o]]) * inv_b;
+  }
 }
 
 // Gradient pass: one workgroup per (worker, tile); every minibatch row adds (r_i / B) val into the
@@ -1710,7 +1721,7 @@ hipError_t csr_grad_launches(const LogregData& p, uint64_t d, uint32_t M, uint32
     hipLaunchKernelGGL(csr_z_kernel<PAIRS>, dim3(M, ntiles), dim3(kCsrThreads), lds_w, s, p.col, p.val, rowbase, bounds, w,
                        zpart, d, batch, ntiles, shift);
   }
-  hipLaunchKernelGGL(csr_z_reduce_kernel, dim3((batch + kBlock - 1) / kBlock, M), dim3(kBlock), 0, s, zpart, p.y, idx,
+  hipLaunchKernelGGL(csr_z_reduce_kernel, dim3((batch + kReduceRows - 1) / kReduceRows, M), dim3(kBlock), 0, s, zpart, p.y, idx,
                      z, batch, nparts, inv_b);
   // The scale pass rides along when every tile is a full one and the write-out is the plain one.
   if (fuse != nullptr && fused_rows != nullptr && shift == kCsrTileShift && d % (1ull << kCsrTileShift) == 0 &&
