@@ -175,3 +175,32 @@ def test_whole_iteration_with_gradients_from_the_caller():
         assert np.array_equal(w.cpu().numpy(), w1), "iterate"
         assert np.array_equal(gref.cpu().numpy(), r1), "reference"
     ctx.close()
+
+
+@pytest.mark.parametrize("case", range(6))
+def test_seeded_shapes_and_distributions(case):
+    # worker counts, row lengths (whole tiles, 2^26 elements or a little more) and value distributions drawn from a
+    # seed: Gaussian, heavy-tailed (Cauchy-like), mostly exact zeros, one dominant element per row, blocks of
+    # constant magnitude
+    rng = np.random.default_rng(1000 + case)
+    M = int(rng.integers(2, 21))
+    tiles = -(-(1 << 26) // (M * 1024)) + int(rng.integers(0, 50))
+    d = tiles * 1024
+    gen = torch.Generator(device=DEV).manual_seed(2000 + case)
+    gref = torch.randn(d, generator=gen, device=DEV)
+    kind = case % 5
+    v = torch.randn((M, d), generator=gen, device=DEV)
+    if kind == 1:
+        v = v / (torch.randn((M, d), generator=gen, device=DEV).abs() + 1e-3)
+    elif kind == 2:
+        v = torch.where(torch.rand((M, d), generator=gen, device=DEV) < 0.02, v, torch.zeros_like(v))
+    elif kind == 3:
+        v = v * 1e-3
+        for m in range(M):
+            v[m, int(rng.integers(0, d))] = float(rng.choice([-1.0, 1.0])) * 50.0
+    elif kind == 4:
+        a = int(rng.integers(0, d // 2))
+        v[:, a:a + d // 3] = torch.sign(v[:, a:a + d // 3]) * 2.5
+    norm = B.NORM_SUB if case % 2 == 0 else B.NORM_NONE
+    g = (v + gref[None, :]).contiguous() if norm == B.NORM_SUB else v.contiguous()
+    _check(M, d, norm, g, gref, gref, int(rng.integers(0, 1000)), f"seeded {case} (kind {kind})", seed=int(rng.integers(0, 2 ** 40)))
