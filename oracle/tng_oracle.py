@@ -22,7 +22,7 @@ IEEE binary32, round-to-nearest-even, one rounding per written operation, no fus
 multiply-add, subnormals kept.  numpy float32 ufuncs do exactly that.  Gradients of the
 logistic model are the textbook definition evaluated in float64.
 
-Readings of the paper taken here (each also listed in the design notes):
+Readings of the paper taken here:
   - second line of the probability display is P(z=0) = 1 - |v_d|/R;
   - Algorithm 1 uses |g - g~| (not |g|) for the probabilities and sign(g - g~) for the sign;
   - the server adds the reference back after averaging (Eq. 1), which Algorithm 1 omits;
