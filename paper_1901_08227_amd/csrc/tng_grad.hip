@@ -1033,7 +1033,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_kernel(const int32_t* co
       store_stream(out4 + q, o);
       amax = fmaxf(amax, absmax4(fuse, o, r1[k], r2[k]));
     }
-    amax = wave_max(amax);
+    amax = wave_max_nonneg(amax);
     if (threadIdx.x % kWave == 0) red[threadIdx.x / kWave] = amax;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -1191,7 +1191,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_run_kernel(const int32_t
       store_stream(out4 + q, o);
       amax = fmaxf(amax, absmax4_t<NORM>(fuse, o, r1[k], r2[k]));
     }
-    amax = wave_max(amax);
+    amax = wave_max_nonneg(amax);
     if (threadIdx.x % kWave == 0) red[threadIdx.x / kWave] = amax;
     lds_barrier();  // the tile is clear again; red is complete
   };
@@ -1345,7 +1345,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_grad_workers_kernel(const int
       store_stream(out4 + q, o);
       amax = fmaxf(amax, absmax4_t<NORM>(fuse, o, r1[k], r2[k]));
     }
-    amax = wave_max(amax);
+    amax = wave_max_nonneg(amax);
     if (threadIdx.x % kWave == 0) red[cur][threadIdx.x / kWave] = amax;
     lds_barrier();  // the tile is clear again; red is complete
   };
@@ -1469,7 +1469,7 @@ __global__ __launch_bounds__(kBlock) void rosenbrock_vec_kernel(const float* __r
       const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
 #pragma unroll
       for (int k = 0; k < MC; ++k) {
-        const float v = wave_max(amax[k]);
+        const float v = wave_max_nonneg(amax[k]);
         if (lane == 0) red[wave][k] = v;
       }
       __syncthreads();
