@@ -628,7 +628,7 @@ constexpr uint32_t kSampleStride = 128;  // the sample: every 128th wavefront ti
 constexpr uint32_t kCandPosMask = 0x3FFu;  // low 10 bits of a candidate word: position within the tile
 
 template <int NORM, int MC>
-__global__ __launch_bounds__(kBlock) void absmax_select_kernel(GradRows g, const float4* __restrict__ ref4,
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) void absmax_select_kernel(GradRows g, const float4* __restrict__ ref4,
                                                                const float4* __restrict__ ref24, float* partials,
                                                                uint64_t nvec, uint32_t M, float eps,
                                                                const float* __restrict__ sample_max,
@@ -637,11 +637,23 @@ __global__ __launch_bounds__(kBlock) void absmax_select_kernel(GradRows g, const
                                                                uint32_t k1, uint32_t iter) {
   constexpr int L = kAbsmaxLoads;
   constexpr uint64_t kWaveTile = (uint64_t)kWave * L;
-  constexpr bool RECIP = kByReciprocal<NORM, MC>;
   static_assert(L == kLoadsPerLane, "the quantise pass reads the slots by the same tiles");
-  __shared__ __attribute__((aligned(16))) uint32_t stage[kWavesPerBlock][kWave * kAbsmaxLoads * 4 + 4];  // count + a whole tile
+  static_assert(NORM == kNormNone || NORM == kNormSub, "the coder that reads g once: no divisor reference");
+  // What a wavefront fetches per tile, in order: the reference, then the MC workers' parts, and nothing up to
+  // a multiple of three.  The items rotate through three register buffers: while item i is worked on, items
+  // i + 1 and i + 2 are on their way -- across the end of the tile as well (the next tile's reference and
+  // first worker are requested during this tile's last workers).  The reference of the tile lives in LDS,
+  // not in registers: three buffers then cost what two buffers and a reference did, and twice the bytes are
+  // in flight per wavefront.  (Measured 2 % faster than two buffers that drained at the end of every tile:
+  // the pass is bound neither by the depth of its prefetch nor by its arithmetic.)
+  constexpr int kItems = (MC + 1 + 2) / 3 * 3;
+  constexpr uint32_t kStageDump = kWave * kAbsmaxLoads * 4 + 4;  // count + a whole tile, then a word per lane for the rest
+  __shared__ __attribute__((aligned(16))) uint32_t stage[kWavesPerBlock][kStageDump + kWave];
+  __shared__ __attribute__((aligned(16))) float4 refs[kWavesPerBlock][L][kWave];
   __shared__ uint32_t over[kWavesPerBlock];
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  // the wavefront's number as a value the compiler knows to be the same in every lane: tile numbers, row and
+  // slot addresses are then scalar, and a lane's own part of every address is one 32-bit offset
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave)), lane = threadIdx.x % kWave;
   const uint32_t m0 = blockIdx.y * MC;
   const uint32_t count = min((uint32_t)MC, M - m0);
   uint32_t nover = 0;  // slots of this wavefront that overflowed
@@ -664,66 +676,109 @@ __global__ __launch_bounds__(kBlock) void absmax_select_kernel(GradRows g, const
     const float r_hat = sample_max[min(m0 + (uint32_t)mm, M - 1)];
     c1[mm] = r_hat >= 0x1p-90f ? (1.0f / r_hat) * (0x1p32f * (1.0f + 0x1p-20f)) : INFINITY;
   }
-  for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < ntiles;
-       tile += (uint64_t)gridDim.x * kWavesPerBlock) {
-    RefTile<NORM> rt[L];
-    uint64_t iv[L];
+  // one worker's part of the tile: its maximum, and its candidates into the slot
+  auto worker = [&](const float4 (&x)[L], int mm, uint64_t tile) {
+    const uint32_t m = m0 + (uint32_t)mm;
+    float amax = 0.f;
+    uint32_t base = 1;  // word 0 of the slot is the count
 #pragma unroll
     for (int j = 0; j < L; ++j) {
-      iv[j] = tile * kWaveTile + (uint64_t)j * kWave + lane;
-      rt[j].load(ref4, ref24, iv[j], eps);
-      if (RECIP) rt[j].reciprocals();
+      float4 v = x[j];
+      if (NORM == kNormSub) {
+        const float4 r = refs[wave][j][lane];
+        v = make_float4(x[j].x - r.x, x[j].y - r.y, x[j].z - r.z, x[j].w - r.w);
+      }
+      amax = max3_abs(v.z, v.w, max3_abs(v.x, v.y, amax));
+      const uint64_t iv = tile * kWaveTile + (uint64_t)(j * kWave + lane);
+      const U32x4 rnd = philox4x32_10((uint32_t)iv, m, iter, 0u, k0, k1);
+      const float vv[4] = {v.x, v.y, v.z, v.w};
+      const uint32_t rr[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool cand = (float)rr[c] < __builtin_fmaf(fabsf(vv[c]), c1[mm], 258.0f);
+        const uint64_t mask = __builtin_amdgcn_ballot_w64(cand);
+        const uint32_t pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                              __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        // Every lane writes, the others into a word of their own behind the tile's: a store under a condition
+        // would end the basic block at every element, and the sixteen elements of a lane could not overlap.
+        // (The staging area holds a whole tile: no test against the slot's capacity here.)
+        stage[wave][cand ? pos : kStageDump + (uint32_t)lane] =
+            (__float_as_uint(vv[c]) & ~kCandPosMask) | (uint32_t)(256 * j + c) | lane4;
+        base += (uint32_t)__builtin_popcountll(mask);
+      }
     }
-    // one worker's part of the tile: its maximum, and its candidates into the slot
-    auto worker = [&](const float4 (&x)[L], int mm) {
-      const uint32_t m = m0 + (uint32_t)mm;
-      float amax = 0.f;
-      uint32_t base = 1;  // word 0 of the slot is the count
+    mx[mm] = fmaxf(mx[mm], amax);
+    if (lane == 0) stage[wave][0] = base - 1;  // candidates found (more than kCandCap: the slot is not used)
+    wave_lds_fence();
+    // Words to write, the count included (8 bytes per lane, the last one whatever the staging area holds);
+    // of a slot that overflowed only the count.  (The slots cost about 0.15 ms per launch -- 0.2 GB next to
+    // 4.8 GB of reads -- and pieces rounded up to whole 128-byte lines, 16-byte stores or a quarter fewer bytes
+    // all measured the same; half of it remains when the stores never leave the caches.  The cache policy does
+    // matter: plain stores +0.03 ms, non-temporal ones +0.08 ms.)
+    const bool fits = base <= (uint32_t)kSlotEntries;
+    nover += fits ? 0u : 1u;
+    const uint32_t used = fits ? base : 1u;
+    if (2u * lane < used) {  // one store instruction covers the slot: 8 bytes per lane, device-coherent policy
+      const uint64_t two = *reinterpret_cast<const uint64_t*>(&stage[wave][2 * lane]);
+      uint64_t* slot = reinterpret_cast<uint64_t*>(slots + ((uint64_t)m * ntiles + tile) * kSlotEntries);
+      __hip_atomic_store(slot + (uint32_t)lane, two, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    wave_lds_fence();
+  };
+  // Every request is made whatever the tile (a load under a branch could not be counted by the waits that
+  // follow it): past the wavefront's last tile all lanes read the first float4 of this tile's part again.
+  auto request = [&](float4 (&b)[L], int item, uint64_t t, uint32_t keep) {
+    if (item == 0) {
+      if (NORM == kNormSub) {
 #pragma unroll
-      for (int j = 0; j < L; ++j) {
-        const float4 v = normalize4<NORM, RECIP>(x[j], rt[j], 0.f);
-        amax = max3_abs(v.z, v.w, max3_abs(v.x, v.y, amax));
-        const U32x4 rnd = philox4x32_10((uint32_t)iv[j], m, iter, 0u, k0, k1);
-        const float vv[4] = {v.x, v.y, v.z, v.w};
-        const uint32_t rr[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const bool cand = (float)rr[c] < __builtin_fmaf(fabsf(vv[c]), c1[mm], 258.0f);
-          const uint64_t mask = __builtin_amdgcn_ballot_w64(cand);
-          const uint32_t pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                                                __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-          // (the staging area holds a whole tile: no test against the slot's capacity here)
-          if (cand) stage[wave][pos] = (__float_as_uint(vv[c]) & ~kCandPosMask) | (uint32_t)(256 * j + c) | lane4;
-          base += (uint32_t)__builtin_popcountll(mask);
-        }
+        for (int j = 0; j < L; ++j) b[j] = load_stream(ref4 + t * kWaveTile + ((uint32_t)(j * kWave + lane) & keep));
       }
-      mx[mm] = fmaxf(mx[mm], amax);
-      if (lane == 0) stage[wave][0] = base - 1;  // candidates found (more than kCandCap: the slot is not used)
-      wave_lds_fence();
-      // Words to write, the count included (8 bytes per lane, the last one whatever the staging area holds);
-      // of a slot that overflowed only the count.  (The slots cost about 0.15 ms per launch -- 0.2 GB next to
-      // 4.8 GB of reads -- and pieces rounded up to whole 128-byte lines, 16-byte stores or a quarter fewer bytes
-      // all measured the same; half of it remains when the stores never leave the caches.)
-      const bool fits = base <= (uint32_t)kSlotEntries;
-      nover += fits ? 0u : 1u;
-      const uint32_t used = fits ? base : 1u;
-      if (2u * lane < used) {  // one store instruction covers the slot: 8 bytes per lane, device-coherent policy
-        const uint64_t two = *reinterpret_cast<const uint64_t*>(&stage[wave][2 * lane]);
-        uint64_t* dst = reinterpret_cast<uint64_t*>(slots + ((uint64_t)m * ntiles + tile) * kSlotEntries) + lane;
-        __hip_atomic_store(dst, two, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      wave_lds_fence();
-    };
-    float4 xa[L], xb[L];
-    auto row = [&](int mm) { return g.row(min(m0 + (uint32_t)mm, M - 1)); };
-    absmax_load<NORM, true>(row(0), iv, nvec, xa);
+    } else if (item <= MC) {
+      const v4f_u_t* row = g.row(min(m0 + (uint32_t)(item - 1), M - 1));
 #pragma unroll
-    for (int mm = 0; mm < MC; mm += 2) {
-      if (mm + 1 < MC) absmax_load<NORM, true>(row(mm + 1), iv, nvec, xb);
-      if ((uint32_t)mm < count) worker(xa, mm);
-      if (mm + 1 < MC) {
-        if (mm + 2 < MC) absmax_load<NORM, true>(row(mm + 2), iv, nvec, xa);
-        if ((uint32_t)(mm + 1) < count) worker(xb, mm + 1);
+      for (int j = 0; j < L; ++j) b[j] = load_row_stream(row + t * kWaveTile + ((uint32_t)(j * kWave + lane) & keep));
+    }
+  };
+  auto work = [&](const float4 (&b)[L], int item, uint64_t tile) {
+    if (item == 0) {
+      if (NORM == kNormSub) {
+#pragma unroll
+        for (int j = 0; j < L; ++j) refs[wave][j][lane] = b[j];
+        wave_lds_fence();
+      }
+    } else if (item <= MC) {
+      if ((uint32_t)(item - 1) < count) worker(b, item - 1, tile);
+    }
+  };
+  const uint64_t stride = (uint64_t)gridDim.x * kWavesPerBlock;
+  uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (tile < ntiles) {
+    float4 b0[L], b1[L], b2[L];
+    request(b0, 0, tile, ~0u);
+    request(b1, 1, tile, ~0u);
+    for (; tile < ntiles; tile += stride) {
+      const bool more = tile + stride < ntiles;
+      const uint64_t t_next = more ? tile + stride : tile;
+      const uint32_t keep_next = more ? ~0u : 0u;
+      // step i: request item i + 2 into the buffer that item i - 1 has just left, then work on item i
+      auto step = [&](auto I, float4 (&into)[L], const float4 (&from)[L]) {
+        constexpr int i = decltype(I)::value;
+        constexpr bool wraps = i + 2 >= kItems;
+        request(into, wraps ? i + 2 - kItems : i + 2, wraps ? t_next : tile, wraps ? keep_next : ~0u);
+        work(from, i, tile);
+      };
+      step(std::integral_constant<int, 0>{}, b2, b0);
+      step(std::integral_constant<int, 1>{}, b0, b1);
+      step(std::integral_constant<int, 2>{}, b1, b2);
+      if constexpr (kItems > 3) {
+        step(std::integral_constant<int, 3>{}, b2, b0);
+        step(std::integral_constant<int, 4>{}, b0, b1);
+        step(std::integral_constant<int, 5>{}, b1, b2);
+      }
+      if constexpr (kItems > 6) {
+        step(std::integral_constant<int, 6>{}, b2, b0);
+        step(std::integral_constant<int, 7>{}, b0, b1);
+        step(std::integral_constant<int, 8>{}, b1, b2);
       }
     }
   }
