@@ -317,12 +317,22 @@ __global__ __launch_bounds__(kSplitThreads) void logreg_dense_grad_split_kernel(
 // A row of up to 256 KiB fits neither store alone: each of the 512 threads (one workgroup per compute
 // unit, so 256 registers per thread) parks NL = min(NV, 16) float4 of the row in LDS (128 KiB per
 // workgroup; a thread reads back only what it wrote) and holds the other NV - NL in registers, next to its
-// NV float4 of partial gradient.  The register half is requested first and stays in flight while the LDS
-// half goes through a few transit registers at a time.
+// NV float4 of partial gradient.  The LDS half is loaded from memory straight into LDS, so that the whole
+// row is requested at once.
 // The workgroups of a worker split its minibatch rows; their partial gradients go to scratch
 // parts[m][s][d] and logreg_dense_parts_kernel adds them in workgroup order.
 constexpr int kRowsThreads = 512;
 constexpr int kRowsWaves = kRowsThreads / kWave;
+// 16 bytes per lane from memory straight into LDS: lane l of the wavefront writes the l-th 16 bytes behind
+// dst, which is the same for the whole wavefront; counted by vmcnt like any load.  Non-temporal (policy bit
+// 2): the row is read once.  (The builtin exists in the device pass only.)
+constexpr int kRowsStagger = 55;  // s_sleep units of 64 clocks: about 1.7 microseconds
+typedef __attribute__((address_space(3))) void* LdsPtr;
+__device__ __forceinline__ void load16_to_lds(GlobalPtr<v4f_t> src, LdsPtr dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds(src, dst, 16, 0, 2);
+#endif
+}
 constexpr int kRowsLds = 16;  // float4 per thread kept in LDS
 template <int NV, bool FULL>
 __global__ __launch_bounds__(kRowsThreads) void logreg_dense_rows_kernel(const float* const* __restrict__ Xs,
@@ -335,11 +345,15 @@ __global__ __launch_bounds__(kRowsThreads) void logreg_dense_rows_kernel(const f
                                                                          uint32_t iter) {
   constexpr int NL = NV < kRowsLds ? NV : kRowsLds;
   constexpr int NR = NV - NL;
-  constexpr int TR = 4;  // transit registers (float4) of the LDS half
-  static_assert(NL % TR == 0 && NR % TR == 0, "both halves are worked through in whole batches");
+  constexpr int TR = 4;                // float4 of the LDS half read back at a time when the row is added
+  constexpr int TW = NV < 8 ? NV : 8;  // float4 of w on their way at a time
+  static_assert(NL % TR == 0 && NL % TW == 0 && NR % TW == 0, "both halves are worked through in whole batches");
+  constexpr int kWaitVmem = 0x0F70;         // s_waitcnt vmcnt(0)
+  constexpr int kWaitLds = 0xC07F;          // s_waitcnt lgkmcnt(0)
   extern __shared__ float4 rowl[];  // [NL][kRowsThreads]
   __shared__ float red[2][kRowsWaves];
   const uint32_t m = blockIdx.y, s = blockIdx.x, S = gridDim.x, t = threadIdx.x;
+  const uint32_t wave_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)(t / kWave)) * kWave;  // a scalar
   const uint32_t nvec = (uint32_t)(d / 4);
   const GlobalPtr<float> X = as_global(Xs[m]);
   const GlobalPtr<float> y = as_global(ys[m]);
@@ -363,45 +377,70 @@ __global__ __launch_bounds__(kRowsThreads) void logreg_dense_rows_kernel(const f
   float4 acc[NV];
 #pragma unroll
   for (int k = 0; k < NV; ++k) acc[k] = zero4;
+  // A row is fetched (memory busy, arithmetic idle) and then worked on (the reverse), and workgroups that start
+  // together stay in step: every compute unit fetches at once and the memory system idles while all of them
+  // compute.  A quarter of the workgroups therefore starts at once and the others 1.7, 3.4 and 5.1 microseconds
+  // later (about the length of the arithmetic on a row), so that the fetches of some fall into the arithmetic of
+  // the others.  Measured at d = 2^16, M = 16, B = 256: iteration 0.236 -> 0.224 ms, this kernel 200
+  // microseconds (with twice the delay 0.230 ms; with eight steps of 0.7 microseconds 204 microseconds).
+  for (uint32_t q = (blockIdx.x + blockIdx.y * gridDim.x) % 4u; q > 0; --q) __builtin_amdgcn_s_sleep(kRowsStagger);
   uint32_t parity = 0;
   for (uint32_t i = s; i < batch; i += S, parity ^= 1u) {
     const uint32_t row = minibatch_row(k0, k1, iter, m, i, n);
     if (t == 0) idx[(uint64_t)m * batch + i] = row;
     const GlobalPtr<float> x = X + (uint64_t)row * d;
+    // Requests of a row, in the order in which they come back: the first batch of w (out of the caches), the
+    // register half, then the LDS half, which goes from memory straight into LDS (16 bytes per lane, lane l of
+    // a wavefront to the l-th float4 behind the wavefront's address: each thread's own slot) -- so the whole
+    // row, 256 KiB at d = 2^16, is in flight at once and no register carries the LDS half.
+    float4 wa[TW];
+    {
+      const uint32_t tt = opaque_t();
+#pragma unroll
+      for (int k = 0; k < TW; ++k) wa[k] = w4[column_of(tt, k)];
+    }
     float4 xr[NR > 0 ? NR : 1];
     {
       const uint32_t tt = opaque_t();
 #pragma unroll
       for (int k = 0; k < NR; ++k) xr[k] = load4_stream(x, column_of(tt, NL + k));
     }
-    float z0 = 0.f, z1 = 0.f, z2 = 0.f, z3 = 0.f;
-#pragma unroll
-    for (int k0b = 0; k0b < NL; k0b += TR) {
-      float4 xa[TR], wa[TR];
+    {
       const uint32_t tt = opaque_t();
 #pragma unroll
-      for (int k = 0; k < TR; ++k) xa[k] = load4_stream(x, column_of(tt, k0b + k));
+      for (int k = 0; k < NL; ++k)
+        load16_to_lds(reinterpret_cast<GlobalPtr<v4f_t>>(x) + column_of(tt, k),
+                      (LdsPtr)(rowl + k * kRowsThreads + wave_first));
+    }
+    __builtin_amdgcn_s_waitcnt(kWaitVmem);  // everything requested above has arrived, the LDS half in LDS
+    asm volatile("" ::: "memory");
+    float z0 = 0.f, z1 = 0.f, z2 = 0.f, z3 = 0.f;
 #pragma unroll
-      for (int k = 0; k < TR; ++k) wa[k] = w4[column_of(tt, k0b + k)];
+    for (int k0b = 0; k0b < NL; k0b += TW) {
+      if (k0b > 0) {
+        const uint32_t tt = opaque_t();
 #pragma unroll
-      for (int k = 0; k < TR; ++k) {
-        const float4 xv = live(k0b + k) ? xa[k] : zero4;
+        for (int k = 0; k < TW; ++k) wa[k] = w4[column_of(tt, k0b + k)];
+      }
+      const uint32_t tt = opaque_t();
+#pragma unroll
+      for (int k = 0; k < TW; ++k) {
+        const float4 xl = rowl[(k0b + k) * kRowsThreads + tt];
+        const float4 xv = live(k0b + k) ? xl : zero4;
         z0 = __builtin_fmaf(xv.x, wa[k].x, z0);
         z1 = __builtin_fmaf(xv.y, wa[k].y, z1);
         z2 = __builtin_fmaf(xv.z, wa[k].z, z2);
         z3 = __builtin_fmaf(xv.w, wa[k].w, z3);
-        rowl[(k0b + k) * kRowsThreads + t] = xv;
       }
       asm volatile("" ::: "memory");  // keeps the next batch's loads behind this batch's use: registers are the scarce thing here
     }
 #pragma unroll
-    for (int k0b = 0; k0b < NR; k0b += TR) {
-      float4 wa[TR];
+    for (int k0b = 0; k0b < NR; k0b += TW) {
       const uint32_t tt = opaque_t();
 #pragma unroll
-      for (int k = 0; k < TR; ++k) wa[k] = w4[column_of(tt, NL + k0b + k)];
+      for (int k = 0; k < TW; ++k) wa[k] = w4[column_of(tt, NL + k0b + k)];
 #pragma unroll
-      for (int k = 0; k < TR; ++k) {
+      for (int k = 0; k < TW; ++k) {
         if (!live(NL + k0b + k)) xr[k0b + k] = zero4;
         z0 = __builtin_fmaf(xr[k0b + k].x, wa[k].x, z0);
         z1 = __builtin_fmaf(xr[k0b + k].y, wa[k].y, z1);
@@ -430,7 +469,8 @@ __global__ __launch_bounds__(kRowsThreads) void logreg_dense_rows_kernel(const f
       const uint32_t tt = opaque_t();
 #pragma unroll
       for (int k = k0b; k < k0b + TR; ++k) {
-        const float4 xv = rowl[k * kRowsThreads + tt];
+        const float4 xl = rowl[k * kRowsThreads + tt];
+        const float4 xv = live(k) ? xl : zero4;
         acc[k].x = __builtin_fmaf(r, xv.x, acc[k].x);
         acc[k].y = __builtin_fmaf(r, xv.y, acc[k].y);
         acc[k].z = __builtin_fmaf(r, xv.z, acc[k].z);
@@ -438,6 +478,8 @@ __global__ __launch_bounds__(kRowsThreads) void logreg_dense_rows_kernel(const f
       }
       asm volatile("" ::: "memory");
     }
+    __builtin_amdgcn_s_waitcnt(kWaitLds);  // this row's LDS reads are done before the next row's loads write there
+    asm volatile("" ::: "memory");
   }
   float4* __restrict__ out = reinterpret_cast<float4*>(parts + ((uint64_t)m * S + s) * d);
 #pragma unroll
