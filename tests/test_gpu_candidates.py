@@ -85,7 +85,10 @@ def test_ordinary_data(norm):
 
 
 @pytest.mark.parametrize("M,d,norm", [(9, 1 << 23, B.NORM_SUB), (3, 1 << 25, B.NORM_SUB), (64, 1 << 20, B.NORM_SUB),
-                                      (5, (1 << 24) + 1024 * 7, B.NORM_NONE)])
+                                      (5, (1 << 24) + 1024 * 7, B.NORM_NONE),
+                                      # one and two workers per workgroup: the scale pass's schedule has idle items then
+                                      (1, 1 << 26, B.NORM_SUB), (2, (1 << 25) + 1024 * 3, B.NORM_NONE),
+                                      (4, 1 << 24, B.NORM_SUB)])
 def test_worker_counts_and_row_lengths(M, d, norm):
     g, gref, gref2 = _inputs(M, d, seed=M)
     _check(M, d, norm, g, gref, gref2, 1, "workers and lengths")
