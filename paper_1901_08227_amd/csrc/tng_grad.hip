@@ -1562,8 +1562,8 @@ hipError_t launch_logreg_dense_grad(const LogregData& p, uint64_t d, uint32_t M,
                          reinterpret_cast<const void*>(logreg_dense_rows_kernel<8, true>),
                          reinterpret_cast<const void*>(logreg_dense_rows_kernel<16, false>),
                          reinterpret_cast<const void*>(logreg_dense_rows_kernel<16, true>),
-                         reinterpret_cast<const void*>(logreg_dense_rows_kernel<32, false>),
-                         reinterpret_cast<const void*>(logreg_dense_rows_kernel<32, true>)};
+                         reinterpret_cast<const void*>(logreg_dense_rows_kernel<32, true>),  // 32 float4 per thread:
+                         reinterpret_cast<const void*>(logreg_dense_rows_kernel<32, true>)};  // d = 2^16 only, always full
     {  // 128 KiB of dynamic LDS: raised once per device
       static std::mutex attr_mutex;
       static bool attr_done[64] = {};
