@@ -34,11 +34,22 @@ __global__ __launch_bounds__(kBlock) void copy_f32_kernel(float* __restrict__ ds
   for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
+// Four float4 per thread in flight and one trip per workgroup wherever the grid allows: the shape that
+// measured fastest for a plain copy (1 GiB: 6.4 TB/s on read + written bytes, against 5.4 with one float4 per
+// thread and 16384 workgroups striding; streaming loads and stores in both).
+constexpr int kCopyPerThread = 4;
 __global__ __launch_bounds__(kBlock) void copy_f32x4_kernel(float4* __restrict__ dst,
                                                             const float4* __restrict__ src, uint64_t n) {
-  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride)
-    store_stream(dst + i, load_stream(src + i));
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock * kCopyPerThread;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock * kCopyPerThread + threadIdx.x; i < n; i += stride) {
+    float4 x[kCopyPerThread];
+#pragma unroll
+    for (int u = 0; u < kCopyPerThread; ++u)
+      if (i + (uint64_t)u * kBlock < n) x[u] = load_stream(src + i + (uint64_t)u * kBlock);
+#pragma unroll
+    for (int u = 0; u < kCopyPerThread; ++u)
+      if (i + (uint64_t)u * kBlock < n) store_stream(dst + i + (uint64_t)u * kBlock, x[u]);
+  }
 }
 
 // Window-average reference (section "Reference Vectors"): mean of the last `window` decoded
@@ -1764,8 +1775,8 @@ hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t 
 hipError_t launch_copy_f32(float* dst, const float* src, uint64_t n, hipStream_t s) {
   if (n == 0) return hipSuccess;
   if (vec_ok(n, dst, src, nullptr)) {
-    const uint32_t gx = div_up_u32(n / 4, kBlock);
-    hipLaunchKernelGGL(copy_f32x4_kernel, dim3(gx < 16384u ? gx : 16384u), dim3(kBlock), 0, s,
+    const uint32_t gx = div_up_u32(n / 4, (uint64_t)kBlock * kCopyPerThread);
+    hipLaunchKernelGGL(copy_f32x4_kernel, dim3(gx < kMaxGridX ? gx : kMaxGridX), dim3(kBlock), 0, s,
                        reinterpret_cast<float4*>(dst), reinterpret_cast<const float4*>(src), n / 4);
   } else {
     const uint32_t gx = div_up_u32(n, kBlock);
