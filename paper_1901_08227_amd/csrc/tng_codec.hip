@@ -620,14 +620,14 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
 // R^ <= R at hand: fl(1 / R^) >= fl(1 / R) (the correctly rounded quotient is monotone) and
 // fl(|v| x) is monotone in x, so  u >= fl(|v| fl(1 / R^))  implies  u >= fl(|v| fl(1 / R)):  level 0
 // whatever R turns out to be.  The elements that fail this test -- the candidates -- are kept in a slot per
-// worker and wavefront tile, one 32-bit word each: sign, exponent and the upper 13 bits of the significand
-// of the normalised value, and in place of the lower 10 bits the position within the tile.  R^ is the
-// maximum over a sample of the row taken beforehand (one tile in kSampleStride).  The quantise pass then
-// reads the slots instead of g: the word brackets |v| between two numbers 2^-13 apart (relatively), the
-// level is monotone in |v|, so where both ends give the same level (the same draw, the same arithmetic as
-// quantize_code, the real R) that is the level; the few elements where they differ (the draw falls
-// between the two thresholds: one candidate in ten thousand) are fetched from g and coded from the value
-// itself.  Everything else is cleared, and the words are packed.  A slot that overflowed (a tile with more
+// worker and wavefront tile, one 32-bit word each: the sign of the normalised value, the position within the
+// tile in the low 10 bits, and in between tau = |v| / u -- the scale up to which the element codes non-zero --
+// to 13 bits of its significand.  R^ is the maximum over a sample of the row taken beforehand (one tile in
+// kSampleStride).  The quantise pass then reads the slots instead of g and compares the row's scale with
+// the entry: the level [u < fl(|v| fl(1 / R))] is 1 for every R below the bracket that the entry gives for tau
+// and 0 for every R above it (thresholds widened by what the roundings can move); the few elements whose
+// bracket contains R (three candidates in ten thousand) are fetched from g and coded from the value and its
+// draw.  Everything else is cleared, and the words are packed.  A slot that overflowed (a tile with more
 // than kCandCap candidates) sends its tile through the ordinary path.  The codes are those of the two-pass
 // coder bit for bit; what changes is that g is read once: 4 + 4/M bytes per element instead of 8 + 8/M.
 // Used for 2-bit codes with the largest-magnitude scale when every wavefront tile is a full one
@@ -658,8 +658,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
   // in flight per wavefront.  (Measured 2 % faster than two buffers that drained at the end of every tile:
   // the pass is bound neither by the depth of its prefetch nor by its arithmetic.)
   constexpr int kItems = (MC + 1 + 2) / 3 * 3;
-  constexpr uint32_t kStageDump = kWave * kAbsmaxLoads * 4 + 4;  // count + a whole tile, then a word per lane for the rest
+  // staging per wavefront: the count and up to kCandCap candidates (value word and draw), one word that takes
+  // everything beyond the capacity, then a word per lane for the elements that are no candidates
+  constexpr uint32_t kStageSink = kSlotEntries, kStageDump = kSlotEntries + 2;
   __shared__ __attribute__((aligned(16))) uint32_t stage[kWavesPerBlock][kStageDump + kWave];
+  __shared__ __attribute__((aligned(16))) uint32_t draws[kWavesPerBlock][kStageDump + kWave];
   __shared__ __attribute__((aligned(16))) float4 refs[kWavesPerBlock][L][kWave];
   __shared__ uint32_t over[kWavesPerBlock];
   // the wavefront's number as a value the compiler knows to be the same in every lane: tile numbers, row and
@@ -710,11 +713,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
         const uint64_t mask = __builtin_amdgcn_ballot_w64(cand);
         const uint32_t pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                                               __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-        // Every lane writes, the others into a word of their own behind the tile's: a store under a condition
-        // would end the basic block at every element, and the sixteen elements of a lane could not overlap.
-        // (The staging area holds a whole tile: no test against the slot's capacity here.)
-        stage[wave][cand ? pos : kStageDump + (uint32_t)lane] =
-            (__float_as_uint(vv[c]) & ~kCandPosMask) | (uint32_t)(256 * j + c) | lane4;
+        // Every lane writes, the others into a word of their own behind the candidates': a store under a
+        // condition would end the basic block at every element, and the sixteen elements of a lane could not
+        // overlap.  Candidates beyond the slot's capacity (the slot is then not used) share one word.
+        const uint32_t at = cand ? min(pos, kStageSink) : kStageDump + (uint32_t)lane;
+        stage[wave][at] = (__float_as_uint(vv[c]) & ~kCandPosMask) | (uint32_t)(256 * j + c) | lane4;
+        draws[wave][at] = rr[c];
         base += (uint32_t)__builtin_popcountll(mask);
       }
     }
@@ -730,7 +734,19 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
     nover += fits ? 0u : 1u;
     const uint32_t used = fits ? base : 1u;
     if (2u * lane < used) {  // one store instruction covers the slot: 8 bytes per lane, device-coherent policy
-      const uint64_t two = *reinterpret_cast<const uint64_t*>(&stage[wave][2 * lane]);
+      // What goes into the slot for a candidate is not v but tau = |v| / u (u its 24-bit draw), the scale up
+      // to which it codes non-zero, to 13 bits of the significand: the quantise pass then compares the row's
+      // scale with tau and needs neither the draw nor the value.  The reciprocal is taken here, for the two
+      // candidates of the lane, not for every element of the tile.  u = 0 gives an infinite tau (or none, for
+      // v = 0), which the quantise pass takes as "look at the value".
+      const uint2 vw = *reinterpret_cast<const uint2*>(&stage[wave][2 * lane]);
+      const uint2 dw = *reinterpret_cast<const uint2*>(&draws[wave][2 * lane]);
+      auto entry = [](uint32_t value_word, uint32_t draw) {
+        const float tau = __uint_as_float(value_word & 0x7FFFFC00u) * (__builtin_amdgcn_rcpf((float)(draw >> 8)) * 0x1p24f);
+        return (__float_as_uint(tau) & 0x7FFFFC00u) | (value_word & 0x800003FFu);
+      };
+      const uint32_t e0 = lane == 0 ? vw.x : entry(vw.x, dw.x);  // word 0 of the slot is the count
+      const uint64_t two = ((uint64_t)entry(vw.y, dw.y) << 32) | e0;
       uint64_t* slot = reinterpret_cast<uint64_t*>(slots + ((uint64_t)m * ntiles + tile) * kSlotEntries);
       __hip_atomic_store(slot + (uint32_t)lane, two, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -863,20 +879,23 @@ __global__ __launch_bounds__(kBlock) void quantize_candidates_kernel(
       const float inv_r = R == 0.f ? 0.f : 1.0f / R;
       auto code_one = [&](uint32_t e) {
         const uint32_t pos = e & kCandPosMask;
-        const uint64_t coord = tile * (uint64_t)(kWave * L * 4) + pos;
-        const U32x4 rnd = philox4x32_10((uint32_t)(coord >> 2), m, iter, 0u, k0, k1);
-        const uint32_t sel = pos & 3u;
-        const uint32_t word = sel == 0u ? rnd.x : sel == 1u ? rnd.y : sel == 2u ? rnd.z : rnd.w;
-        // |v| lies between the word with its low bits cleared and the word with them set; quantize_code's
-        // level is [u < |v| inv_r], monotone in |v|
-        const float u = uniform24(word);
+        // The entry brackets tau = |v| / u: its significand was cut to 13 bits twice (the value's, then tau's own)
+        // and its arithmetic is good to 2^-22, so tau lies in [lo (1 - 2^-22), hi (1 + 2^-13 + 2^-21)].
+        // quantize_code's level [u < fl(|v| fl(1 / R))] is 1 for R <= tau (1 - 2^-21) and 0 for R >= tau (1 + 2^-21)
+        // (the two roundings move |v| / R by less than 2^-22 relatively, 1 / R > 2^126 included), so only a scale
+        // inside the widened bracket -- three candidates in ten thousand -- needs the value and the draw.
         const float lo = __uint_as_float(e & 0x7FFFFC00u), hi = __uint_as_float((e & 0x7FFFFC00u) | kCandPosMask);
+        const bool bounded = (e & 0x7F800000u) != 0x7F800000u;  // u = 0: tau is infinite or no number
         uint32_t code;
-        if (u < lo * inv_r) {
+        if (bounded && R <= lo * (1.0f - 0x1p-19f)) {
           code = 1u | ((e >> 31) << 1);
-        } else if (!(u < hi * inv_r)) {
+        } else if (R >= hi * (1.0f + 0x1p-12f)) {  // (false where tau is not bounded)
           code = 0u;
-        } else {  // the draw falls between the two thresholds: from the value itself
+        } else {
+          const uint64_t coord = tile * (uint64_t)(kWave * L * 4) + pos;
+          const U32x4 rnd = philox4x32_10((uint32_t)(coord >> 2), m, iter, 0u, k0, k1);
+          const uint32_t sel = pos & 3u;
+          const uint32_t word = sel == 0u ? rnd.x : sel == 1u ? rnd.y : sel == 2u ? rnd.z : rnd.w;
           float r1 = 0.f;
           if (NORM == kNormSub) r1 = reinterpret_cast<const float*>(ref4)[coord];
           code = quantize_code<2>(normalize_w<NORM>(g.base[(uint64_t)m * g.pitch + coord], r1, 1.f, 0.f), inv_r, word);

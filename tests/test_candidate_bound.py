@@ -4,11 +4,13 @@ Compression": P(z = 1) = |v| / R, coded as [u < fl(|v| fl(1 / R))] with u on the
 The scale pass decides, before R is known, which elements can still code non-zero, against a lower bound
 R^ <= R, with the three-operation test  float(word) < fma(|v|, c1, 258),
 c1 = fl(fl(1 / R^) (2^32 + 2^12)); everything that fails it is coded 0 without being looked at again.  The
-quantise pass sees a kept element only as a bracket [lo, hi] around |v| (the low 10 bits of the binary32
-pattern cleared / set) and takes the level where both ends agree.  Both steps are only right if
+quantise pass sees a kept element only as a bracket [lo, hi] around tau = |v| / u, the scale up to which the
+element codes non-zero (13 bits of the value's significand, a reciprocal good to one unit in the last place,
+13 bits of the quotient's significand), and decides from the row's scale alone: level 1 for
+R <= lo (1 - 2^-19), level 0 for R >= hi (1 + 2^-12), the value itself in between.  Both steps are only right if
 
   (1) an element that fails the test has level 0 for every R >= R^, and
-  (2) the level at lo is never above, and the level at hi never below, the level at |v|.
+  (2) the level is 1 at every scale below the bracket's lower threshold and 0 at every scale above the upper one.
 
 Held here on the host in binary32 arithmetic (numpy's correctly rounded operations; the fused multiply-add
 through exact rational arithmetic), on random operands and on draws placed right at the thresholds.
@@ -119,24 +121,41 @@ def test_zeros_tiny_bounds_and_the_ends_of_the_draw():
     assert keep[3] and keep[4] and keep[6] and keep[7]   # |v| = R^: level 1 for every draw (u < 1)
 
 
+def tau_entry(absv, word, rcp_ulps):
+    """The slot entry's bracket as the scale pass forms it; rcp_ulps moves the reciprocal by that many units in
+    the last place (the hardware's is good to one)."""
+    v13 = (absv.view(np.uint32) & np.uint32(0x7FFFFC00)).view(F32)
+    k = (word >> np.uint32(8)).astype(F32)
+    with np.errstate(divide="ignore", over="ignore", invalid="ignore"):
+        rc = (F32(1.0) / k).astype(F32)
+        for _ in range(abs(rcp_ulps)):
+            rc = np.nextafter(rc, F32(np.inf) if rcp_ulps > 0 else F32(0.0)).astype(F32)
+        tau = (v13 * (rc * F32(2.0 ** 24)).astype(F32)).astype(F32)
+    lo_bits = tau.view(np.uint32) & np.uint32(0x7FFFFC00)
+    return lo_bits.view(F32), (lo_bits | np.uint32(0x3FF)).view(F32), (lo_bits & np.uint32(0x7F800000)) != np.uint32(0x7F800000)
+
+
 def test_the_bracket_of_a_kept_element_decides_from_the_safe_side():
     rng = np.random.default_rng(23)
-    n = 2_000_000
-    absv, R, _ = operands(rng, n, 4)
-    bits = absv.view(np.uint32)
-    lo = (bits & np.uint32(0x7FFFFC00)).view(F32)
-    hi = ((bits & np.uint32(0x7FFFFC00)) | np.uint32(0x3FF)).view(F32)
-    assert np.all(lo <= absv) and np.all(absv <= hi)
-    inv_r = (F32(1.0) / R).astype(F32)
-    # draws right at the three thresholds
-    for which in (lo, absv, hi):
-        t = (which * inv_r).astype(np.float64) * 2.0 ** 24
-        ugrid = np.clip(np.floor(t) + rng.integers(-2, 3, n), 0, 2 ** 24 - 1)
-        u = (ugrid * 2.0 ** -24).astype(F32)
-        at_lo, at_v, at_hi = u < lo * inv_r, u < absv * inv_r, u < hi * inv_r
-        assert not np.any(at_lo & ~at_v), "level 1 at the lower end but not at the value"
-        assert not np.any(at_v & ~at_hi), "level 1 at the value but not at the upper end"
-    # how often the two ends disagree for an ordinary draw: the cases that go back to the value itself
-    u = (rng.integers(0, 2 ** 24, n) * 2.0 ** -24).astype(F32)
-    undecided = np.count_nonzero((u < hi * inv_r) & ~(u < lo * inv_r))
-    assert undecided <= 2e-4 * n
+    n = 1_000_000
+    c_lo, c_hi = F32(1.0 - 2.0 ** -19), F32(1.0 + 2.0 ** -12)
+    for spread in (1, 5):
+        absv, _, _ = operands(rng, n, spread)
+        for draws in ("any", "small"):
+            word = rng.integers(0, 2 ** 32, n, dtype=np.uint64)
+            if draws == "small":
+                word >>= rng.integers(8, 31, n).astype(np.uint64)  # small u: large tau, down to u = 0
+            word = word.astype(np.uint32)
+            for ulps in (-1, 0, 1):
+                lo, hi, bounded = tau_entry(absv, word, ulps)
+                with np.errstate(over="ignore", invalid="ignore"):
+                    r_one = (lo * c_lo).astype(F32)    # the largest scale decided as level 1
+                    r_zero = (hi * c_hi).astype(F32)   # the smallest scale decided as level 0
+                # scales below the smallest normal number never reach the coder (they are taken as 0)
+                ok1 = bounded & np.isfinite(r_one) & (r_one >= F32(2.0 ** -126))
+                assert np.all(level(word[ok1], absv[ok1], r_one[ok1])), "decided 1 where the level is 0"
+                ok0 = np.isfinite(r_zero) & (r_zero >= F32(2.0 ** -126))   # (an unbounded tau never compares >=)
+                assert not np.any(level(word[ok0], absv[ok0], r_zero[ok0])), "decided 0 where the level is 1"
+                # and between the thresholds lies only a sliver of the scales: what goes back to the value
+                both = ok1 & ok0 & (lo > 0)
+                assert np.all(r_zero[both] <= lo[both] * F32(1.0 + 2.0 ** -11))
