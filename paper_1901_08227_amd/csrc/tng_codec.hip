@@ -207,10 +207,9 @@ __device__ __forceinline__ void block_max_to_partials(float (&mx)[MC], uint32_t 
 
 // scales[m] = max over the nblocks partial maxima of worker m; a maximum below the smallest normal
 // number is taken as 0.  One workgroup per worker.
-__global__ __launch_bounds__(kBlock) void absmax_finish_kernel(const float* __restrict__ partials, uint32_t nblocks,
-                                                               uint32_t M, float* __restrict__ scales) {
+__device__ __forceinline__ void absmax_finish_worker(const float* __restrict__ partials, uint32_t nblocks, uint32_t M,
+                                                     float* __restrict__ scales, uint32_t m) {
   __shared__ float red[kWavesPerBlock];
-  const uint32_t m = blockIdx.x;
   float v = 0.f;
   for (uint32_t b = threadIdx.x; b < nblocks; b += kBlock) v = fmaxf(v, partials[(uint64_t)b * M + m]);
   v = wave_max(v);
@@ -221,6 +220,10 @@ __global__ __launch_bounds__(kBlock) void absmax_finish_kernel(const float* __re
     for (int k = 1; k < kWavesPerBlock; ++k) v = fmaxf(v, red[k]);
     scales[m] = v < FLT_MIN ? 0.f : v;
   }
+}
+__global__ __launch_bounds__(kBlock) void absmax_finish_kernel(const float* __restrict__ partials, uint32_t nblocks,
+                                                               uint32_t M, float* __restrict__ scales) {
+  absmax_finish_worker(partials, nblocks, M, scales, blockIdx.x);
 }
 
 // The M gradient rows as the vector kernels read them.  Row m starts m * pitch floats into the array;
@@ -819,10 +822,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
   }
 }
 
-// Whether the slots are worth using: at most one tile in fifty may have overflowed (such tiles go through a
-// plain, unpipelined form of the ordinary path).  use_slots[0] = 1 or 0; one workgroup.
-__global__ __launch_bounds__(kBlock) void candidate_vote_kernel(const uint32_t* __restrict__ overflowed, uint32_t n,
-                                                                uint64_t tiles_in_all, uint32_t* __restrict__ use_slots) {
+// The reduction of the scale pass's partial maxima (workgroups 0 .. M - 1, one per worker) and, in one more
+// workgroup, whether the slots are worth using: at most one tile in fifty may have overflowed (such tiles go
+// through a plain, unpipelined form of the ordinary path).  use_slots[0] = 1 or 0.
+__global__ __launch_bounds__(kBlock) void absmax_finish_vote_kernel(const float* __restrict__ partials, uint32_t nblocks,
+                                                                    uint32_t M, float* __restrict__ scales,
+                                                                    const uint32_t* __restrict__ overflowed, uint32_t n,
+                                                                    uint64_t tiles_in_all,
+                                                                    uint32_t* __restrict__ use_slots) {
+  if (blockIdx.x < M) {
+    absmax_finish_worker(partials, nblocks, M, scales, blockIdx.x);
+    return;
+  }
   __shared__ unsigned long long sum;
   if (threadIdx.x == 0) sum = 0ull;
   __syncthreads();
@@ -1615,10 +1626,9 @@ hipError_t absmax_candidates_dispatch(const CodecShape& c, uint32_t iter, const 
 #undef TNG_SELECT
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(absmax_finish_kernel, dim3(c.M), dim3(kBlock), 0, s, partials, nblocks, c.M, scales);
-  hipLaunchKernelGGL(candidate_vote_kernel, dim3(1), dim3(kBlock), 0, s, cs.overflowed,
-                     nblocks * ((c.M + (uint32_t)mc - 1) / (uint32_t)mc), (uint64_t)c.M * (nvec / (kWave * kAbsmaxLoads)),
-                     cs.use_slots);
+  hipLaunchKernelGGL(absmax_finish_vote_kernel, dim3(c.M + 1), dim3(kBlock), 0, s, partials, nblocks, c.M, scales,
+                     cs.overflowed, nblocks * ((c.M + (uint32_t)mc - 1) / (uint32_t)mc),
+                     (uint64_t)c.M * (nvec / (kWave * kAbsmaxLoads)), cs.use_slots);
   return hipGetLastError();
 }
 
