@@ -626,7 +626,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
 // worker and wavefront tile, one 32-bit word each: the sign of the normalised value, the position within the
 // tile in the low 10 bits, and in between tau = |v| / u -- the scale up to which the element codes non-zero --
 // to 13 bits of its significand.  R^ is the maximum over a sample of the row taken beforehand (one tile in
-// kSampleStride).  The quantise pass then reads the slots instead of g and compares the row's scale with
+// kSampleStride); a row whose sample says that its candidates will not fit the slots is left to the ordinary path.  The quantise pass then reads the slots instead of g and compares the row's scale with
 // the entry: the level [u < fl(|v| fl(1 / R))] is 1 for every R below the bracket that the entry gives for tau
 // and 0 for every R above it (thresholds widened by what the roundings can move); the few elements whose
 // bracket contains R (three candidates in ten thousand) are fetched from g and coded from the value and its
@@ -641,11 +641,100 @@ constexpr int kSlotEntries = 128;     // 32-bit words per slot: 512 bytes per wo
 constexpr uint32_t kSampleStride = 128;  // the sample: every 128th wavefront tile of a row
 constexpr uint32_t kCandPosMask = 0x3FFu;  // low 10 bits of a candidate word: position within the tile
 
+// The sample of a row taken before the scale pass: over every kSampleStride-th wavefront tile, the largest
+// |v| (the lower bound R^ of the row's scale) and the sum of |v|.  Their ratio, mean |v| / R^, is the share
+// of the row's elements that will be candidates -- P(u < |v| / R^) averaged over the elements -- so it tells
+// beforehand whether the slots can hold them.  One worker per workgroup row (blockIdx.y); partial results per
+// workgroup, reduced by sample_finish_kernel.
+constexpr float kDenseLimit = 0.10f;  // 1024 elements x 0.10 + two standard deviations fill a slot of kCandCap
+template <int NORM>
+__global__ __launch_bounds__(kBlock) void sample_stats_kernel(GradRows g, const float4* __restrict__ ref4,
+                                                              float* __restrict__ part_max,
+                                                              float* __restrict__ part_sum, uint64_t nvec, uint32_t M) {
+  constexpr int L = kAbsmaxLoads;
+  constexpr uint64_t kWaveTile = (uint64_t)kWave * L;
+  __shared__ float red[2][kWavesPerBlock];
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const uint32_t m = blockIdx.y;
+  const uint64_t ntiles = nvec / kWaveTile;  // whole tiles only
+  const v4f_u_t* row = g.row(m);
+  float amax = 0.f, asum = 0.f;
+  for (uint64_t tile = ((uint64_t)blockIdx.x * kWavesPerBlock + wave) * kSampleStride; tile < ntiles;
+       tile += (uint64_t)gridDim.x * kWavesPerBlock * kSampleStride) {
+    float4 x[L], r[L];
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+      const uint64_t i = tile * kWaveTile + (uint64_t)(j * kWave + lane);
+      x[j] = load_row_stream(row + i);
+      r[j] = NORM == kNormSub ? ref4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+      const float a0 = fabsf(x[j].x - r[j].x), a1 = fabsf(x[j].y - r[j].y);
+      const float a2 = fabsf(x[j].z - r[j].z), a3 = fabsf(x[j].w - r[j].w);
+      amax = fmaxf(fmaxf(amax, fmaxf(a0, a1)), fmaxf(a2, a3));
+      asum += (a0 + a1) + (a2 + a3);
+    }
+  }
+  amax = wave_max(amax);
+  asum = wave_sum(asum);
+  if (lane == 0) {
+    red[0][wave] = amax;
+    red[1][wave] = asum;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float mx = red[0][0], sm = red[1][0];
+#pragma unroll
+    for (int k = 1; k < kWavesPerBlock; ++k) {
+      mx = fmaxf(mx, red[0][k]);
+      sm += red[1][k];
+    }
+    part_max[(uint64_t)blockIdx.x * M + m] = mx;
+    part_sum[(uint64_t)blockIdx.x * M + m] = sm;
+  }
+}
+
+// sample_max[m] = R^ of worker m (0 when below the smallest normal number, as for a scale), and
+// select_ok[m] = 1 when the sample says that the row's candidates fit the slots, else 0: the scale pass then
+// takes that worker's part as an ordinary scale pass and the quantise pass takes its tiles through the
+// ordinary path, without the slots.  sampled = elements of a row in the sample.  One workgroup per worker.
+__global__ __launch_bounds__(kBlock) void sample_finish_kernel(const float* __restrict__ part_max,
+                                                               const float* __restrict__ part_sum, uint32_t nblocks,
+                                                               uint32_t M, float sampled, float* __restrict__ sample_max,
+                                                               uint32_t* __restrict__ select_ok) {
+  __shared__ float red[2][kWavesPerBlock];
+  const uint32_t m = blockIdx.x;
+  float mx = 0.f, sm = 0.f;
+  for (uint32_t b = threadIdx.x; b < nblocks; b += kBlock) {
+    mx = fmaxf(mx, part_max[(uint64_t)b * M + m]);
+    sm += part_sum[(uint64_t)b * M + m];
+  }
+  mx = wave_max(mx);
+  sm = wave_sum(sm);
+  if (threadIdx.x % kWave == 0) {
+    red[0][threadIdx.x / kWave] = mx;
+    red[1][threadIdx.x / kWave] = sm;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int k = 1; k < kWavesPerBlock; ++k) {
+      mx = fmaxf(mx, red[0][k]);
+      sm += red[1][k];
+    }
+    sample_max[m] = mx < FLT_MIN ? 0.f : mx;
+    // (a sum that is no number, or an infinite one, compares false: the slots are then not used)
+    select_ok[m] = sm <= kDenseLimit * sampled * mx ? 1u : 0u;
+  }
+}
+
 template <int NORM, int MC>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) void absmax_select_kernel(GradRows g, const float4* __restrict__ ref4,
                                                                const float4* __restrict__ ref24, float* partials,
                                                                uint64_t nvec, uint32_t M, float eps,
                                                                const float* __restrict__ sample_max,
+                                                               const uint32_t* __restrict__ select_ok,
                                                                uint32_t* __restrict__ slots,
                                                                uint32_t* __restrict__ overflowed, uint32_t k0,
                                                                uint32_t k1, uint32_t iter) {
@@ -688,15 +777,31 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
   // quantise pass codes a candidate exactly, so more is harmless.  Below 2^-90 no bound is claimed (c1 would
   // overflow): every non-zero element is a candidate.
   float c1[MC];
+  bool select[MC];  // the sample found the worker's row too dense for the slots: only its maximum is taken
 #pragma unroll
   for (int mm = 0; mm < MC; ++mm) {
     const float r_hat = sample_max[min(m0 + (uint32_t)mm, M - 1)];
     c1[mm] = r_hat >= 0x1p-90f ? (1.0f / r_hat) * (0x1p32f * (1.0f + 0x1p-20f)) : INFINITY;
+    select[mm] = select_ok[min(m0 + (uint32_t)mm, M - 1)] != 0u;
   }
   // one worker's part of the tile: its maximum, and its candidates into the slot
   auto worker = [&](const float4 (&x)[L], int mm, uint64_t tile) {
     const uint32_t m = m0 + (uint32_t)mm;
     float amax = 0.f;
+    if (!select[mm]) {  // (the same for the whole wavefront)
+#pragma unroll
+      for (int j = 0; j < L; ++j) {
+        float4 v = x[j];
+        if (NORM == kNormSub) {
+          const float4 r = refs[wave][j][lane];
+          v = make_float4(x[j].x - r.x, x[j].y - r.y, x[j].z - r.z, x[j].w - r.w);
+        }
+        amax = max3_abs(v.z, v.w, max3_abs(v.x, v.y, amax));
+      }
+      mx[mm] = fmaxf(mx[mm], amax);
+      nover += 1u;  // counts as a slot that is not used
+      return;
+    }
     uint32_t base = 1;  // word 0 of the slot is the count
 #pragma unroll
     for (int j = 0; j < L; ++j) {
@@ -851,7 +956,8 @@ template <int NORM, int MC>
 __global__ __launch_bounds__(kBlock) void quantize_candidates_kernel(
     GradRows g, const float4* __restrict__ ref4, const float4* __restrict__ ref24, const float* __restrict__ scales,
     const uint32_t* __restrict__ slots, uint32_t* __restrict__ codes, uint64_t nvec, uint64_t words, uint32_t M,
-    float eps, uint32_t k0, uint32_t k1, uint32_t iter, const uint32_t* __restrict__ use_slots) {
+    float eps, uint32_t k0, uint32_t k1, uint32_t iter, const uint32_t* __restrict__ use_slots,
+    const uint32_t* __restrict__ select_ok) {
   constexpr int L = kLoadsPerLane;
   constexpr int WPW = kWave * L * 4 * 2 / 32;  // 64 packed words per wavefront tile
   static_assert(WPW == kWave, "one word per lane");
@@ -883,7 +989,8 @@ __global__ __launch_bounds__(kBlock) void quantize_candidates_kernel(
     const int slot = mm;
     const float R = scales[m];
     const uint32_t* __restrict__ sl = slots + ((uint64_t)m * ntiles + tile) * kSlotEntries;
-    const uint32_t n = R == 0.f ? 0u : cnt[mm];
+    // (a worker whose row the sample found too dense has no slots: its tiles take the ordinary path)
+    const uint32_t n = R == 0.f ? 0u : select_ok[m] != 0u ? cnt[mm] : (uint32_t)kCandCap + 1u;
     if (n <= (uint32_t)kCandCap) {
       lds.b32[slot][wave][lane] = 0u;
       wave_lds_fence();
@@ -1570,13 +1677,15 @@ hipError_t absmax_vec_launch(const CodecShape& c, uint64_t dv, const float* g, c
 struct CandidateScratch {
   uint32_t* use_slots;
   float* sample_max;
+  uint32_t* select_ok;
   float* sample_partials;
+  float* sample_sums;
   uint32_t* overflowed;
   uint32_t* slots;
 };
 inline size_t round_up_256(size_t v) { return (v + 255) / 256 * 256; }
 inline size_t candidate_head_bytes(uint32_t M) {
-  return 256 + round_up_256((size_t)M * sizeof(float)) + 2 * round_up_256((size_t)kAbsmaxMaxBlocks * M * sizeof(float));
+  return 256 + 2 * round_up_256((size_t)M * sizeof(float)) + 3 * round_up_256((size_t)kAbsmaxMaxBlocks * M * sizeof(float));
 }
 inline CandidateScratch candidate_scratch(const CodecShape& c, void* scratch) {
   unsigned char* p = static_cast<unsigned char*>(scratch);
@@ -1585,7 +1694,11 @@ inline CandidateScratch candidate_scratch(const CodecShape& c, void* scratch) {
   p += 256;
   cs.sample_max = reinterpret_cast<float*>(p);
   p += round_up_256((size_t)c.M * sizeof(float));
+  cs.select_ok = reinterpret_cast<uint32_t*>(p);
+  p += round_up_256((size_t)c.M * sizeof(float));
   cs.sample_partials = reinterpret_cast<float*>(p);
+  p += round_up_256((size_t)kAbsmaxMaxBlocks * c.M * sizeof(float));
+  cs.sample_sums = reinterpret_cast<float*>(p);
   p += round_up_256((size_t)kAbsmaxMaxBlocks * c.M * sizeof(float));
   cs.overflowed = reinterpret_cast<uint32_t*>(p);
   p += round_up_256((size_t)kAbsmaxMaxBlocks * c.M * sizeof(float));
@@ -1599,24 +1712,26 @@ hipError_t absmax_candidates_dispatch(const CodecShape& c, uint32_t iter, const 
                                       hipStream_t s) {
   const uint64_t nvec = c.d / 4;
   const int mc = pick_workers_per_block(c.M, (nvec + kBlock * kAbsmaxLoads - 1) / (kBlock * kAbsmaxLoads), 0.3);
-  uint32_t nsample = 0, nblocks = 0;
+  uint32_t nblocks = 0;
   hipError_t e;
-  // the sample: every kSampleStride-th wavefront tile of every row, workers in the same groups
-  switch (mc) {
-    case 8: e = absmax_vec_launch<NORM, 8>(c, c.d, g, gref, gref2, cs.sample_partials, &nsample, s, kSampleStride); break;
-    case 4: e = absmax_vec_launch<NORM, 4>(c, c.d, g, gref, gref2, cs.sample_partials, &nsample, s, kSampleStride); break;
-    case 2: e = absmax_vec_launch<NORM, 2>(c, c.d, g, gref, gref2, cs.sample_partials, &nsample, s, kSampleStride); break;
-    default: e = absmax_vec_launch<NORM, 1>(c, c.d, g, gref, gref2, cs.sample_partials, &nsample, s, kSampleStride); break;
-  }
+  // the sample: every kSampleStride-th wavefront tile of every row
+  const uint64_t row_tiles = nvec / (kWave * kAbsmaxLoads);
+  const uint64_t sample_tiles = (row_tiles + kSampleStride - 1) / kSampleStride;
+  uint32_t nsample = div_up_u32(sample_tiles, kWavesPerBlock);
+  if (nsample > kAbsmaxMaxBlocks) nsample = kAbsmaxMaxBlocks;
+  hipLaunchKernelGGL((sample_stats_kernel<NORM>), dim3(nsample, c.M), dim3(kBlock), 0, s, GradRows{g, c.d},
+                     reinterpret_cast<const float4*>(gref), cs.sample_partials, cs.sample_sums, nvec, c.M);
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(absmax_finish_kernel, dim3(c.M), dim3(kBlock), 0, s, cs.sample_partials, nsample, c.M, cs.sample_max);
+  hipLaunchKernelGGL(sample_finish_kernel, dim3(c.M), dim3(kBlock), 0, s, cs.sample_partials, cs.sample_sums, nsample,
+                     c.M, (float)(sample_tiles * (kWave * kAbsmaxLoads * 4)), cs.sample_max, cs.select_ok);
   const uint32_t per_y = div_up_u32(nvec, (uint64_t)kBlock * kAbsmaxLoads);
   const uint32_t cap = kAbsmaxMaxBlocks - 1;
   nblocks = per_y < cap ? per_y : cap;
 #define TNG_SELECT(MC)                                                                                              \
   hipLaunchKernelGGL((absmax_select_kernel<NORM, MC>), dim3(nblocks, (c.M + MC - 1) / MC), dim3(kBlock), 0, s,      \
                      GradRows{g, c.d}, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), \
-                     partials, nvec, c.M, c.eps, cs.sample_max, cs.slots, cs.overflowed, c.k0, c.k1, iter)
+                     partials, nvec, c.M, c.eps, cs.sample_max, cs.select_ok, cs.slots, cs.overflowed, c.k0, c.k1, iter)
   switch (mc) {
     case 8: TNG_SELECT(8); break;
     case 4: TNG_SELECT(4); break;
@@ -1647,7 +1762,7 @@ hipError_t quantize_candidates_dispatch(const CodecShape& c, uint32_t iter, cons
 #define TNG_QC(MC)                                                                                                   \
   hipLaunchKernelGGL((quantize_candidates_kernel<NORM, MC>), dim3((uint32_t)tiles, (c.M + MC - 1) / MC), dim3(kBlock), 0, \
                      s, GradRows{g, c.d}, reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), \
-                     scales, cs.slots, codes, nvec, c.words, c.M, c.eps, c.k0, c.k1, iter, cs.use_slots)
+                     scales, cs.slots, codes, nvec, c.words, c.M, c.eps, c.k0, c.k1, iter, cs.use_slots, cs.select_ok)
   switch (mc) {
     case 16: TNG_QC(16); break;
     case 8: TNG_QC(8); break;

@@ -130,6 +130,21 @@ def test_mixture_of_tiles_and_degenerate_rows():
         _check(M, d, norm, src.contiguous(), ref, gref2, 7, "mixture")
 
 
+@pytest.mark.parametrize("dense_workers", [(17,), (0, 5, 9, 63), tuple(range(0, 64, 2))])
+def test_rows_that_the_sample_finds_too_dense(dense_workers):
+    # Gaussian residuals (one element in seven codes non-zero: more than a slot holds) on some workers, the
+    # ordinary data on the others.  One dense worker in 64 stays under the limit for unused slots, so its tiles
+    # go through the quantise pass's own ordinary path; half of them make the whole call fall back.
+    M, d = 64, 1 << 20
+    g, gref, gref2 = _inputs(M, d, seed=31)
+    gen = torch.Generator(device=DEV).manual_seed(32)
+    for m in dense_workers:
+        g[m] = gref + torch.randn(d, generator=gen, device=DEV)
+    codes, _ = _check(M, d, B.NORM_SUB, g.contiguous(), gref, gref2, 4, f"dense workers {dense_workers[:4]}")
+    nz = [np.count_nonzero(np.unpackbits(codes[m].view(np.uint8)).reshape(-1, 2).any(axis=1)) / d for m in (dense_workers[0], 1)]
+    assert nz[0] > 0.12 and nz[1] < 0.08, nz
+
+
 def test_same_codes_as_the_two_pass_coder_on_shorter_rows():
     # the same data cut into rows just below the path's threshold goes through the two-pass kernels: worker 0's
     # codes over the first d/2 coordinates must agree between the two (the draws depend on the element index only)
