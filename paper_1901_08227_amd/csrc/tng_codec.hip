@@ -314,8 +314,7 @@ template <int NORM, int MC>
 __global__ __launch_bounds__(kBlock) void absmax_vec_kernel(GradRows g, const float4* __restrict__ ref4,
                                                             const float4* __restrict__ ref24,
                                                             float* partials, uint64_t nvec,
-                                                            uint32_t M, float eps, const float* __restrict__ means,
-                                                            uint32_t tile_stride) {
+                                                            uint32_t M, float eps, const float* __restrict__ means) {
   constexpr int L = kAbsmaxLoads;
   constexpr uint64_t kWaveTile = (uint64_t)kWave * L;
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -324,9 +323,8 @@ __global__ __launch_bounds__(kBlock) void absmax_vec_kernel(GradRows g, const fl
 #pragma unroll
   for (int mm = 0; mm < MC; ++mm) mx[mm] = 0.f;
   const uint64_t ntiles = (nvec + kWaveTile - 1) / kWaveTile;  // wavefront tiles
-  // tile_stride > 1: the maximum over a sample of the row only (every tile_stride-th tile)
-  for (uint64_t tile = ((uint64_t)blockIdx.x * kWavesPerBlock + wave) * tile_stride; tile < ntiles;
-       tile += (uint64_t)gridDim.x * kWavesPerBlock * tile_stride) {
+  for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < ntiles;
+       tile += (uint64_t)gridDim.x * kWavesPerBlock) {
     RefTile<NORM> rt[L];
     uint64_t iv[L];
     const bool full = (tile + 1) * kWaveTile <= nvec;  // wave-uniform
@@ -626,7 +624,8 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_vec_kernel(
 // worker and wavefront tile, one 32-bit word each: the sign of the normalised value, the position within the
 // tile in the low 10 bits, and in between tau = |v| / u -- the scale up to which the element codes non-zero --
 // to 13 bits of its significand.  R^ is the maximum over a sample of the row taken beforehand (one tile in
-// kSampleStride); a row whose sample says that its candidates will not fit the slots is left to the ordinary path.  The quantise pass then reads the slots instead of g and compares the row's scale with
+// kSampleStride); a row whose sample says that its candidates will not fit the slots is left to the
+// ordinary path.  The quantise pass then reads the slots instead of g and compares the row's scale with
 // the entry: the level [u < fl(|v| fl(1 / R))] is 1 for every R below the bracket that the entry gives for tau
 // and 0 for every R above it (thresholds widened by what the roundings can move); the few elements whose
 // bracket contains R (three candidates in ten thousand) are fetched from g and coded from the value and its
@@ -1658,16 +1657,16 @@ inline bool vec_ok(uint64_t d, const void* a, const void* b, const void* c) {
 
 template <int NORM, int MC>
 hipError_t absmax_vec_launch(const CodecShape& c, uint64_t dv, const float* g, const float* gref, const float* gref2,
-                             float* partials, uint32_t* nblocks, hipStream_t s, uint32_t tile_stride = 1) {
+                             float* partials, uint32_t* nblocks, hipStream_t s) {
   const uint64_t nvec = dv / 4;
-  const uint32_t per_y = div_up_u32(nvec, (uint64_t)kBlock * kAbsmaxLoads * tile_stride);
+  const uint32_t per_y = div_up_u32(nvec, (uint64_t)kBlock * kAbsmaxLoads);
   const uint32_t cap = kAbsmaxMaxBlocks - 1;  // one row of partials is kept for the rows' scalar remainder
   const uint32_t gx = per_y < cap ? per_y : cap;
   *nblocks = gx;
   dim3 grid(gx, (c.M + MC - 1) / MC);
   hipLaunchKernelGGL((absmax_vec_kernel<NORM, MC>), grid, dim3(kBlock), 0, s, GradRows{g, c.d},
                      reinterpret_cast<const float4*>(gref), reinterpret_cast<const float4*>(gref2), partials, nvec,
-                     c.M, c.eps, c.means, tile_stride);
+                     c.M, c.eps, c.means);
   return hipGetLastError();
 }
 
